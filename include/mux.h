@@ -1,0 +1,167 @@
+/*
+ * mux.h - C ABI of the MI355X (gfx950) head-wise paged KV-cache library.
+ *
+ * The library implements the data path of MuxServe's unified KV cache
+ * (arXiv 2404.02015, Section 3.4 "Resource Manager" and its closing
+ * "Implementation" paragraph): the KV cache of every colocated LLM lives in ONE
+ * pool of small blocks, each block holding the K and V of one KV head for a fixed
+ * number of tokens; a memory manager hands blocks to the engines, the engines write
+ * new K/V into the blocks they were given and run attention over them, and the
+ * blocks go back to the pool when the request ends.
+ *
+ * Conventions for every call
+ *   - plain C linkage, no exceptions, no global state; the return value is a status
+ *     (MUX_OK or a negative mux_status_t) unless stated otherwise.
+ *   - "HOST" pointers are ordinary process memory, "DEVICE" pointers are HIP device
+ *     memory of the GPU that is current when the call is made.
+ *   - the caller owns the pool memory, block tables, Q/O tensors and workspaces; the
+ *     library owns only the ids and counters inside mux_pool_t.
+ *   - pool management calls are synchronous host calls, do no GPU work and may be
+ *     made from several host threads on the same pool.
+ *   - the three kernel calls only ENQUEUE work on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and return; they never synchronise and never
+ *     allocate device memory.  Calls for different models on different streams over
+ *     the same pool are safe concurrently because their blocks are disjoint.
+ *
+ * Pool layout (part of the ABI): block `id` starts at
+ *     kv_base + id * (2 * block_size * head_dim * elem_bytes)
+ * and holds the K tile [block_size][head_dim] row-major, followed by the V tile
+ * [block_size][head_dim] row-major, for one (model, layer, kv head, token span).
+ *
+ * Block tables: int32 [n_seqs][n_kv_heads][max_blocks]; entry [s][h][j] is the id of
+ * the block holding tokens j*block_size .. (j+1)*block_size-1 of kv head h of
+ * sequence s.  Entries past ceil(len/block_size) are never read.
+ */
+#ifndef MUX_H
+#define MUX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MUX_API __attribute__((visibility("default")))
+
+typedef struct mux_pool mux_pool_t; /* opaque, library-owned host object */
+
+typedef enum { MUX_BF16 = 0, MUX_FP32 = 1 } mux_dtype_t;
+
+typedef enum {
+    MUX_OK = 0,
+    MUX_ERR_INVALID = -1,     /* bad argument; unknown, foreign, repeated or already-free block id */
+    MUX_ERR_NOMEM = -2,       /* not enough free blocks; ALL-OR-NOTHING: nothing changed */
+    MUX_ERR_QUOTA = -3,       /* reserved for per-model token-block quotas (Section 3.3) */
+    MUX_ERR_HIP = -4,         /* a HIP runtime call or kernel launch failed */
+    MUX_ERR_UNSUPPORTED = -5  /* shape or dtype outside what the kernels are built for */
+} mux_status_t;
+
+#define MUX_MAX_MODELS 1024 /* model_id must lie in [0, MUX_MAX_MODELS) */
+
+/* ---------------------------------------------------------------------------------
+ * Unified KV space (Section 3.4: one space shared by all colocated LLMs, cut into
+ * head-wise blocks).
+ *
+ * mux_pool_create carves the caller's device buffer into `num_blocks` blocks and
+ * builds the free list.  kv_base: DEVICE, 16-byte aligned, at least
+ * num_blocks * 2 * block_size * head_dim * elem_bytes long (kv_bytes is checked); it
+ * stays owned by the caller and must outlive the pool.  init_free_order: HOST,
+ * nullable; if given it must be a permutation of [0, num_blocks) and is the order in
+ * which the fresh pool hands out ids (identity otherwise).  Supported: block_size
+ * 1..256, head_dim 64 or 128, dtype bf16 or fp32; anything else MUX_ERR_UNSUPPORTED.
+ * mux_pool_destroy frees host state only.
+ * ------------------------------------------------------------------------------- */
+MUX_API int mux_pool_create(mux_pool_t **out, void *kv_base, size_t kv_bytes, int64_t num_blocks,
+                    int32_t block_size, int32_t head_dim, mux_dtype_t dtype,
+                    const int32_t *init_free_order);
+MUX_API int mux_pool_destroy(mux_pool_t *pool);
+
+/* Counters: free blocks, blocks held by one model, bytes per block. Negative = error. */
+MUX_API int64_t mux_pool_num_free(const mux_pool_t *pool);
+MUX_API int64_t mux_pool_num_used(const mux_pool_t *pool, int32_t model_id);
+MUX_API int64_t mux_pool_block_bytes(const mux_pool_t *pool);
+
+/* ---------------------------------------------------------------------------------
+ * Block manager (Section 3.4, Implementation: an engine requests new cache blocks,
+ * keeps them from its prefill through its decoding steps, and they are released only
+ * when the request finishes).  The free list is a LIFO stack: mux_alloc_blocks pops n
+ * ids and returns them in pop order; mux_free_blocks pushes ids in the order given,
+ * so the last id freed is the first one handed out again.
+ *
+ * out_ids / ids: HOST arrays of n int32.  n == 0 is a no-op.
+ * mux_alloc_blocks: fewer than n free blocks -> MUX_ERR_NOMEM, pool and out_ids
+ * untouched.  mux_free_blocks: an id that is out of range, not currently held by
+ * `model_id`, or named twice in the call -> MUX_ERR_INVALID, nothing changed.
+ * ------------------------------------------------------------------------------- */
+MUX_API int mux_alloc_blocks(mux_pool_t *pool, int32_t model_id, int64_t n, int32_t *out_ids);
+MUX_API int mux_free_blocks(mux_pool_t *pool, int32_t model_id, int64_t n, const int32_t *ids);
+
+/* ---------------------------------------------------------------------------------
+ * KV append (Section 3.4, Implementation: the engine fills K/V into the blocks it
+ * was assigned).  For every new token t, sequence s = tok_seq[t], position
+ * p = tok_pos[t] and kv head h, the rows k_new[t][h][:] and v_new[t][h][:] are copied
+ * bit for bit to row p % block_size of block block_tables[s][h][p / block_size].
+ *
+ * k_new, v_new: DEVICE [n_tokens][n_kv_heads][head_dim] in the pool dtype, 16-byte
+ * aligned.  tok_seq, tok_pos: DEVICE int32 [n_tokens].  block_tables: DEVICE.
+ * A token whose sequence, position or block id is out of range is skipped by the
+ * kernel (nothing is written for it); no error can be reported for device-side data.
+ * Two tokens of one call must not name the same (sequence, position).
+ * ------------------------------------------------------------------------------- */
+MUX_API int mux_kv_append(mux_pool_t *pool, const void *k_new, const void *v_new, const int32_t *tok_seq,
+                  const int32_t *tok_pos, const int32_t *block_tables, int32_t n_tokens,
+                  int32_t n_seqs, int32_t n_kv_heads, int32_t max_blocks, void *stream);
+
+/* ---------------------------------------------------------------------------------
+ * Decode attention (Section 2.1: one new token per step attends to the cached K/V of
+ * all earlier tokens; Section 3.4: that cache is read through head-wise blocks).
+ * For sequence s and query head i (kv head h = i / (n_q_heads / n_kv_heads)):
+ *     out[s][i][:] = sum_j softmax_j(scale * <q[s][i], K_j>) V_j,  j < ctx_lens[s],
+ * with K_j, V_j row j % block_size of block block_tables[s][h][j / block_size].
+ * ctx_lens count the token appended in this step.  ctx_lens[s] == 0 gives zeros.
+ * Storage is the pool dtype; all arithmetic and accumulation are fp32, with one
+ * round-to-nearest-even to the storage type at the end.
+ *
+ * out, q: DEVICE [n_seqs][n_q_heads][head_dim], pool dtype, 16-byte aligned.
+ * ctx_lens: DEVICE int32 [n_seqs].  max_ctx_len: HOST upper bound on ctx_lens, used
+ * to size the grid and the split of long contexts without reading device memory
+ * (tokens beyond it are ignored).  workspace: DEVICE scratch of at least
+ * mux_decode_workspace_bytes(...) bytes, 16-byte aligned, private to this call until
+ * it has finished on `stream`; may be NULL when that function returns 0.
+ * ------------------------------------------------------------------------------- */
+MUX_API int mux_decode_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *block_tables,
+                    const int32_t *ctx_lens, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads,
+                    int32_t max_blocks, int32_t max_ctx_len, float scale, void *workspace,
+                    size_t workspace_bytes, void *stream);
+MUX_API size_t mux_decode_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs, int32_t n_q_heads,
+                                  int32_t n_kv_heads, int32_t max_ctx_len);
+
+/* ---------------------------------------------------------------------------------
+ * Chunked causal prefill attention (Section 2.1: prefill processes the prompt tokens
+ * in parallel).  Sequence s contributes the query rows cu_q_lens[s] .. cu_q_lens[s+1]-1
+ * of the packed q; row r of that chunk sits at absolute position p = q_start[s] + r and
+ * attends to keys 0 .. p.  The chunk's own K/V must already be in the pool
+ * (mux_kv_append first).  Arithmetic as for decode; for bf16 the softmax weights are
+ * rounded to bf16 before the P.V matrix product, accumulation stays fp32.
+ *
+ * out, q: DEVICE [total_q][n_q_heads][head_dim].  cu_q_lens: DEVICE int32 [n_seqs+1].
+ * q_start: DEVICE int32 [n_seqs], tokens cached before this chunk.  max_q_len,
+ * max_ctx_len: HOST upper bounds on the chunk lengths and on q_start + chunk length.
+ * workspace: reserved, may be NULL (mux_prefill_workspace_bytes returns 0).
+ * ------------------------------------------------------------------------------- */
+MUX_API int mux_prefill_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *cu_q_lens,
+                     const int32_t *q_start, const int32_t *block_tables, int32_t n_seqs,
+                     int32_t total_q, int32_t max_q_len, int32_t max_ctx_len, int32_t n_q_heads,
+                     int32_t n_kv_heads, int32_t max_blocks, float scale, void *workspace,
+                     size_t workspace_bytes, void *stream);
+MUX_API size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs, int32_t total_q,
+                                   int32_t n_q_heads, int32_t n_kv_heads);
+
+/* Human-readable name of a status code (static storage). */
+MUX_API const char *mux_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MUX_H */

@@ -1,0 +1,224 @@
+"""Thin ctypes binding of libmux.so: same names as include/mux.h, argument marshalling only.
+
+Tensors are torch tensors used purely as handles to device memory (`data_ptr()`); streams
+are torch.cuda.Stream objects (or None for the current stream).  Every step of the path runs
+inside the library's HIP kernels; there is no fallback: if libmux.so is missing or fails to
+load, importing a function from here raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+import torch  # must be imported before libmux.so so both share one HIP runtime
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmux.so")
+
+MUX_OK, MUX_ERR_INVALID, MUX_ERR_NOMEM, MUX_ERR_QUOTA, MUX_ERR_HIP, MUX_ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+MUX_BF16, MUX_FP32 = 0, 1
+
+EXPORTS = [
+    "mux_pool_create", "mux_pool_destroy", "mux_pool_num_free", "mux_pool_num_used", "mux_pool_block_bytes",
+    "mux_alloc_blocks", "mux_free_blocks", "mux_kv_append", "mux_decode_attn", "mux_decode_workspace_bytes",
+    "mux_prefill_attn", "mux_prefill_workspace_bytes", "mux_status_string",
+]
+
+
+class MuxError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__("%s: %s (%d)" % (what, status_string(status), status))
+        self.status = status
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libmux.so (built by paper_2404_02015_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("%s not found: run `python -m paper_2404_02015_amd.build` first" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+    L.mux_pool_create.argtypes = [C.POINTER(vp), vp, sz, i64, i32, i32, C.c_int, vp]
+    L.mux_pool_create.restype = C.c_int
+    L.mux_pool_destroy.argtypes = [vp]
+    L.mux_pool_num_free.argtypes = [vp]
+    L.mux_pool_num_free.restype = i64
+    L.mux_pool_num_used.argtypes = [vp, i32]
+    L.mux_pool_num_used.restype = i64
+    L.mux_pool_block_bytes.argtypes = [vp]
+    L.mux_pool_block_bytes.restype = i64
+    L.mux_alloc_blocks.argtypes = [vp, i32, i64, vp]
+    L.mux_free_blocks.argtypes = [vp, i32, i64, vp]
+    L.mux_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    L.mux_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, sz, vp]
+    L.mux_decode_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+    L.mux_decode_workspace_bytes.restype = sz
+    L.mux_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, sz, vp]
+    L.mux_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+    L.mux_prefill_workspace_bytes.restype = sz
+    L.mux_status_string.argtypes = [C.c_int]
+    L.mux_status_string.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return load().mux_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != MUX_OK:
+        raise MuxError(status, what)
+
+
+def _dev(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("expected %s, got %s" % (dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _device_pool(pool: "Pool") -> int:
+    if not pool.kv.is_cuda:
+        raise ValueError("this pool lives in host memory: kernels need a device pool")
+    return pool.handle
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _host_ids(ids) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(ids), dtype=np.int32)
+
+
+class Pool:
+    """Handle of a mux_pool_t plus the torch tensor that backs it (kept alive here)."""
+
+    def __init__(self, handle: int, kv: torch.Tensor, num_blocks: int, block_size: int, head_dim: int, dtype: int):
+        self.handle, self.kv = handle, kv
+        self.num_blocks, self.block_size, self.head_dim, self.dtype = num_blocks, block_size, head_dim, dtype
+        self.torch_dtype = torch.bfloat16 if dtype == MUX_BF16 else torch.float32
+        self.elem_bytes = 2 if dtype == MUX_BF16 else 4
+        self.block_bytes = 2 * block_size * head_dim * self.elem_bytes
+
+    def __del__(self):
+        try:
+            mux_pool_destroy(self)
+        except Exception:
+            pass
+
+
+def mux_pool_create(kv: torch.Tensor, num_blocks: int, block_size: int, head_dim: int, dtype: int = MUX_BF16,
+                    init_free_order=None) -> Pool:
+    """kv: a contiguous device tensor (any dtype) whose storage becomes the unified KV space.
+    (A host tensor is accepted too: the block manager never touches the memory, only the
+    kernel calls do, and those insist on device memory.)"""
+    if not kv.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    h = C.c_void_p()
+    order = None if init_free_order is None else _host_ids(init_free_order)
+    if order is not None and order.size != num_blocks:
+        raise MuxError(MUX_ERR_INVALID, "mux_pool_create")
+    rc = load().mux_pool_create(C.byref(h), kv.data_ptr(), kv.numel() * kv.element_size(), num_blocks, block_size, head_dim,
+                                dtype, None if order is None else order.ctypes.data)
+    _check(rc, "mux_pool_create")
+    return Pool(h.value, kv, num_blocks, block_size, head_dim, dtype)
+
+
+def mux_pool_destroy(pool: Pool) -> None:
+    if pool.handle:
+        load().mux_pool_destroy(pool.handle)
+        pool.handle = None
+
+
+def mux_pool_num_free(pool: Pool) -> int:
+    return load().mux_pool_num_free(pool.handle)
+
+
+def mux_pool_num_used(pool: Pool, model_id: int) -> int:
+    return load().mux_pool_num_used(pool.handle, model_id)
+
+
+def mux_alloc_blocks_status(pool: Pool, model_id: int, n: int, out: Optional[np.ndarray] = None):
+    """Returns (status, ids); ids is the filled array when status == MUX_OK, else None."""
+    if out is None:
+        out = np.full(max(n, 0), -7, dtype=np.int32)
+    assert out.dtype == np.int32 and out.size >= n and out.flags.c_contiguous
+    rc = load().mux_alloc_blocks(pool.handle, model_id, n, out.ctypes.data)
+    return rc, (out if rc == MUX_OK else None)
+
+
+def mux_alloc_blocks(pool: Pool, model_id: int, n: int, out: Optional[np.ndarray] = None) -> np.ndarray:
+    rc, ids = mux_alloc_blocks_status(pool, model_id, n, out)
+    _check(rc, "mux_alloc_blocks")
+    return ids
+
+
+def mux_free_blocks_status(pool: Pool, model_id: int, ids) -> int:
+    ids = _host_ids(ids)
+    return load().mux_free_blocks(pool.handle, model_id, ids.size, ids.ctypes.data)
+
+
+def mux_free_blocks(pool: Pool, model_id: int, ids) -> None:
+    _check(mux_free_blocks_status(pool, model_id, ids), "mux_free_blocks")
+
+
+def mux_kv_append(pool: Pool, k_new: torch.Tensor, v_new: torch.Tensor, tok_seq: torch.Tensor, tok_pos: torch.Tensor,
+                  block_tables: torch.Tensor, stream=None) -> None:
+    n_tokens, n_kv, d = k_new.shape
+    n_seqs, n_kv2, max_blocks = block_tables.shape
+    if d != pool.head_dim or n_kv != n_kv2 or v_new.shape != k_new.shape or tok_seq.numel() != n_tokens or tok_pos.numel() != n_tokens:
+        raise MuxError(MUX_ERR_INVALID, "mux_kv_append")
+    rc = load().mux_kv_append(_device_pool(pool), _dev(k_new, pool.torch_dtype), _dev(v_new, pool.torch_dtype),
+                              _dev(tok_seq, torch.int32), _dev(tok_pos, torch.int32), _dev(block_tables, torch.int32),
+                              n_tokens, n_seqs, n_kv, max_blocks, _stream(stream))
+    _check(rc, "mux_kv_append")
+
+
+def mux_decode_workspace_bytes(pool: Pool, n_seqs: int, n_q_heads: int, n_kv_heads: int, max_ctx_len: int) -> int:
+    return load().mux_decode_workspace_bytes(pool.handle, n_seqs, n_q_heads, n_kv_heads, max_ctx_len)
+
+
+def mux_decode_attn(pool: Pool, out: torch.Tensor, q: torch.Tensor, block_tables: torch.Tensor, ctx_lens: torch.Tensor,
+                    max_ctx_len: int, scale: float, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    n_seqs, n_q, d = q.shape
+    n_seqs2, n_kv, max_blocks = block_tables.shape
+    if d != pool.head_dim or n_seqs2 != n_seqs or out.shape != q.shape or ctx_lens.numel() != n_seqs:
+        raise MuxError(MUX_ERR_INVALID, "mux_decode_attn")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().mux_decode_attn(_device_pool(pool), _dev(out, pool.torch_dtype), _dev(q, pool.torch_dtype),
+                                _dev(block_tables, torch.int32), _dev(ctx_lens, torch.int32), n_seqs, n_q, n_kv,
+                                max_blocks, max_ctx_len, scale, _dev(workspace), ws_bytes, _stream(stream))
+    _check(rc, "mux_decode_attn")
+
+
+def mux_prefill_workspace_bytes(pool: Pool, n_seqs: int, total_q: int, n_q_heads: int, n_kv_heads: int) -> int:
+    return load().mux_prefill_workspace_bytes(pool.handle, n_seqs, total_q, n_q_heads, n_kv_heads)
+
+
+def mux_prefill_attn(pool: Pool, out: torch.Tensor, q: torch.Tensor, cu_q_lens: torch.Tensor, q_start: torch.Tensor,
+                     block_tables: torch.Tensor, max_q_len: int, max_ctx_len: int, scale: float,
+                     workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    total_q, n_q, d = q.shape
+    n_seqs, n_kv, max_blocks = block_tables.shape
+    if d != pool.head_dim or out.shape != q.shape or cu_q_lens.numel() != n_seqs + 1 or q_start.numel() != n_seqs:
+        raise MuxError(MUX_ERR_INVALID, "mux_prefill_attn")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().mux_prefill_attn(_device_pool(pool), _dev(out, pool.torch_dtype), _dev(q, pool.torch_dtype),
+                                 _dev(cu_q_lens, torch.int32), _dev(q_start, torch.int32),
+                                 _dev(block_tables, torch.int32), n_seqs, total_q, max_q_len, max_ctx_len, n_q, n_kv,
+                                 max_blocks, scale, _dev(workspace), ws_bytes, _stream(stream))
+    _check(rc, "mux_prefill_attn")

@@ -1,0 +1,504 @@
+// Decode attention over the unified head-wise paged KV pool (gfx950, wave64).
+//
+// MuxServe, Section 2.1 (each decoding step attends to the cached K/V of every earlier
+// token) and Section 3.4 (that cache is a pool of blocks, each holding one KV head for a
+// few tokens).  The result is plain softmax(scale * q K^T) V per (sequence, query head).
+//
+// Shape of the work: for multi-head models every K/V byte is used once, about one flop per
+// byte, so the kernel is a gather at HBM speed.  Design:
+//   - a workgroup of 4 waves owns one (sequence, kv head, span of the context); long
+//     contexts are split into spans so that every workgroup has a bounded, similar amount
+//     of bytes to read and the grid is far larger than the 256 CUs;
+//   - a wave reads whole blocks: each load instruction is 64 lanes x 16 bytes = 1 KiB of
+//     contiguous tile, i.e. RPL = 1024 / row_bytes full rows; a 16-token block of 128 bf16
+//     is 4 loads of K and 4 of V, all issued before any of them is used, and the next
+//     block's 8 loads are issued before the current block is consumed;
+//   - the lanes that share a row reduce their partial dot products with DPP row
+//     operations; each group of lanes that owns a row slot keeps its own running
+//     max / sum / accumulator (online softmax), so nothing crosses rows inside the loop;
+//   - the block ids of a wave are fetched with one coalesced load up front and broadcast
+//     with readlane, so block addresses are scalar;
+//   - the row slots of a wave are merged with shuffles, the 4 waves through LDS, and spans
+//     through a small fp32 workspace and a combine kernel.
+// All arithmetic is fp32; the output is rounded once to the storage type.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <type_traits>
+
+#include "mux_internal.h"
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
+constexpr int kMaxWaveBlocks = 64;              // block ids a wave keeps in one register
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kNegBig = -3.0e38f;             // "no score seen yet"; finite so that differences stay finite
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over each group of LPR consecutive lanes; every lane of the group gets the sum.
+template <int LPR>
+__device__ __forceinline__ float row_sum(float x)
+{
+    x += dpp_move<0xB1>(x);                      // quad_perm [1,0,3,2]
+    x += dpp_move<0x4E>(x);                      // quad_perm [2,3,0,1]
+    if (LPR >= 8) x += dpp_move<0x141>(x);       // row_half_mirror
+    if (LPR >= 16) x += dpp_move<0x140>(x);      // row_mirror
+    if (LPR >= 32) x += __shfl_xor(x, 16);
+    return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <bool BF16>
+struct Piece {  // the 16 bytes one lane loads
+    static constexpr int N = BF16 ? 8 : 4;
+    static __device__ __forceinline__ void widen(const u32x4 v, float (&x)[N])
+    {
+        if constexpr (BF16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[2 * i] = __uint_as_float(v[i] << 16);
+                x[2 * i + 1] = __uint_as_float(v[i] & 0xffff0000u);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = __uint_as_float(v[i]);
+        }
+    }
+};
+
+__device__ __forceinline__ unsigned short to_bf16_rne(float f)
+{
+    unsigned u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<unsigned short>(u >> 16);
+}
+
+template <bool BF16>
+__device__ __forceinline__ void store_out(void *out, long long idx, float v)
+{
+    if constexpr (BF16)
+        static_cast<unsigned short *>(out)[idx] = to_bf16_rne(v);
+    else
+        static_cast<float *>(out)[idx] = v;
+}
+
+struct DecodeArgs {
+    const char *kv_base;
+    long long block_bytes;
+    int num_blocks;
+    int block_size;
+    void *out;
+    const void *q;
+    const int *tables;
+    const int *ctx_lens;
+    int n_seqs, n_q_heads, n_kv_heads, max_blocks, max_ctx_len;
+    float scale_log2e;
+    int span_blocks;  // blocks per workgroup span
+    int n_splits;
+    int n_passes;
+    float *ws_acc;  // [n_seqs][n_q_heads][n_splits][D]
+    float *ws_ml;   // [n_seqs][n_q_heads][n_splits][2]
+};
+
+// BF16: storage type; D: head size; BS: tokens per block at compile time (0 = run time);
+// GT: query heads of one KV group handled together.
+template <bool BF16, int D, int BS, int GT>
+__global__ __launch_bounds__(kThreads) void decode_attn_kernel(const DecodeArgs a)
+{
+    constexpr int EB = BF16 ? 2 : 4;
+    constexpr int EPL = 16 / EB;          // elements per lane per load
+    constexpr int LPR = D / EPL;          // lanes per row
+    constexpr int RPL = 64 / LPR;         // rows per load instruction
+    static_assert(LPR >= 4 && LPR <= 32, "unsupported head size");
+    constexpr bool kFixed = BS > 0;
+    static_assert(!kFixed || BS % RPL == 0, "fixed block size must hold whole load groups");
+    constexpr int NG = kFixed ? BS / RPL : 1;  // loads per tile handled at once
+
+    const int B = kFixed ? BS : a.block_size;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps the block loop scalar
+    const int rg = lane / LPR;            // row slot of this lane inside a load
+    const int c0 = (lane % LPR) * EPL;    // first head dimension of this lane
+
+    // blockIdx -> (sequence, kv head, pass, split), split fastest
+    int w = blockIdx.x;
+    const int split = w % a.n_splits;  w /= a.n_splits;
+    const int pass = w % a.n_passes;   w /= a.n_passes;
+    const int kvh = w % a.n_kv_heads;
+    const int s = w / a.n_kv_heads;
+
+    int L = a.ctx_lens[s];
+    L = min(max(L, 0), a.max_ctx_len);
+    const int n_blk_seq = (L + B - 1) / B;
+    const int blk_lo = split * a.span_blocks;
+    if (a.n_splits > 1 && blk_lo >= n_blk_seq) return;  // nothing of this sequence falls in the span
+    const int blk_hi = min(blk_lo + a.span_blocks, n_blk_seq);
+
+    const int group = a.n_q_heads / a.n_kv_heads;
+    const int head0 = kvh * group + pass * GT;  // first query head of this pass
+
+    // q rows, pre-multiplied by scale * log2(e): scores live in the exp2 domain
+    float qf[GT][EPL];
+#pragma unroll
+    for (int h = 0; h < GT; ++h) {
+        const int qh = min(head0 + h, kvh * group + group - 1);
+        const u32x4 raw = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.q) +
+                                                           ((static_cast<long long>(s) * a.n_q_heads + qh) * D + c0) * EB);
+        Piece<BF16>::widen(raw, qf[h]);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) qf[h][e] *= a.scale_log2e;
+    }
+
+    float m[GT], l[GT], acc[GT][EPL];
+#pragma unroll
+    for (int h = 0; h < GT; ++h) {
+        m[h] = kNegBig;
+        l[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
+    }
+
+    // Block ids of this wave: block blk_lo + wave + kWaves * j sits in lane j.
+    const int n_mine = blk_hi - blk_lo > wave ? (blk_hi - blk_lo - wave + kWaves - 1) / kWaves : 0;
+    const int *row = a.tables + (static_cast<long long>(s) * a.n_kv_heads + kvh) * a.max_blocks;
+    int my_ids = 0;
+    if (lane < n_mine) my_ids = row[blk_lo + wave + kWaves * lane];
+
+    auto tile_ptr = [&](int j) -> const char * {
+        int id = __builtin_amdgcn_readlane(my_ids, j);
+        id = min(max(id, 0), a.num_blocks - 1);  // a corrupt table must not leave the pool
+        return a.kv_base + static_cast<long long>(id) * a.block_bytes;
+    };
+
+    // Fold NG row groups (K pieces k[], V pieces v[]) into the running softmax state.
+    // Rows whose index (g * RPL + rg) is >= n_valid are ignored when MASKED.
+    auto fold = [&](const u32x4 (&k)[NG], const u32x4 (&v)[NG], auto masked_tag, int n_valid) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        float p[GT][NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            float kf[EPL];
+            Piece<BF16>::widen(k[g], kf);
+            const bool ok = !MASKED || (g * RPL + rg < n_valid);
+#pragma unroll
+            for (int h = 0; h < GT; ++h) {
+                float dot = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) dot = __builtin_fmaf(qf[h][e], kf[e], dot);
+                dot = row_sum<LPR>(dot);
+                p[h][g] = ok ? dot : kNegBig;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < GT; ++h) {
+            float mx = p[h][0];
+#pragma unroll
+            for (int g = 1; g < NG; ++g) mx = fmaxf(mx, p[h][g]);
+            const float m_new = fmaxf(m[h], mx);
+            const float alpha = fast_exp2(m[h] - m_new);
+            float sum = 0.f;
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                float e = fast_exp2(p[h][g] - m_new);
+                if (MASKED && !(g * RPL + rg < n_valid)) e = 0.f;
+                p[h][g] = e;
+                sum += e;
+            }
+            l[h] = l[h] * alpha + sum;
+            m[h] = m_new;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[h][e] *= alpha;
+        }
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            float vf[EPL];
+            Piece<BF16>::widen(v[g], vf);
+            if (MASKED && !(g * RPL + rg < n_valid)) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) vf[e] = 0.f;  // stale bytes may be NaN
+            }
+#pragma unroll
+            for (int h = 0; h < GT; ++h)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[h][e] = __builtin_fmaf(p[h][g], vf[e], acc[h][e]);
+        }
+    };
+
+    if constexpr (kFixed) {
+        constexpr int kTileBytes = BS * D * EB;
+        auto load_tile = [&](int j, u32x4 (&k)[NG], u32x4 (&v)[NG]) {
+            const char *t = tile_ptr(j) + static_cast<unsigned>(lane * 16);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) k[g] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(t + g * 1024));
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+                v[g] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(t + kTileBytes + g * 1024));
+        };
+        // Every block but the wave's last one is full, so only the last may need masking.
+        auto consume_full = [&](const u32x4 (&k)[NG], const u32x4 (&v)[NG]) { fold(k, v, std::false_type{}, BS); };
+        auto consume_last = [&](int j, const u32x4 (&k)[NG], const u32x4 (&v)[NG]) {
+            const int n_valid = L - (blk_lo + wave + kWaves * j) * BS;  // wave-uniform, >= 1
+            if (n_valid >= BS)
+                fold(k, v, std::false_type{}, BS);
+            else
+                fold(k, v, std::true_type{}, n_valid);
+        };
+        // Two register sets alternate; the loads of the next block are always issued before
+        // the current block is consumed, and unconditionally inside the loop so that the wait
+        // counters only cover the block being consumed.
+        if (n_mine > 0) {
+            u32x4 ka[NG], va[NG], kb[NG], vb[NG];
+            load_tile(0, ka, va);
+            int j = 0;
+            for (; j + 2 < n_mine; j += 2) {
+                load_tile(j + 1, kb, vb);
+                consume_full(ka, va);
+                load_tile(j + 2, ka, va);
+                consume_full(kb, vb);
+            }
+            if (j + 1 < n_mine) {
+                load_tile(j + 1, kb, vb);
+                consume_full(ka, va);
+                consume_last(j + 1, kb, vb);
+            } else {
+                consume_last(j, ka, va);
+            }
+        }
+    } else {
+        const long long tile_bytes = static_cast<long long>(B) * D * EB;
+        for (int j = 0; j < n_mine; ++j) {
+            const char *t = tile_ptr(j);
+            const int first_tok = (blk_lo + wave + kWaves * j) * B;
+            const int rows_here = min(B, L - first_tok);
+            for (int r0 = 0; r0 < rows_here; r0 += RPL) {
+                u32x4 k[1], v[1];
+                k[0] = u32x4{0, 0, 0, 0};
+                v[0] = u32x4{0, 0, 0, 0};
+                if (r0 + rg < rows_here) {  // never read past the tile
+                    const char *src = t + static_cast<long long>(r0) * (D * EB) + lane * 16;
+                    k[0] = *reinterpret_cast<const u32x4 *>(src);
+                    v[0] = *reinterpret_cast<const u32x4 *>(src + tile_bytes);
+                }
+                fold(k, v, std::true_type{}, rows_here - r0);
+            }
+        }
+    }
+
+    // Merge the RPL row slots of the wave: afterwards every lane holds the wave's state.
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+        for (int h = 0; h < GT; ++h) {
+            const float mo = __shfl_xor(m[h], off);
+            const float lo = __shfl_xor(l[h], off);
+            const float mn = fmaxf(m[h], mo);
+            const float wa = fast_exp2(m[h] - mn), wb = fast_exp2(mo - mn);
+            l[h] = l[h] * wa + lo * wb;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[h][e] = acc[h][e] * wa + __shfl_xor(acc[h][e], off) * wb;
+            m[h] = mn;
+        }
+    }
+
+    __shared__ float sm_acc[kWaves][GT][D];
+    __shared__ float sm_m[kWaves][GT], sm_l[kWaves][GT];
+    if (lane < LPR) {
+#pragma unroll
+        for (int h = 0; h < GT; ++h) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) sm_acc[wave][h][c0 + e] = acc[h][e];
+            if (lane == 0) {
+                sm_m[wave][h] = m[h];
+                sm_l[wave][h] = l[h];
+            }
+        }
+    }
+    __syncthreads();
+
+    for (int idx = tid; idx < GT * D; idx += kThreads) {
+        const int h = idx / D, c = idx % D;
+        if (pass * GT + h >= group) continue;
+        float mm = sm_m[0][h];
+#pragma unroll
+        for (int k = 1; k < kWaves; ++k) mm = fmaxf(mm, sm_m[k][h]);
+        float o = 0.f, ll = 0.f;
+#pragma unroll
+        for (int k = 0; k < kWaves; ++k) {
+            const float wk = fast_exp2(sm_m[k][h] - mm);
+            o += sm_acc[k][h][c] * wk;
+            ll += sm_l[k][h] * wk;
+        }
+        const long long qrow = static_cast<long long>(s) * a.n_q_heads + head0 + h;
+        if (a.n_splits == 1) {
+            store_out<BF16>(a.out, qrow * D + c, ll > 0.f ? o / ll : 0.f);
+        } else {
+            const long long part = qrow * a.n_splits + split;
+            a.ws_acc[part * D + c] = o;
+            if (c == 0) {
+                a.ws_ml[part * 2] = mm;
+                a.ws_ml[part * 2 + 1] = ll;
+            }
+        }
+    }
+}
+
+// Merge the spans of one (sequence, query head): thread c owns head dimension c.
+template <bool BF16, int D>
+__global__ __launch_bounds__(D) void decode_combine_kernel(const DecodeArgs a)
+{
+    const int qrow = blockIdx.x;  // s * n_q_heads + head
+    const int s = qrow / a.n_q_heads;
+    const int c = threadIdx.x;
+    const int B = a.block_size;
+    int L = a.ctx_lens[s];
+    L = min(max(L, 0), a.max_ctx_len);
+    const int n_blk_seq = (L + B - 1) / B;
+    const int n_parts = min((n_blk_seq + a.span_blocks - 1) / a.span_blocks, a.n_splits);
+    const float *ml = a.ws_ml + static_cast<long long>(qrow) * a.n_splits * 2;
+    const float *pa = a.ws_acc + static_cast<long long>(qrow) * a.n_splits * D;
+    float mm = kNegBig;
+    for (int i = 0; i < n_parts; ++i) mm = fmaxf(mm, ml[2 * i]);
+    float o = 0.f, ll = 0.f;
+    for (int i = 0; i < n_parts; ++i) {
+        const float wi = fast_exp2(ml[2 * i] - mm);
+        o += pa[static_cast<long long>(i) * D + c] * wi;
+        ll += ml[2 * i + 1] * wi;
+    }
+    store_out<BF16>(a.out, static_cast<long long>(qrow) * D + c, ll > 0.f ? o / ll : 0.f);
+}
+
+template <bool BF16, int D, int BS, int GT>
+void launch_one(const DecodeArgs &a, unsigned grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((decode_attn_kernel<BF16, D, BS, GT>), dim3(grid), dim3(kThreads), 0, st, a);
+}
+
+template <bool BF16, int D, int BS>
+void launch_by_heads(int gt, const DecodeArgs &a, unsigned grid, hipStream_t st)
+{
+    switch (gt) {
+        case 1: launch_one<BF16, D, BS, 1>(a, grid, st); break;
+        case 2: launch_one<BF16, D, BS, 2>(a, grid, st); break;
+        case 4: launch_one<BF16, D, BS, 4>(a, grid, st); break;
+        default: launch_one<BF16, D, BS, 8>(a, grid, st); break;
+    }
+}
+
+template <bool BF16, int D>
+void launch_by_block(int block_size, int gt, const DecodeArgs &a, unsigned grid, hipStream_t st)
+{
+    if (block_size == 16)
+        launch_by_heads<BF16, D, 16>(gt, a, grid, st);
+    else
+        launch_by_heads<BF16, D, 0>(gt, a, grid, st);
+}
+
+int env_int(const char *name, int fallback)
+{
+    const char *v = std::getenv(name);
+    return v && *v ? std::atoi(v) : fallback;
+}
+
+}  // namespace
+
+mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads,
+                                int32_t max_ctx_len)
+{
+    mux_decode_plan plan{};
+    const int group = n_q_heads / n_kv_heads;
+    int gt = 1;
+    while (gt < group && gt < 8) gt *= 2;
+    plan.heads_per_pass = gt;
+    plan.n_passes = (group + gt - 1) / gt;
+
+    const int B = pool->block_size;
+    const long long ctx_blocks = (static_cast<long long>(max_ctx_len) + B - 1) / B;
+    // Span: about 512 tokens, in whole blocks, a multiple of the wave count, at most what a
+    // wave can index from one register; shortened while the grid would leave CUs idle.
+    static const int forced = env_int("MUX_DECODE_SPAN_BLOCKS", 0);
+    long long span = forced > 0 ? forced : (512 + B - 1) / B;
+    span = (span + kWaves - 1) / kWaves * kWaves;
+    if (span > kWaves * kMaxWaveBlocks) span = kWaves * kMaxWaveBlocks;
+    if (forced <= 0) {
+        const long long items = static_cast<long long>(n_seqs) * n_kv_heads * plan.n_passes;
+        while (span > kWaves && items * ((ctx_blocks + span - 1) / span) < 2048) span = (span / 2 + kWaves - 1) / kWaves * kWaves;
+    }
+    plan.span_tokens = static_cast<int32_t>(span * B);
+    plan.n_splits = static_cast<int32_t>((ctx_blocks + span - 1) / span);
+    if (plan.n_splits < 1) plan.n_splits = 1;
+    plan.workspace_bytes =
+        plan.n_splits > 1 ? static_cast<size_t>(n_seqs) * n_q_heads * plan.n_splits * (pool->head_dim + 2) * sizeof(float) : 0;
+    return plan;
+}
+
+int mux_launch_decode_attn(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q,
+                           const int32_t *tables, const int32_t *ctx_lens, int32_t n_seqs, int32_t n_q_heads,
+                           int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len, float scale, void *workspace,
+                           void *stream)
+{
+    DecodeArgs a{};
+    a.kv_base = pool->kv_base;
+    a.block_bytes = pool->block_bytes;
+    a.num_blocks = static_cast<int>(pool->num_blocks);
+    a.block_size = pool->block_size;
+    a.out = out;
+    a.q = q;
+    a.tables = tables;
+    a.ctx_lens = ctx_lens;
+    a.n_seqs = n_seqs;
+    a.n_q_heads = n_q_heads;
+    a.n_kv_heads = n_kv_heads;
+    a.max_blocks = max_blocks;
+    a.max_ctx_len = max_ctx_len;
+    a.scale_log2e = scale * kLog2e;
+    a.span_blocks = plan.span_tokens / pool->block_size;
+    a.n_splits = plan.n_splits;
+    a.n_passes = plan.n_passes;
+    if (plan.n_splits > 1) {
+        a.ws_acc = static_cast<float *>(workspace);
+        a.ws_ml = a.ws_acc + static_cast<size_t>(n_seqs) * n_q_heads * plan.n_splits * pool->head_dim;
+    }
+    const long long grid = static_cast<long long>(n_seqs) * n_kv_heads * plan.n_passes * plan.n_splits;
+    if (grid > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool bf16 = pool->dtype == MUX_BF16;
+    const int gt = plan.heads_per_pass;
+    const unsigned g = static_cast<unsigned>(grid);
+    if (bf16 && pool->head_dim == 128)
+        launch_by_block<true, 128>(pool->block_size, gt, a, g, st);
+    else if (bf16 && pool->head_dim == 64)
+        launch_by_block<true, 64>(pool->block_size, gt, a, g, st);
+    else if (!bf16 && pool->head_dim == 128)
+        launch_by_block<false, 128>(pool->block_size, gt, a, g, st);
+    else if (!bf16 && pool->head_dim == 64)
+        launch_by_block<false, 64>(pool->block_size, gt, a, g, st);
+    else
+        return MUX_ERR_UNSUPPORTED;
+    if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
+    if (plan.n_splits > 1) {
+        const unsigned rows = static_cast<unsigned>(n_seqs) * static_cast<unsigned>(n_q_heads);
+        if (pool->head_dim == 128) {
+            if (bf16)
+                hipLaunchKernelGGL((decode_combine_kernel<true, 128>), dim3(rows), dim3(128), 0, st, a);
+            else
+                hipLaunchKernelGGL((decode_combine_kernel<false, 128>), dim3(rows), dim3(128), 0, st, a);
+        } else {
+            if (bf16)
+                hipLaunchKernelGGL((decode_combine_kernel<true, 64>), dim3(rows), dim3(64), 0, st, a);
+            else
+                hipLaunchKernelGGL((decode_combine_kernel<false, 64>), dim3(rows), dim3(64), 0, st, a);
+        }
+        if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
+    }
+    return MUX_OK;
+}

@@ -1,0 +1,53 @@
+// Internal definitions shared by the translation units of the library (not part of the ABI).
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "mux.h"
+
+struct mux_pool {
+    // geometry of the unified KV space
+    char *kv_base = nullptr;      // device memory, caller-owned
+    int64_t num_blocks = 0;
+    int32_t block_size = 0;       // tokens per block
+    int32_t head_dim = 0;
+    mux_dtype_t dtype = MUX_BF16;
+    int32_t elem_bytes = 2;
+    int64_t block_bytes = 0;      // 2 * block_size * head_dim * elem_bytes (K tile then V tile)
+
+    // block manager state, guarded by `lock`
+    mutable std::mutex lock;
+    std::vector<int32_t> free_ids;          // LIFO: back() is handed out next
+    std::vector<int32_t> holder;            // per block: model id, kFree, or kPending during a free call
+    std::vector<int64_t> used_by_model;     // MUX_MAX_MODELS counters
+
+    static constexpr int32_t kFree = -1;
+    static constexpr int32_t kPending = -2;
+};
+
+// Kernel launchers (defined in the .hip files).  They validate nothing; the C entry
+// points in mux_api.cpp check every host-visible argument first.
+int mux_launch_kv_append(const mux_pool *pool, const void *k_new, const void *v_new, const int32_t *tok_seq,
+                         const int32_t *tok_pos, const int32_t *tables, int32_t n_tokens, int32_t n_seqs,
+                         int32_t n_kv_heads, int32_t max_blocks, void *stream);
+
+struct mux_decode_plan {
+    int32_t span_tokens;   // tokens of one sequence handled by one workgroup
+    int32_t n_splits;      // ceil(max_ctx_len / span_tokens)
+    int32_t heads_per_pass;  // query heads of one KV group handled together by a workgroup
+    int32_t n_passes;        // ceil(group / heads_per_pass)
+    size_t workspace_bytes;  // 0 when n_splits == 1
+};
+mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads,
+                                int32_t max_ctx_len);
+int mux_launch_decode_attn(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q,
+                           const int32_t *tables, const int32_t *ctx_lens, int32_t n_seqs, int32_t n_q_heads,
+                           int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len, float scale,
+                           void *workspace, void *stream);
+
+int mux_launch_prefill_attn(const mux_pool *pool, void *out, const void *q, const int32_t *cu_q_lens,
+                            const int32_t *q_start, const int32_t *tables, int32_t n_seqs, int32_t total_q,
+                            int32_t max_q_len, int32_t max_ctx_len, int32_t n_q_heads, int32_t n_kv_heads,
+                            int32_t max_blocks, float scale, void *stream);

@@ -1,0 +1,198 @@
+"""Test harness: drives the GPU library and the CPU oracle in lockstep on the same seeded
+inputs.  The two sides never exchange data: each keeps its own pool, block manager and
+tables; the harness compares what they return.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+from oracle import mux_oracle as orc
+from paper_2404_02015_amd import binding as mx
+from paper_2404_02015_amd import workloads as wl
+
+SENTINEL16 = 0x7FC1  # a bf16 NaN pattern; as fp32 pairs (0x7FC17FC1) it is a NaN too
+
+
+def torch_dtype(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def to_oracle(t: torch.Tensor) -> np.ndarray:
+    """Device or host tensor -> the numpy form the oracle takes (bf16 as uint16 bits)."""
+    return wl.as_bits(t.detach().cpu())
+
+
+class Lockstep:
+    """One library pool and one oracle pool with the same geometry and initial order.
+    Every block-manager call goes to both and must return the same status and ids."""
+
+    def __init__(self, num_blocks: int, block_size: int, head_dim: int, dtype: str = "bf16",
+                 order: Optional[np.ndarray] = None, device: str = "cuda", sentinel: bool = True):
+        self.num_blocks, self.block_size, self.head_dim, self.dtype = num_blocks, block_size, head_dim, dtype
+        self.elem = 2 if dtype == "bf16" else 4
+        self.block_bytes = 2 * block_size * head_dim * self.elem
+        n16 = num_blocks * self.block_bytes // 2
+        self.kv = torch.empty(n16, dtype=torch.int16, device=device)
+        if sentinel:
+            self.kv.fill_(SENTINEL16)
+        self.lib = mx.mux_pool_create(self.kv, num_blocks, block_size, head_dim,
+                                      mx.MUX_BF16 if dtype == "bf16" else mx.MUX_FP32, order)
+        self.orc = orc.OraclePool(num_blocks, block_size, head_dim, orc.BF16 if dtype == "bf16" else orc.FP32, order)
+        self.device = device
+
+    # -- block manager, both sides ----------------------------------------------------
+    def alloc(self, model_id: int, n: int) -> np.ndarray:
+        rc_l, ids_l = mx.mux_alloc_blocks_status(self.lib, model_id, n)
+        rc_o, ids_o = self.orc.alloc_status(model_id, n)
+        assert rc_l == rc_o, (rc_l, rc_o)
+        if rc_l != 0:
+            raise mx.MuxError(rc_l, "mux_alloc_blocks")
+        assert np.array_equal(ids_l, ids_o), "block ids differ between library and oracle"
+        return ids_l
+
+    def alloc_or_none(self, model_id: int, n: int):
+        try:
+            return self.alloc(model_id, n)
+        except mx.MuxError as e:
+            assert e.status == mx.MUX_ERR_NOMEM
+            return None
+
+    def free(self, model_id: int, ids) -> None:
+        rc_l = mx.mux_free_blocks_status(self.lib, model_id, ids)
+        rc_o = self.orc.free_status(model_id, ids)
+        assert rc_l == rc_o == 0, (rc_l, rc_o)
+
+    def check_counters(self, n_models: int = 8) -> None:
+        assert mx.mux_pool_num_free(self.lib) == self.orc.num_free()
+        for m in range(n_models):
+            assert mx.mux_pool_num_used(self.lib, m) == self.orc.num_used(m)
+
+    def pool_image(self) -> np.ndarray:
+        """The device pool as uint16 [num_blocks][2][block_size][row_u16]."""
+        row16 = self.head_dim * self.elem // 2
+        return self.kv.cpu().numpy().view(np.uint16).reshape(self.num_blocks, 2, self.block_size, row16)
+
+
+@dataclass
+class JobState:
+    """One model's sequences in a Lockstep pool."""
+    model_id: int
+    shape: wl.ModelShape
+    lens: np.ndarray                 # tokens currently cached per sequence
+    tables: np.ndarray               # host copy [n_seqs][n_kv][max_blocks]
+    tables_dev: torch.Tensor
+    sampled: np.ndarray              # sequences whose K/V the oracle also holds
+
+    @property
+    def n_seqs(self) -> int:
+        return int(self.lens.size)
+
+
+def open_job(ls: Lockstep, model_id: int, shape: wl.ModelShape, n_seqs: int, max_len: int,
+             sampled: Optional[np.ndarray] = None, poison: bool = True) -> JobState:
+    max_blocks = (max_len + ls.block_size - 1) // ls.block_size
+    tables = np.full((n_seqs, shape.n_kv_heads, max_blocks), -1, dtype=np.int32)
+    if poison:  # entries past a sequence's blocks are never to be read: make them dangerous
+        tables[:, :, 1::2] = ls.num_blocks + 12345
+    dev = torch.from_numpy(tables).to(ls.device)
+    if sampled is None:
+        sampled = np.ones(n_seqs, dtype=bool)
+    return JobState(model_id, shape, np.zeros(n_seqs, dtype=np.int32), tables, dev, sampled)
+
+
+def extend(ls: Lockstep, job: JobState, new_lens: np.ndarray, seed: int, on_device_values: bool = False,
+           stream=None, bank: Optional[Dict[str, torch.Tensor]] = None):
+    """Grow every sequence of `job` to new_lens tokens: allocate blocks (both sides, ids must
+    agree), draw K/V for the new tokens, append on the GPU and - for sampled sequences - into
+    the oracle.  Returns the (k_new, v_new, tok_seq, tok_pos) device tensors of the call."""
+    new_lens = np.asarray(new_lens, dtype=np.int32)
+    assert (new_lens >= job.lens).all()
+    B, n_kv, d = ls.block_size, job.shape.n_kv_heads, ls.head_dim
+    wl.grow_tables(ls.alloc, job.model_id, job.tables, job.lens, new_lens, B)
+    job.tables_dev.copy_(torch.from_numpy(job.tables))
+    add = (new_lens - job.lens).astype(np.int64)
+    n_tokens = int(add.sum())
+    if n_tokens == 0:
+        job.lens = new_lens.copy()
+        return None
+    tok_seq = np.repeat(np.arange(job.n_seqs, dtype=np.int32), add)
+    starts = np.repeat(job.lens.astype(np.int64), add)
+    offs = np.arange(n_tokens, dtype=np.int64) - np.repeat(np.cumsum(add) - add, add)
+    tok_pos = (starts + offs).astype(np.int32)
+    tdt = torch_dtype(ls.dtype)
+    if bank is not None:
+        # reuse slices of a pre-drawn bank of N(0,1) values (very large fills)
+        need = n_tokens * n_kv * d
+        off = (seed * 7919) % max(1, bank["k"].numel() - need)
+        off -= off % 8
+        k_new = bank["k"][off:off + need].view(n_tokens, n_kv, d)
+        v_new = bank["v"][off:off + need].view(n_tokens, n_kv, d)
+    elif on_device_values:
+        g = torch.Generator(device=ls.device)
+        g.manual_seed(seed)
+        k_new = torch.randn(n_tokens, n_kv, d, generator=g, device=ls.device, dtype=torch.float32).to(tdt)
+        v_new = torch.randn(n_tokens, n_kv, d, generator=g, device=ls.device, dtype=torch.float32).to(tdt)
+    else:
+        k_new = wl.randn_values(seed, (n_tokens, n_kv, d), ls.dtype).to(ls.device)
+        v_new = wl.randn_values(seed + 1, (n_tokens, n_kv, d), ls.dtype).to(ls.device)
+    ts_dev = torch.from_numpy(tok_seq).to(ls.device)
+    tp_dev = torch.from_numpy(tok_pos).to(ls.device)
+    mx.mux_kv_append(ls.lib, k_new, v_new, ts_dev, tp_dev, job.tables_dev, stream=stream)
+    keep = job.sampled[tok_seq]
+    if keep.any():
+        idx = torch.from_numpy(np.nonzero(keep)[0]).to(ls.device)
+        k_h, v_h = to_oracle(k_new.index_select(0, idx)), to_oracle(v_new.index_select(0, idx))
+        ls.orc.kv_append(k_h, v_h, tok_seq[keep], tok_pos[keep], job.tables)
+    job.lens = new_lens.copy()
+    return k_new, v_new, ts_dev, tp_dev
+
+
+def make_q(ls: Lockstep, job: JobState, seed: int, n_rows: Optional[int] = None) -> torch.Tensor:
+    n = job.n_seqs if n_rows is None else n_rows
+    return wl.randn_values(seed, (n, job.shape.n_q_heads, ls.head_dim), ls.dtype).to(ls.device)
+
+
+def decode_gpu(ls: Lockstep, job: JobState, q: torch.Tensor, scale: float, stream=None, max_ctx_len: Optional[int] = None,
+               ctx_lens: Optional[np.ndarray] = None) -> torch.Tensor:
+    lens = job.lens if ctx_lens is None else np.asarray(ctx_lens, dtype=np.int32)
+    mcl = int(lens.max()) if max_ctx_len is None else max_ctx_len
+    mcl = max(mcl, 0)
+    out = torch.full_like(q, float("nan"))
+    ws_bytes = mx.mux_decode_workspace_bytes(ls.lib, job.n_seqs, job.shape.n_q_heads, job.shape.n_kv_heads, max(mcl, 1))
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=ls.device) if ws_bytes else None
+    lens_dev = torch.from_numpy(lens).to(ls.device)
+    mx.mux_decode_attn(ls.lib, out, q, job.tables_dev, lens_dev, mcl, scale, ws, stream=stream)
+    return out
+
+
+def decode_oracle(ls: Lockstep, job: JobState, q: torch.Tensor, scale: float, rows: Optional[np.ndarray] = None,
+                  ctx_lens: Optional[np.ndarray] = None) -> np.ndarray:
+    """Oracle outputs for the listed sequences (default: all sampled ones), fp32 [len(rows)][Hq][d]."""
+    rows = np.nonzero(job.sampled)[0] if rows is None else np.asarray(rows)
+    lens = job.lens if ctx_lens is None else np.asarray(ctx_lens, dtype=np.int32)
+    qh = to_oracle(q)[rows]
+    return ls.orc.decode_attn(qh, job.tables[rows], lens[rows], job.shape.n_q_heads, scale)
+
+
+def tolerance(dtype: str) -> float:
+    """Max-abs bound against the oracle: 2e-2 for bf16 K/V (the bf16 output rounding alone is
+    up to 2^-7 for |o| in [2, 4)), 1e-4 for fp32 K/V; fp32 accumulation on both sides."""
+    return 2e-2 if dtype == "bf16" else 1e-4
+
+
+def assert_close(got: torch.Tensor, want: np.ndarray, dtype: str, what: str = "") -> float:
+    g = got.detach().float().cpu().numpy()
+    assert g.shape == want.shape, (g.shape, want.shape)
+    assert np.isfinite(g).all(), "non-finite output " + what
+    err = float(np.abs(g - want).max()) if g.size else 0.0
+    assert err <= tolerance(dtype), "%s max-abs error %.3e > %.1e" % (what, err, tolerance(dtype))
+    return err
+
+
+def default_scale(head_dim: int) -> float:
+    return 1.0 / math.sqrt(head_dim)

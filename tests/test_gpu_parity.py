@@ -1,0 +1,222 @@
+"""GPU parity: the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Block tables and appended bytes must be bit-exact; attention outputs must agree within
+max-abs 2e-2 (bf16 K/V) or 1e-4 (fp32 K/V).  Inputs are seeded and synthetic.
+"""
+import numpy as np
+import pytest
+import torch
+
+import mux_harness as H
+from paper_2404_02015_amd import binding as mx
+from paper_2404_02015_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+# ---------------------------------------------------------------------------------
+# KV append: bit-exact scatter, nothing else touched
+# ---------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,head_dim,block_size,n_kv", [
+    ("bf16", 128, 16, 4), ("bf16", 64, 16, 8), ("fp32", 128, 16, 2), ("fp32", 64, 8, 3), ("bf16", 128, 1, 2),
+    ("bf16", 64, 32, 5),
+])
+def test_append_is_bit_exact_and_touches_nothing_else(dtype, head_dim, block_size, n_kv):
+    _say("append %s d=%d B=%d Hkv=%d" % (dtype, head_dim, block_size, n_kv))
+    rng = np.random.Generator(np.random.PCG64(101))
+    n_blocks = 700
+    ls = H.Lockstep(n_blocks, block_size, head_dim, dtype, wl.placement_order(rng, n_blocks))
+    shape = wl.ModelShape("t", n_kv, n_kv, head_dim)
+    lens = np.array([0, 1, block_size, block_size + 1, 3 * block_size + 2, 5], dtype=np.int32)
+    job = H.open_job(ls, 0, shape, lens.size, int(lens.max()) + 2 * block_size + 3)
+    H.extend(ls, job, lens, seed=5)                       # many tokens per sequence (prefill-like)
+    H.extend(ls, job, lens + 1, seed=6)                   # one token per sequence (decode-like)
+    H.extend(ls, job, lens + np.array([0, 2, 0, block_size, 1, 0], np.int32) + 1, seed=7)
+    torch.cuda.synchronize()
+    got = ls.pool_image()
+    want = np.full_like(got, H.SENTINEL16)
+    for s in range(job.n_seqs):
+        for pos in range(int(job.lens[s])):
+            for h in range(n_kv):
+                bid = job.tables[s, h, pos // block_size]
+                for which in (0, 1):
+                    want[bid, which, pos % block_size] = ls.orc.read_row(bid, pos % block_size, which).view(np.uint16)
+    assert np.array_equal(got, want)
+    ls.check_counters()
+
+
+def test_append_skips_out_of_range_tokens():
+    ls = H.Lockstep(64, 16, 128, "bf16")
+    shape = wl.ModelShape("t", 2, 2, 128)
+    job = H.open_job(ls, 0, shape, 2, 64, poison=True)
+    ids = ls.alloc(0, 2)
+    job.tables[0, :, 0] = ids
+    job.tables_dev.copy_(torch.from_numpy(job.tables))
+    k = wl.randn_values(1, (5, 2, 128)).cuda()
+    v = wl.randn_values(2, (5, 2, 128)).cuda()
+    # token 0 is fine; the others name a bad sequence, a negative position, a position past
+    # the table and an entry holding an out-of-range id
+    tok_seq = torch.tensor([0, 7, 0, 0, 0], dtype=torch.int32, device="cuda")
+    tok_pos = torch.tensor([3, 0, -1, 4000, 16], dtype=torch.int32, device="cuda")
+    mx.mux_kv_append(ls.lib, k, v, tok_seq, tok_pos, job.tables_dev)
+    torch.cuda.synchronize()
+    img = ls.pool_image()
+    want = np.full_like(img, H.SENTINEL16)
+    for h in range(2):
+        want[ids[h], 0, 3] = wl.as_bits(k.cpu())[0, h]
+        want[ids[h], 1, 3] = wl.as_bits(v.cpu())[0, h]
+    assert np.array_equal(img, want)
+
+
+# ---------------------------------------------------------------------------------
+# decode attention
+# ---------------------------------------------------------------------------------
+def _decode_case(dtype, head_dim, block_size, n_q, n_kv, lens, seed, scale=None, n_blocks=None):
+    lens = np.asarray(lens, dtype=np.int32)
+    need = int(((lens + block_size - 1) // block_size).sum()) * n_kv
+    n_blocks = n_blocks or need + 64
+    rng = np.random.Generator(np.random.PCG64(seed))
+    ls = H.Lockstep(n_blocks, block_size, head_dim, dtype, wl.placement_order(rng, n_blocks))
+    shape = wl.ModelShape("t", n_q, n_kv, head_dim)
+    job = H.open_job(ls, 0, shape, lens.size, int(lens.max()) + block_size)
+    H.extend(ls, job, np.maximum(lens - 1, 0), seed=seed * 10 + 1)   # history
+    H.extend(ls, job, lens, seed=seed * 10 + 3)                       # this step's token
+    q = H.make_q(ls, job, seed * 10 + 5)
+    scale = H.default_scale(head_dim) if scale is None else scale
+    got = H.decode_gpu(ls, job, q, scale)
+    want = H.decode_oracle(ls, job, q, scale)
+    torch.cuda.synchronize()
+    return ls, job, q, got, want
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_config1_two_models_share_one_pool(dtype):
+    """Configuration 1: models A (8 heads) and B (4 heads), head size 64, 4 sequences each,
+    contexts uniform in [1,128], one pool of 1024 blocks in seeded random order; each sequence
+    appends one token (alloc -> append -> decode)."""
+    w = wl.config(1)
+    _say("config 1 %s lens=%s" % (dtype, [j.lens.tolist() for j in w.jobs]))
+    ls = H.Lockstep(w.num_blocks, w.block_size, w.head_dim, dtype, wl.placement_order(w.rng(), w.num_blocks))
+    jobs = [H.open_job(ls, j.model_id, j.shape, j.n_seqs, 128 + 16) for j in w.jobs]
+    for j, st in zip(w.jobs, jobs):
+        H.extend(ls, st, j.lens - 1, seed=w.seed * 100 + j.model_id)
+    streams = [torch.cuda.Stream() for _ in jobs]
+    outs = []
+    for j, st, stream in zip(w.jobs, jobs, streams):
+        stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(stream):
+            H.extend(ls, st, j.lens, seed=w.seed * 100 + 10 + j.model_id, stream=stream)
+            q = H.make_q(ls, st, w.seed * 100 + 20 + j.model_id)
+            outs.append((q, H.decode_gpu(ls, st, q, H.default_scale(w.head_dim), stream=stream)))
+    torch.cuda.synchronize()
+    for st, (q, got) in zip(jobs, outs):
+        H.assert_close(got, H.decode_oracle(ls, st, q, H.default_scale(w.head_dim)), dtype, "model %d" % st.model_id)
+    all_ids = np.concatenate([st.tables[s, :, :(int(st.lens[s]) + w.block_size - 1) // w.block_size].ravel()
+                              for st in jobs for s in range(st.n_seqs)])
+    assert len(set(all_ids.tolist())) == all_ids.size       # no block belongs to two (sequence, head) pairs
+    ls.check_counters()
+
+
+@pytest.mark.parametrize("dtype,head_dim,block_size,n_q,n_kv", [
+    ("bf16", 128, 16, 4, 4), ("bf16", 128, 16, 8, 2), ("bf16", 128, 16, 16, 2), ("bf16", 128, 16, 6, 2),
+    ("bf16", 128, 16, 32, 2), ("bf16", 64, 16, 4, 4), ("bf16", 64, 16, 8, 1),
+    ("fp32", 128, 16, 4, 2), ("fp32", 64, 16, 3, 3),
+    ("bf16", 128, 1, 2, 2), ("bf16", 128, 8, 4, 2), ("bf16", 128, 32, 2, 2), ("bf16", 64, 8, 2, 1),
+    ("fp32", 128, 8, 2, 2), ("fp32", 64, 1, 2, 2), ("bf16", 128, 24, 2, 2),
+])
+def test_decode_matches_oracle_across_shapes(dtype, head_dim, block_size, n_q, n_kv):
+    # lengths: empty, single token, block boundaries, several spans with ragged tails
+    lens = [0, 1, 2, block_size, block_size + 1, 63, 64, 65, 200, 513, 1000, 1500]
+    _say("decode %s d=%d B=%d Hq=%d Hkv=%d" % (dtype, head_dim, block_size, n_q, n_kv))
+    ls, job, q, got, want = _decode_case(dtype, head_dim, block_size, n_q, n_kv, lens, seed=block_size + n_q)
+    err = H.assert_close(got, want, dtype)
+    g = got.float().cpu().numpy()
+    assert np.array_equal(g[0], np.zeros_like(g[0]))                          # empty context -> zeros
+    # a single cached token returns its V row exactly, for every query head of the group
+    v_row = np.stack([ls.orc.read_row(job.tables[1, h, 0], 0, 1) for h in range(n_kv)])
+    v_row = torch.from_numpy(v_row.view(np.int16) if dtype == "bf16" else v_row)
+    v_row = (v_row.view(torch.bfloat16) if dtype == "bf16" else v_row).float().numpy()
+    assert np.array_equal(g[1], np.repeat(v_row, n_q // n_kv, axis=0))
+    print("max abs err %.2e" % err)
+
+
+def test_decode_rows_sum_to_one_on_gpu():
+    """V == 1 everywhere => O == 1 (softmax weights sum to one), checked on the GPU path."""
+    rng = np.random.Generator(np.random.PCG64(3))
+    ls = H.Lockstep(4096, 16, 128, "bf16", wl.placement_order(rng, 4096))
+    shape = wl.ModelShape("t", 8, 4, 128)
+    lens = np.array([5, 77, 640, 1999], dtype=np.int32)
+    job = H.open_job(ls, 0, shape, 4, 2048)
+    k, v, ts, tp = H.extend(ls, job, lens, seed=9)
+    mx.mux_kv_append(ls.lib, k, torch.ones_like(v), ts, tp, job.tables_dev)
+    q = H.make_q(ls, job, 10)
+    got = H.decode_gpu(ls, job, q, 0.3).float().cpu().numpy()
+    assert np.abs(got - 1.0).max() <= 2.0 ** -8
+
+
+def test_decode_dominant_key_and_large_scores():
+    ls = H.Lockstep(512, 16, 128, "fp32")
+    shape = wl.ModelShape("t", 1, 1, 128)
+    job = H.open_job(ls, 0, shape, 1, 320)
+    k, v, ts, tp = H.extend(ls, job, np.array([300], np.int32), seed=21)
+    q = (30.0 * k[123]).reshape(1, 1, 128).contiguous()     # scores of a few thousand
+    got = H.decode_gpu(ls, job, q, 1.0)
+    want = H.decode_oracle(ls, job, q, 1.0)
+    H.assert_close(got, want, "fp32")
+    assert np.abs(got.cpu().numpy()[0, 0] - v[123, 0].cpu().numpy()).max() < 1e-4
+
+
+def test_physical_placement_is_invisible_bit_for_bit():
+    outs = []
+    for scramble_seed in (1, 2):
+        rng = np.random.Generator(np.random.PCG64(scramble_seed))
+        ls = H.Lockstep(3000, 16, 128, "bf16", wl.placement_order(rng, 3000))
+        shape = wl.ModelShape("t", 8, 2, 128)
+        job = H.open_job(ls, 0, shape, 3, 1200)
+        H.extend(ls, job, np.array([17, 600, 1111], np.int32), seed=33)
+        q = H.make_q(ls, job, 34)
+        outs.append((job.tables.copy(), H.decode_gpu(ls, job, q, 0.09).cpu()))
+    assert not np.array_equal(outs[0][0], outs[1][0])
+    assert torch.equal(outs[0][1].view(torch.int16), outs[1][1].view(torch.int16))
+
+
+def test_max_ctx_hint_larger_than_needed_changes_nothing():
+    ls, job, q, got, want = _decode_case("bf16", 128, 16, 4, 4, [40, 300], seed=77)
+    loose = H.decode_gpu(ls, job, q, H.default_scale(128), max_ctx_len=job.tables.shape[2] * 16)
+    H.assert_close(loose, want, "bf16")
+
+
+@pytest.mark.parametrize("idx", [2, 3, 5])
+def test_small_decode_configs_every_output(idx):
+    """Shrunk versions of configurations 2, 3 and 5 (same models, fewer and shorter sequences)
+    where the oracle checks every output element."""
+    w = wl.config(idx, small=True)
+    _say("small config %d: %s" % (idx, [(j.shape.name, j.n_seqs, int(j.lens.max())) for j in w.jobs]))
+    rng = w.rng()
+    if w.placement == "churn":
+        ls = H.Lockstep(w.num_blocks, w.block_size, w.head_dim, "bf16", None)
+        wl.run_churn(rng, w.churn_ops, 512, ls.alloc_or_none, ls.free, n_models=len(w.jobs))
+        ls.check_counters()
+    else:
+        ls = H.Lockstep(w.num_blocks, w.block_size, w.head_dim, "bf16", wl.placement_order(rng, w.num_blocks))
+    states, outs = [], []
+    for j in w.jobs:
+        st = H.open_job(ls, j.model_id, j.shape, j.n_seqs, int(j.lens.max()) + 16)
+        H.extend(ls, st, j.lens - 1, seed=w.seed * 100 + j.model_id)
+        states.append(st)
+    streams = [torch.cuda.Stream() for _ in states]
+    torch.cuda.synchronize()
+    for j, st, stream in zip(w.jobs, states, streams):
+        with torch.cuda.stream(stream):
+            H.extend(ls, st, j.lens, seed=w.seed * 100 + 50 + j.model_id, stream=stream)
+            q = H.make_q(ls, st, w.seed * 100 + 70 + j.model_id)
+            outs.append((q, H.decode_gpu(ls, st, q, H.default_scale(w.head_dim), stream=stream)))
+    torch.cuda.synchronize()
+    for st, (q, got) in zip(states, outs):
+        err = H.assert_close(got, H.decode_oracle(ls, st, q, H.default_scale(w.head_dim)), "bf16", st.shape.name)
+        print("model %s max abs err %.2e" % (st.shape.name, err))
+    ls.check_counters()

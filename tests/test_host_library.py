@@ -1,0 +1,179 @@
+"""CPU-only checks of the library: every symbol the header declares is exported, the block
+manager (Section 3.4, Implementation: request blocks, keep them, release at request end)
+agrees call by call with the oracle's, and argument errors are reported without touching a
+GPU.  No kernel is launched here.
+"""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import mux_oracle as orc
+from paper_2404_02015_amd import binding as mx
+from paper_2404_02015_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def host_pool(num_blocks, block_size=16, head_dim=128, dtype=mx.MUX_BF16, order=None):
+    elem = 2 if dtype == mx.MUX_BF16 else 4
+    # the block manager never touches the memory: a small host buffer stands in for it and
+    # the byte count is given as if it were the full pool
+    kv = torch.empty(64, dtype=torch.uint8)
+    h = C.c_void_p()
+    o = None if order is None else np.ascontiguousarray(order, dtype=np.int32)
+    rc = mx.load().mux_pool_create(C.byref(h), kv.data_ptr(), num_blocks * 2 * block_size * head_dim * elem, num_blocks,
+                                   block_size, head_dim, dtype, None if o is None else o.ctypes.data)
+    if rc != 0:
+        raise mx.MuxError(rc, "mux_pool_create")
+    return mx.Pool(h.value, kv, num_blocks, block_size, head_dim, dtype)
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "mux.h")).read()
+    declared = re.findall(r"MUX_API\s+[\w\s\*]+?\b(mux_\w+)\s*\(", header)
+    assert len(declared) >= 13 and set(declared) == set(mx.EXPORTS)
+    lib = mx.load()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    for name in ("mux_pool_create", "mux_alloc_blocks", "mux_free_blocks", "mux_kv_append", "mux_decode_attn",
+                 "mux_prefill_attn"):
+        assert name in declared
+
+
+def test_status_strings():
+    assert mx.status_string(0) == "MUX_OK" and mx.status_string(-2) == "MUX_ERR_NOMEM"
+    assert mx.status_string(-5) == "MUX_ERR_UNSUPPORTED" and "UNKNOWN" in mx.status_string(-99)
+
+
+def test_allocator_hand_example_and_errors():
+    p = host_pool(8)
+    assert list(mx.mux_alloc_blocks(p, 0, 3)) == [0, 1, 2]
+    mx.mux_free_blocks(p, 0, [1])
+    assert list(mx.mux_alloc_blocks(p, 0, 2)) == [1, 3]
+    mx.mux_free_blocks(p, 0, [0, 3])
+    assert list(mx.mux_alloc_blocks(p, 0, 1)) == [3]
+    assert mx.mux_pool_num_free(p) == 5 and mx.mux_pool_num_used(p, 0) == 3
+    out = np.full(8, -7, dtype=np.int32)
+    rc, ids = mx.mux_alloc_blocks_status(p, 1, 6, out)
+    assert rc == mx.MUX_ERR_NOMEM and ids is None and (out == -7).all() and mx.mux_pool_num_free(p) == 5
+    assert mx.mux_free_blocks_status(p, 0, [1, 1]) == mx.MUX_ERR_INVALID
+    assert mx.mux_free_blocks_status(p, 0, [0]) == mx.MUX_ERR_INVALID       # already free
+    assert mx.mux_free_blocks_status(p, 1, [1]) == mx.MUX_ERR_INVALID       # other model's
+    assert mx.mux_free_blocks_status(p, 0, [1, 8]) == mx.MUX_ERR_INVALID    # out of range
+    assert mx.mux_free_blocks_status(p, 0, [-1]) == mx.MUX_ERR_INVALID
+    assert mx.mux_free_blocks_status(p, 4000, [1]) == mx.MUX_ERR_INVALID    # model id out of range
+    assert mx.mux_pool_num_used(p, 0) == 3 and mx.mux_pool_num_free(p) == 5
+    assert mx.mux_alloc_blocks_status(p, 0, -1)[0] == mx.MUX_ERR_INVALID
+    assert mx.mux_alloc_blocks_status(p, 0, 0)[0] == mx.MUX_OK
+
+
+def test_pool_create_argument_checks():
+    with pytest.raises(mx.MuxError) as e:
+        host_pool(4, order=[0, 1, 1, 2])
+    assert e.value.status == mx.MUX_ERR_INVALID
+    for kw in (dict(head_dim=96), dict(block_size=512), dict(dtype=7)):
+        with pytest.raises(mx.MuxError) as e:
+            host_pool(4, **kw)
+        assert e.value.status == mx.MUX_ERR_UNSUPPORTED
+    # a buffer smaller than the pool is refused
+    kv = torch.empty(1024, dtype=torch.uint8)
+    with pytest.raises(mx.MuxError):
+        mx.mux_pool_create(kv, 8, 16, 128)
+    p = host_pool(4, order=[3, 0, 2, 1])
+    assert list(mx.mux_alloc_blocks(p, 0, 4)) == [3, 0, 2, 1]
+
+
+def test_library_and_oracle_allocators_agree_under_churn():
+    n_blocks = 6000
+    rng = np.random.Generator(np.random.PCG64(7))
+    order = wl.placement_order(rng, n_blocks)
+    lib, ora = host_pool(n_blocks, order=order), orc.OraclePool(n_blocks, 16, 128, init_free_order=order)
+    stats = {"nomem": 0}
+
+    def alloc(m, n):
+        rc_l, ids_l = mx.mux_alloc_blocks_status(lib, m, n)
+        rc_o, ids_o = ora.alloc_status(m, n)
+        assert rc_l == rc_o
+        if rc_l != 0:
+            stats["nomem"] += 1
+            return None
+        assert np.array_equal(ids_l, ids_o)
+        return ids_l
+
+    def free(m, ids):
+        assert mx.mux_free_blocks_status(lib, m, ids) == ora.free_status(m, ids) == 0
+        assert mx.mux_pool_num_free(lib) == ora.num_free()
+
+    wl.run_churn(rng, 3000, 500, alloc, free)
+    assert stats["nomem"] > 0
+    assert mx.mux_pool_num_free(lib) == ora.num_free() == n_blocks
+    # after the churn the free lists are in the same (scrambled) order
+    assert np.array_equal(mx.mux_alloc_blocks(lib, 0, n_blocks), ora.alloc(0, n_blocks))
+
+
+def test_config2_named_pool_runs_out_identically():
+    """The second configuration names a 200 000-block pool, less than its sequences need: both
+    block managers must fail at the same call and stay unchanged."""
+    w = wl.config(2)
+    n_blocks = 200000
+    order = wl.placement_order(w.rng(), n_blocks)
+    lib, ora = host_pool(n_blocks, order=order), orc.OraclePool(n_blocks, 16, 128, init_free_order=order)
+    failed_at = None
+    for job in w.jobs:
+        for s, L in enumerate(job.lens):
+            n = int((L + 15) // 16) * job.shape.n_kv_heads
+            rc_l, ids_l = mx.mux_alloc_blocks_status(lib, job.model_id, n)
+            rc_o, ids_o = ora.alloc_status(job.model_id, n)
+            assert rc_l == rc_o
+            if rc_l != 0:
+                assert rc_l == mx.MUX_ERR_NOMEM
+                failed_at = (job.model_id, s, mx.mux_pool_num_free(lib))
+                break
+            assert np.array_equal(ids_l, ids_o)
+        if failed_at:
+            break
+    assert failed_at is not None and failed_at[2] == ora.num_free() and failed_at[2] < n
+    assert w.demand_blocks() > n_blocks
+
+
+def test_kernel_calls_reject_bad_host_arguments_before_launching():
+    p = host_pool(64)
+    lib = mx.load()
+    h = p.handle
+    fake = 4096  # never dereferenced: every call below fails its host-side checks first
+    assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 6, 4, 4, 64, 1.0, None, 0, None) == mx.MUX_ERR_INVALID  # 6 % 4
+    assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 4, 4, 4, 65, 1.0, None, 0, None) == mx.MUX_ERR_INVALID  # hint > table
+    assert lib.mux_decode_attn(h, fake + 2, fake, fake, fake, 2, 4, 4, 4, 64, 1.0, None, 0, None) == mx.MUX_ERR_INVALID  # alignment
+    assert lib.mux_decode_attn(h, None, fake, fake, fake, 2, 4, 4, 4, 64, 1.0, None, 0, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_decode_attn(h, fake, fake, fake, fake, 0, 4, 4, 4, 64, 1.0, None, 0, None) == mx.MUX_OK           # empty batch
+    # long contexts need a workspace
+    need = lib.mux_decode_workspace_bytes(h, 2, 4, 4, 4096)
+    assert need > 0
+    assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 4, 4, 256, 4096, 1.0, None, 0, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 4, 4, 256, 4096, 1.0, fake, need - 1, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_kv_append(h, fake, fake, fake, fake, fake, -1, 1, 4, 4, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_kv_append(h, fake, fake, fake, fake, fake, 0, 1, 4, 4, None) == mx.MUX_OK
+    assert lib.mux_kv_append(h, fake + 8, fake, fake, fake, fake, 3, 1, 4, 4, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_prefill_attn(h, fake, fake, fake, fake, fake, 1, 8, 8, 4, 4, 4, 4, 1.0, None, 0, None) == mx.MUX_ERR_INVALID  # q longer than ctx
+    assert lib.mux_prefill_attn(h, fake, fake, fake, fake, fake, 1, 8, 8, 8, 5, 4, 4, 1.0, None, 0, None) == mx.MUX_ERR_INVALID  # 5 % 4
+    assert lib.mux_prefill_attn(h, fake, fake, fake, fake, fake, 0, 0, 0, 0, 4, 4, 4, 1.0, None, 0, None) == mx.MUX_OK
+    # the Python layer refuses to launch kernels on a host pool
+    with pytest.raises(ValueError):
+        mx.mux_kv_append(p, torch.zeros(1, 4, 128, dtype=torch.bfloat16), torch.zeros(1, 4, 128, dtype=torch.bfloat16),
+                         torch.zeros(1, dtype=torch.int32), torch.zeros(1, dtype=torch.int32),
+                         torch.zeros(1, 4, 4, dtype=torch.int32))
+
+
+def test_decode_plan_workspace_is_monotone_and_bounded():
+    p = host_pool(64)
+    lib = mx.load()
+    assert lib.mux_decode_workspace_bytes(p.handle, 4096, 32, 32, 16) == 0      # one span: no workspace
+    prev = 0
+    for ctx in (1024, 4096, 16384):
+        b = lib.mux_decode_workspace_bytes(p.handle, 64, 32, 32, ctx)
+        assert b >= prev and b < 64 * 32 * (ctx // 16 + 4) * 130 * 4
+        prev = b
