@@ -1,0 +1,278 @@
+#!/usr/bin/env python3
+"""Benchmark of the head-wise paged KV-cache hot path on one MI355X.
+
+Workload (N=1): the second configuration - two colocated LLaMA-7B-shaped models (32 heads x
+128, bf16) sharing one pool of 16-token head-blocks in seeded random placement, 64 decoding
+sequences per model with contexts uniform in [128, 2048].  One *step* is one decoding step of
+one layer for every model, each model on its own HIP stream:
+
+    mux_alloc_blocks (for sequences whose new token opens a block) -> table patch ->
+    mux_kv_append (one token per sequence) -> mux_decode_attn (all cached tokens)
+
+Everything is resident in HBM before the timed region.  `value` is the K/V bytes the decode
+attention has to read (valid tokens only) per second of wall time over the whole step loop.
+The `roofline` object prices the dominant kernel (decode attention) against the 8 TB/s HBM
+peak from HIP-event durations of its launches inside the timed loop; `cpu_baseline` times the
+CPU oracle on a bounded sample of the same sequences on this machine's host cores.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2404_02015_amd import binding as mx  # noqa: E402
+from paper_2404_02015_amd import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+
+class DecodeModel:
+    """Device state of one colocated model: tables, lengths, per-step inputs, its stream."""
+
+    def __init__(self, pool, job: wl.ModelJob, block_size: int, total_steps: int, seed: int, device: str):
+        self.pool, self.job, self.B = pool, job, block_size
+        self.shape = job.shape
+        self.n = job.n_seqs
+        n_kv, n_q, d = self.shape.n_kv_heads, self.shape.n_q_heads, self.shape.head_dim
+        self.lens = (job.lens.astype(np.int64) - 1).astype(np.int32)   # cached before the first step
+        self.max_blocks = wl.max_blocks_for(job.lens, block_size, extra_tokens=total_steps + 1)
+        self.stream = torch.cuda.Stream()
+        self.device = device
+        g = torch.Generator(device=device)
+        g.manual_seed(seed)
+        # block tables for the history, ids from the library's block manager
+        self.tables = wl.build_tables(lambda m, k: mx.mux_alloc_blocks(pool, m, k), job.model_id, self.lens, n_kv,
+                                      block_size, self.max_blocks)
+        self.tables_dev = torch.from_numpy(self.tables).to(device)
+        # history K/V ~ N(0,1), drawn on the device sequence by sequence and appended
+        for s0 in range(0, self.n, 8):
+            s1 = min(self.n, s0 + 8)
+            cnt = self.lens[s0:s1].astype(np.int64)
+            nt = int(cnt.sum())
+            if nt == 0:
+                continue
+            k = torch.randn(nt, n_kv, d, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+            v = torch.randn(nt, n_kv, d, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+            seq = np.repeat(np.arange(s0, s1, dtype=np.int32), cnt)
+            pos = (np.arange(nt, dtype=np.int64) - np.repeat(np.cumsum(cnt) - cnt, cnt)).astype(np.int32)
+            mx.mux_kv_append(pool, k, v, torch.from_numpy(seq).to(device), torch.from_numpy(pos).to(device),
+                             self.tables_dev)
+        torch.cuda.synchronize()
+        # per-step inputs: one new K/V row and one query row per sequence
+        self.k_steps = torch.randn(total_steps, self.n, n_kv, d, generator=g, device=device).to(torch.bfloat16)
+        self.v_steps = torch.randn(total_steps, self.n, n_kv, d, generator=g, device=device).to(torch.bfloat16)
+        self.q_steps = torch.randn(total_steps, self.n, n_q, d, generator=g, device=device).to(torch.bfloat16)
+        self.out = torch.empty(self.n, n_q, d, device=device, dtype=torch.bfloat16)
+        self.tok_seq = torch.arange(self.n, dtype=torch.int32, device=device)
+        # row 0: position of the token appended this step, row 1: context length after the append
+        self.pos_len = torch.stack([torch.from_numpy(self.lens - 1), torch.from_numpy(self.lens)]).to(device).contiguous()
+        max_final = int(job.lens.max()) + total_steps + 1
+        ws = mx.mux_decode_workspace_bytes(pool, self.n, n_q, n_kv, max_final)
+        self.workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=device)
+        # pinned staging ring for table patches (ids are written here by mux_alloc_blocks itself)
+        cap = self.n * n_kv
+        self.pin_ids = torch.empty(total_steps, cap, dtype=torch.int32, pin_memory=True)
+        self.pin_idx = torch.empty(total_steps, cap, dtype=torch.int64, pin_memory=True)
+        self.pin_ids_np, self.pin_idx_np = self.pin_ids.numpy(), self.pin_idx.numpy()
+        self.flat_tables = self.tables_dev.view(-1)
+        self.head_base = (np.arange(n_kv, dtype=np.int64) * self.max_blocks)
+        self.scale = 1.0 / math.sqrt(d)
+        self.step_no = 0
+        self.kv_bytes_per_token = 2 * n_kv * d * 2
+        self.decode_events = []
+
+    def step(self, record: bool, after=None):
+        """Enqueue one decoding step on this model's stream.  `after`: an event the decode
+        attention (not the small kernels before it) waits for.  Returns the K/V bytes the
+        decode attention has to read and the event that marks its end."""
+        i = self.step_no
+        self.step_no += 1
+        n_kv = self.shape.n_kv_heads
+        new_lens = self.lens + 1
+        crossing = np.nonzero((new_lens - 1) % self.B == 0)[0]
+        with torch.cuda.stream(self.stream):
+            if crossing.size:
+                cnt = 0
+                for s in crossing:
+                    ids = self.pin_ids_np[i, cnt:cnt + n_kv]
+                    mx.mux_alloc_blocks(self.pool, self.job.model_id, n_kv, ids)
+                    col = int(new_lens[s] - 1) // self.B
+                    self.pin_idx_np[i, cnt:cnt + n_kv] = (int(s) * n_kv * self.max_blocks + col) + self.head_base
+                    cnt += n_kv
+                idx_dev = self.pin_idx[i, :cnt].to(self.device, non_blocking=True)
+                ids_dev = self.pin_ids[i, :cnt].to(self.device, non_blocking=True)
+                self.flat_tables.index_copy_(0, idx_dev, ids_dev)
+            self.pos_len.add_(1)
+            mx.mux_kv_append(self.pool, self.k_steps[i], self.v_steps[i], self.tok_seq, self.pos_len[0], self.tables_dev,
+                             stream=self.stream)
+            max_ctx = int(new_lens.max())
+            if after is not None:
+                self.stream.wait_event(after)
+            e0, e1 = torch.cuda.Event(enable_timing=record), torch.cuda.Event(enable_timing=record)
+            if record:
+                e0.record(self.stream)
+            mx.mux_decode_attn(self.pool, self.out, self.q_steps[i], self.tables_dev, self.pos_len[1], max_ctx, self.scale,
+                               self.workspace, stream=self.stream)
+            e1.record(self.stream)
+            if record:
+                self.decode_events.append((e0, e1, int(new_lens.astype(np.int64).sum()) * self.kv_bytes_per_token))
+        self.lens = new_lens
+        return int(new_lens.astype(np.int64).sum()) * self.kv_bytes_per_token, e1
+
+
+def build_workload(cfg_index: int, total_steps: int, device: str = "cuda"):
+    w = wl.config(cfg_index)
+    decode_jobs = [j for j in w.jobs if j.kind == "decode"]
+    growth = sum(j.n_seqs * j.shape.n_kv_heads * (total_steps // w.block_size + 2) for j in decode_jobs)
+    num_blocks = max(w.num_blocks, w.demand_blocks() + growth)
+    block_bytes = 2 * w.block_size * w.head_dim * 2
+    kv = torch.empty(num_blocks * block_bytes, dtype=torch.uint8, device=device)
+    order = wl.placement_order(w.rng(), num_blocks)
+    pool = mx.mux_pool_create(kv, num_blocks, w.block_size, w.head_dim, mx.MUX_BF16, order)
+    models = [DecodeModel(pool, j, w.block_size, total_steps, w.seed * 1000 + j.model_id, device) for j in decode_jobs]
+    return w, pool, models
+
+
+def cpu_baseline(models, budget_s: float = 12.0):
+    """Time the CPU oracle (as it stands) on a bounded sample of the workload's sequences."""
+    from oracle import mux_oracle as orc
+
+    orc.build()
+    m = models[0]
+    B, d, n_kv, n_q = m.B, m.shape.head_dim, m.shape.n_kv_heads, m.shape.n_q_heads
+    order = np.argsort(-m.lens, kind="stable")
+    # sample: sequences of the first model, longest first, until ~1/4 of its tokens
+    target = int(m.lens.astype(np.int64).sum() // 4)
+    pick, tok = [], 0
+    for s in order:
+        pick.append(int(s))
+        tok += int(m.lens[s])
+        if tok >= target:
+            break
+    pick = np.array(sorted(pick))
+    lens = m.lens[pick]
+    nb = int(((lens + B - 1) // B).sum()) * n_kv
+    pool = orc.OraclePool(nb + 8, B, d, orc.BF16)
+    tables = wl.build_tables(lambda mid, k: pool.alloc(mid, k), 0, lens, n_kv, B, int((lens.max() + B - 1) // B))
+    rng = np.random.default_rng(1)
+    for i, L in enumerate(lens):  # values do not matter for the timing; N(0,1) in bf16
+        k = (rng.standard_normal((int(L), n_kv, d), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+        v = (rng.standard_normal((int(L), n_kv, d), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+        pool.kv_append(k, v, np.full(int(L), i, np.int32), np.arange(int(L), dtype=np.int32), tables)
+    q = (rng.standard_normal((len(pick), n_q, d), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        pool.decode_attn(q, tables, lens, n_q, m.scale)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt > budget_s:
+            break
+    kv_bytes = int(lens.astype(np.int64).sum()) * m.kv_bytes_per_token
+    return {
+        "value": kv_bytes * reps / dt / 1e9, "unit": "GB/s", "cores": orc.num_threads(), "kind": "oracle",
+        "sample": "%d longest-first sequences of model 0 (%d tokens, %.1f MB of K/V), %d passes in %.1f s"
+                  % (len(pick), int(lens.sum()), kv_bytes / 1e6, reps, dt),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap-decode", action="store_true", help="let the models' decode kernels run concurrently")
+    ap.add_argument("--pmc-calibration", action="store_true", help="also run three 1 GiB device copies after the timed loop")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        return 2
+    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: launched with WORLD_SIZE > 1; this build runs on one GPU only", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    mx.load()
+    total = args.steps + args.warmup
+    w, pool, models = build_workload(args.config, total)
+
+    # Scheduling policy of this harness: every model has its own stream, so the block-table
+    # patches and appends of one model overlap with whatever the other models run; the decode
+    # attention kernels, each of which saturates HBM on its own, are chained one after the
+    # other through events unless --overlap-decode is given.
+    last = None
+    for _ in range(args.warmup):
+        for m in models:
+            _, ev = m.step(record=False, after=last)
+            last = None if args.overlap_decode else ev
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    kv_bytes = 0
+    for _ in range(args.steps):
+        for m in models:
+            b, ev = m.step(record=True, after=last)
+            last = None if args.overlap_decode else ev
+            kv_bytes += b
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    if args.pmc_calibration:
+        # a plain copy of known size in the same process, for scaling rocprofv3 --pmc byte counters
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    # dominant kernel: decode attention (main kernel + span combine), HIP-event durations
+    durs, algo = [], []
+    for m in models:
+        for e0, e1, b in m.decode_events:
+            durs.append(e0.elapsed_time(e1) * 1e-3)
+            algo.append(b)
+    achieved = float(np.sum(algo) / np.sum(durs) / 1e9)
+    n_seqs = sum(m.n for m in models)
+    result = {
+        "metric": "decode-attn KV GB/s (% of HBM peak) + tokens/s, multi-LLM mixed batch",
+        "value": kv_bytes / dt / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 storage, f32 arithmetic", "data": "synthetic",
+        "config": {
+            "workload": "config %d: %s; block_size %d; %d head-blocks, seeded random placement; per step and model: "
+                        "alloc -> table patch -> kv_append(1 token/seq) -> decode_attn, one stream per model, decode kernels %s"
+                        % (args.config, ", ".join("%s x%d seqs" % (m.shape.name, m.n) for m in models), w.block_size,
+                           pool.num_blocks, "overlapped" if args.overlap_decode else "chained"),
+            "layers": 1,
+        },
+        "pct_hbm_peak": 100.0 * kv_bytes / dt / 1e9 / HBM_PEAK_GBS,
+        "tokens_per_s": n_seqs * args.steps / dt,
+        "roofline": {
+            "kernel": "decode_attn_kernel (+ decode_combine_kernel), one launch per model per step",
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None, "avg_launch_ms": float(np.mean(durs) * 1e3), "algorithmic_bytes_per_launch": float(np.mean(algo)),
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(models)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -32,8 +32,12 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+#ifndef MUX_DECODE_MIN_WAVES
+#define MUX_DECODE_MIN_WAVES 1
+#endif
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
+constexpr int kMaxRanked = 1024;               // largest batch ordered longest-first inside the kernel
 constexpr int kMaxWaveBlocks = 64;              // block ids a wave keeps in one register
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -3.0e38f;             // "no score seen yet"; finite so that differences stay finite
@@ -113,7 +117,7 @@ struct DecodeArgs {
 // BF16: storage type; D: head size; BS: tokens per block at compile time (0 = run time);
 // GT: query heads of one KV group handled together.
 template <bool BF16, int D, int BS, int GT>
-__global__ __launch_bounds__(kThreads) void decode_attn_kernel(const DecodeArgs a)
+__global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_kernel(const DecodeArgs a)
 {
     constexpr int EB = BF16 ? 2 : 4;
     constexpr int EPL = 16 / EB;          // elements per lane per load
@@ -135,12 +139,45 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(const DecodeArgs 
     const int split = w % a.n_splits;  w /= a.n_splits;
     const int pass = w % a.n_passes;   w /= a.n_passes;
     const int kvh = w % a.n_kv_heads;
-    const int s = w / a.n_kv_heads;
+    const int turn = w / a.n_kv_heads;
+
+    // Longest sequence first: workgroups are dispatched in index order and a workgroup's time
+    // grows with its context length, so the sequence served in turn r is the one with the r-th
+    // longest context (ties by index).  Every workgroup ranks the batch itself from LDS, a few
+    // hundred cycles for the batch sizes of a decode step; very large batches keep index order.
+    int s = turn;
+    if (a.n_seqs > 1 && a.n_seqs <= kMaxRanked) {
+        __shared__ int sm_len[kMaxRanked];
+        __shared__ int sm_pick;
+        for (int t = tid; t < a.n_seqs; t += kThreads) sm_len[t] = min(max(a.ctx_lens[t], 0), a.max_ctx_len);
+        __syncthreads();
+        for (int t = tid; t < a.n_seqs; t += kThreads) {
+            const int lt = sm_len[t];
+            int rank = 0;
+            for (int u = 0; u < a.n_seqs; ++u) {
+                const int lu = sm_len[u];
+                rank += (lu > lt || (lu == lt && u < t)) ? 1 : 0;
+            }
+            if (rank == turn) sm_pick = t;
+        }
+        __syncthreads();
+        s = sm_pick;
+    }
+
+    // Block ids of this wave: block blk_lo + wave + kWaves * j sits in lane j.  The load does
+    // not wait for the context length (any entry inside the table row may be read; entries
+    // past the sequence's blocks are never used), so the two latencies overlap.
+    const int blk_lo = split * a.span_blocks;
+    const int *row = a.tables + (static_cast<long long>(s) * a.n_kv_heads + kvh) * a.max_blocks;
+    int my_ids = 0;
+    {
+        const int col = blk_lo + wave + kWaves * lane;
+        if (col < a.max_blocks) my_ids = row[col];
+    }
 
     int L = a.ctx_lens[s];
     L = min(max(L, 0), a.max_ctx_len);
     const int n_blk_seq = (L + B - 1) / B;
-    const int blk_lo = split * a.span_blocks;
     if (a.n_splits > 1 && blk_lo >= n_blk_seq) return;  // nothing of this sequence falls in the span
     const int blk_hi = min(blk_lo + a.span_blocks, n_blk_seq);
 
@@ -168,11 +205,7 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(const DecodeArgs 
         for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
     }
 
-    // Block ids of this wave: block blk_lo + wave + kWaves * j sits in lane j.
     const int n_mine = blk_hi - blk_lo > wave ? (blk_hi - blk_lo - wave + kWaves - 1) / kWaves : 0;
-    const int *row = a.tables + (static_cast<long long>(s) * a.n_kv_heads + kvh) * a.max_blocks;
-    int my_ids = 0;
-    if (lane < n_mine) my_ids = row[blk_lo + wave + kWaves * lane];
 
     auto tile_ptr = [&](int j) -> const char * {
         int id = __builtin_amdgcn_readlane(my_ids, j);
@@ -423,16 +456,24 @@ mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_
 
     const int B = pool->block_size;
     const long long ctx_blocks = (static_cast<long long>(max_ctx_len) + B - 1) / B;
-    // Span: about 512 tokens, in whole blocks, a multiple of the wave count, at most what a
-    // wave can index from one register; shortened while the grid would leave CUs idle.
+    // Span: as long as possible (a workgroup pays its start-up latency and the merge of its
+    // waves once, and a lone long workgroup still streams fast), but short enough that the
+    // grid has at least ~2 workgroups per resident slot; whole blocks, a multiple of the wave
+    // count, at most what a wave can index from one register.
     static const int forced = env_int("MUX_DECODE_SPAN_BLOCKS", 0);
-    long long span = forced > 0 ? forced : (512 + B - 1) / B;
-    span = (span + kWaves - 1) / kWaves * kWaves;
-    if (span > kWaves * kMaxWaveBlocks) span = kWaves * kMaxWaveBlocks;
-    if (forced <= 0) {
+    const long long max_span = kWaves * kMaxWaveBlocks;
+    long long span;
+    if (forced > 0) {
+        span = forced;
+    } else {
         const long long items = static_cast<long long>(n_seqs) * n_kv_heads * plan.n_passes;
-        while (span > kWaves && items * ((ctx_blocks + span - 1) / span) < 2048) span = (span / 2 + kWaves - 1) / kWaves * kWaves;
+        long long want_splits = (2048 + items - 1) / items;
+        if (want_splits > ctx_blocks) want_splits = ctx_blocks;
+        if (want_splits < 1) want_splits = 1;
+        span = (ctx_blocks + want_splits - 1) / want_splits;
     }
+    span = (span + kWaves - 1) / kWaves * kWaves;
+    if (span > max_span) span = max_span;
     plan.span_tokens = static_cast<int32_t>(span * B);
     plan.n_splits = static_cast<int32_t>((ctx_blocks + span - 1) / span);
     if (plan.n_splits < 1) plan.n_splits = 1;
