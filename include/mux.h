@@ -148,7 +148,10 @@ MUX_API size_t mux_decode_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs
  * out, q: DEVICE [total_q][n_q_heads][head_dim].  cu_q_lens: DEVICE int32 [n_seqs+1].
  * q_start: DEVICE int32 [n_seqs], tokens cached before this chunk.  max_q_len,
  * max_ctx_len: HOST upper bounds on the chunk lengths and on q_start + chunk length.
- * workspace: reserved, may be NULL (mux_prefill_workspace_bytes returns 0).
+ * workspace: DEVICE scratch of at least mux_prefill_workspace_bytes(...) bytes, 16-byte
+ * aligned; that function returns 0 (workspace may be NULL) for bf16 pools with 16-token
+ * blocks, which run on the matrix cores; other pools take a slow generic path that may
+ * need scratch for long contexts.
  * ------------------------------------------------------------------------------- */
 MUX_API int mux_prefill_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *cu_q_lens,
                      const int32_t *q_start, const int32_t *block_tables, int32_t n_seqs,
@@ -156,7 +159,7 @@ MUX_API int mux_prefill_attn(mux_pool_t *pool, void *out, const void *q, const i
                      int32_t n_kv_heads, int32_t max_blocks, float scale, void *workspace,
                      size_t workspace_bytes, void *stream);
 MUX_API size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs, int32_t total_q,
-                                   int32_t n_q_heads, int32_t n_kv_heads);
+                                   int32_t max_ctx_len, int32_t n_q_heads, int32_t n_kv_heads);
 
 /* Human-readable name of a status code (static storage). */
 MUX_API const char *mux_status_string(int status);

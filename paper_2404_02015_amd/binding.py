@@ -61,7 +61,7 @@ def load() -> C.CDLL:
     L.mux_decode_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     L.mux_decode_workspace_bytes.restype = sz
     L.mux_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, sz, vp]
-    L.mux_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+    L.mux_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
     L.mux_prefill_workspace_bytes.restype = sz
     L.mux_status_string.argtypes = [C.c_int]
     L.mux_status_string.restype = C.c_char_p
@@ -205,8 +205,9 @@ def mux_decode_attn(pool: Pool, out: torch.Tensor, q: torch.Tensor, block_tables
     _check(rc, "mux_decode_attn")
 
 
-def mux_prefill_workspace_bytes(pool: Pool, n_seqs: int, total_q: int, n_q_heads: int, n_kv_heads: int) -> int:
-    return load().mux_prefill_workspace_bytes(pool.handle, n_seqs, total_q, n_q_heads, n_kv_heads)
+def mux_prefill_workspace_bytes(pool: Pool, n_seqs: int, total_q: int, max_ctx_len: int, n_q_heads: int,
+                                n_kv_heads: int) -> int:
+    return load().mux_prefill_workspace_bytes(pool.handle, n_seqs, total_q, max_ctx_len, n_q_heads, n_kv_heads)
 
 
 def mux_prefill_attn(pool: Pool, out: torch.Tensor, q: torch.Tensor, cu_q_lens: torch.Tensor, q_start: torch.Tensor,

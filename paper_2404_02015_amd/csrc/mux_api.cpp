@@ -186,15 +186,19 @@ int mux_decode_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *b
                                   max_blocks, max_ctx_len, scale, workspace, stream);
 }
 
-size_t mux_prefill_workspace_bytes(const mux_pool_t *, int32_t, int32_t, int32_t, int32_t) { return 0; }
+size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs, int32_t total_q, int32_t max_ctx_len,
+                                   int32_t n_q_heads, int32_t n_kv_heads)
+{
+    if (!pool || n_seqs <= 0 || total_q <= 0 || max_ctx_len <= 0 || !heads_ok(n_q_heads, n_kv_heads)) return 0;
+    if (mux_prefill_uses_mfma(pool)) return 0;
+    return mux_plan_decode(pool, total_q, n_q_heads, n_kv_heads, max_ctx_len).workspace_bytes;
+}
 
 int mux_prefill_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *cu_q_lens, const int32_t *q_start,
                      const int32_t *block_tables, int32_t n_seqs, int32_t total_q, int32_t max_q_len,
                      int32_t max_ctx_len, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, float scale,
                      void *workspace, size_t workspace_bytes, void *stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     if (!pool || n_seqs < 0 || total_q < 0 || max_q_len < 0 || max_ctx_len < 0 || !heads_ok(n_q_heads, n_kv_heads) ||
         max_blocks < 0)
         return MUX_ERR_INVALID;
@@ -202,8 +206,10 @@ int mux_prefill_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *
     if (!out || !q || !cu_q_lens || !q_start || !block_tables || !aligned16(out) || !aligned16(q)) return MUX_ERR_INVALID;
     if (max_q_len > max_ctx_len || max_ctx_len > static_cast<int64_t>(max_blocks) * pool->block_size)
         return MUX_ERR_INVALID;
+    const size_t need = mux_prefill_workspace_bytes(pool, n_seqs, total_q, max_ctx_len, n_q_heads, n_kv_heads);
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return MUX_ERR_INVALID;
     return mux_launch_prefill_attn(pool, out, q, cu_q_lens, q_start, block_tables, n_seqs, total_q, max_q_len,
-                                   max_ctx_len, n_q_heads, n_kv_heads, max_blocks, scale, stream);
+                                   max_ctx_len, n_q_heads, n_kv_heads, max_blocks, scale, workspace, stream);
 }
 
 const char *mux_status_string(int status)

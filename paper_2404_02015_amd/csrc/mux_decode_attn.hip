@@ -104,8 +104,14 @@ struct DecodeArgs {
     void *out;
     const void *q;
     const int *tables;
-    const int *ctx_lens;
-    int n_seqs, n_q_heads, n_kv_heads, max_blocks, max_ctx_len;
+    const int *ctx_lens;    // decode: context length of every row
+    // generic prefill: every query row of every chunk is one "decode" row; its table row and
+    // context length follow from cu_q_lens / q_start (both null for decode)
+    const int *cu_q_lens;
+    const int *q_start;
+    int n_table_seqs;       // sequences in the block table (== n_seqs for decode)
+    int n_seqs;             // rows of q / out
+    int n_q_heads, n_kv_heads, max_blocks, max_ctx_len;
     float scale_log2e;
     int span_blocks;  // blocks per workgroup span
     int n_splits;
@@ -113,6 +119,24 @@ struct DecodeArgs {
     float *ws_acc;  // [n_seqs][n_q_heads][n_splits][D]
     float *ws_ml;   // [n_seqs][n_q_heads][n_splits][2]
 };
+
+// Row r of q/out -> (block-table row, context length).
+__device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &table_row, int &len)
+{
+    if (a.cu_q_lens == nullptr) {
+        table_row = r;
+        len = a.ctx_lens[r];
+    } else {
+        int lo = 0, hi = a.n_table_seqs - 1;  // last sequence whose first row is <= r
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (a.cu_q_lens[mid] <= r) lo = mid; else hi = mid - 1;
+        }
+        table_row = lo;
+        len = a.q_start[lo] + (r - a.cu_q_lens[lo]) + 1;  // causal: keys up to and including its own
+    }
+    len = min(max(len, 0), a.max_ctx_len);
+}
 
 // BF16: storage type; D: head size; BS: tokens per block at compile time (0 = run time);
 // GT: query heads of one KV group handled together.
@@ -146,7 +170,7 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     // longest context (ties by index).  Every workgroup ranks the batch itself from LDS, a few
     // hundred cycles for the batch sizes of a decode step; very large batches keep index order.
     int s = turn;
-    if (a.n_seqs > 1 && a.n_seqs <= kMaxRanked) {
+    if (a.cu_q_lens == nullptr && a.n_seqs > 1 && a.n_seqs <= kMaxRanked) {
         __shared__ int sm_len[kMaxRanked];
         __shared__ int sm_pick;
         for (int t = tid; t < a.n_seqs; t += kThreads) sm_len[t] = min(max(a.ctx_lens[t], 0), a.max_ctx_len);
@@ -168,15 +192,14 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     // not wait for the context length (any entry inside the table row may be read; entries
     // past the sequence's blocks are never used), so the two latencies overlap.
     const int blk_lo = split * a.span_blocks;
-    const int *row = a.tables + (static_cast<long long>(s) * a.n_kv_heads + kvh) * a.max_blocks;
+    int table_row, L;
+    resolve_row(a, s, table_row, L);
+    const int *row = a.tables + (static_cast<long long>(table_row) * a.n_kv_heads + kvh) * a.max_blocks;
     int my_ids = 0;
     {
         const int col = blk_lo + wave + kWaves * lane;
         if (col < a.max_blocks) my_ids = row[col];
     }
-
-    int L = a.ctx_lens[s];
-    L = min(max(L, 0), a.max_ctx_len);
     const int n_blk_seq = (L + B - 1) / B;
     if (a.n_splits > 1 && blk_lo >= n_blk_seq) return;  // nothing of this sequence falls in the span
     const int blk_hi = min(blk_lo + a.span_blocks, n_blk_seq);
@@ -393,8 +416,8 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const DecodeArgs a)
     const int s = qrow / a.n_q_heads;
     const int c = threadIdx.x;
     const int B = a.block_size;
-    int L = a.ctx_lens[s];
-    L = min(max(L, 0), a.max_ctx_len);
+    int table_row, L;
+    resolve_row(a, s, table_row, L);
     const int n_blk_seq = (L + B - 1) / B;
     const int n_parts = min((n_blk_seq + a.span_blocks - 1) / a.span_blocks, a.n_splits);
     const float *ml = a.ws_ml + static_cast<long long>(qrow) * a.n_splits * 2;
@@ -482,12 +505,16 @@ mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_
     return plan;
 }
 
-int mux_launch_decode_attn(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q,
-                           const int32_t *tables, const int32_t *ctx_lens, int32_t n_seqs, int32_t n_q_heads,
-                           int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len, float scale, void *workspace,
-                           void *stream)
+namespace {
+int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q, const int32_t *tables,
+                const int32_t *ctx_lens, const int32_t *cu_q_lens, const int32_t *q_start, int32_t n_table_seqs,
+                int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len,
+                float scale, void *workspace, void *stream)
 {
     DecodeArgs a{};
+    a.cu_q_lens = cu_q_lens;
+    a.q_start = q_start;
+    a.n_table_seqs = n_table_seqs;
     a.kv_base = pool->kv_base;
     a.block_bytes = pool->block_bytes;
     a.num_blocks = static_cast<int>(pool->num_blocks);
@@ -542,4 +569,27 @@ int mux_launch_decode_attn(const mux_pool *pool, const mux_decode_plan &plan, vo
         if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
     }
     return MUX_OK;
+}
+}  // namespace
+
+int mux_launch_decode_attn(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q,
+                           const int32_t *tables, const int32_t *ctx_lens, int32_t n_seqs, int32_t n_q_heads,
+                           int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len, float scale, void *workspace,
+                           void *stream)
+{
+    return launch_rows(pool, plan, out, q, tables, ctx_lens, nullptr, nullptr, n_seqs, n_seqs, n_q_heads, n_kv_heads,
+                       max_blocks, max_ctx_len, scale, workspace, stream);
+}
+
+// Generic prefill (fp32 pools, block sizes other than 16): every query row is handled as a
+// decode row whose context ends at its own position.  Correct for any supported pool, but it
+// re-reads the keys for every row; the matrix-core kernel covers the hot configuration.
+int mux_launch_prefill_rows_as_decode(const mux_pool *pool, void *out, const void *q, const int32_t *cu_q_lens,
+                                      const int32_t *q_start, const int32_t *tables, int32_t n_seqs, int32_t total_q,
+                                      int32_t max_ctx_len, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks,
+                                      float scale, void *workspace, void *stream)
+{
+    const mux_decode_plan plan = mux_plan_decode(pool, total_q, n_q_heads, n_kv_heads, max_ctx_len);
+    return launch_rows(pool, plan, out, q, tables, nullptr, cu_q_lens, q_start, n_seqs, total_q, n_q_heads, n_kv_heads,
+                       max_blocks, max_ctx_len, scale, workspace, stream);
 }

@@ -179,6 +179,25 @@ def decode_oracle(ls: Lockstep, job: JobState, q: torch.Tensor, scale: float, ro
     return ls.orc.decode_attn(qh, job.tables[rows], lens[rows], job.shape.n_q_heads, scale)
 
 
+def prefill_gpu(ls: Lockstep, job: JobState, q: torch.Tensor, q_lens: np.ndarray, q_start: np.ndarray, scale: float,
+                stream=None) -> torch.Tensor:
+    """q: packed [sum(q_lens)][Hq][d]; the chunk's K/V are already appended."""
+    q_lens, q_start = np.asarray(q_lens, dtype=np.int32), np.asarray(q_start, dtype=np.int32)
+    cu = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
+    out = torch.full_like(q, float("nan"))
+    max_q, max_ctx = int(q_lens.max()), int((q_start + q_lens).max())
+    ws_bytes = mx.mux_prefill_workspace_bytes(ls.lib, job.n_seqs, int(cu[-1]), max_ctx, job.shape.n_q_heads, job.shape.n_kv_heads)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=ls.device) if ws_bytes else None
+    mx.mux_prefill_attn(ls.lib, out, q, torch.from_numpy(cu).to(ls.device), torch.from_numpy(q_start).to(ls.device),
+                        job.tables_dev, max_q, max_ctx, scale, ws, stream=stream)
+    return out
+
+
+def prefill_oracle(ls: Lockstep, job: JobState, q: torch.Tensor, q_lens: np.ndarray, q_start: np.ndarray, scale: float) -> np.ndarray:
+    cu = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
+    return ls.orc.prefill_attn(to_oracle(q), cu, np.asarray(q_start, dtype=np.int32), job.tables, job.shape.n_q_heads, scale)
+
+
 def tolerance(dtype: str) -> float:
     """Max-abs bound against the oracle: 2e-2 for bf16 K/V (the bf16 output rounding alone is
     up to 2^-7 for |o| in [2, 4)), 1e-4 for fp32 K/V; fp32 accumulation on both sides."""

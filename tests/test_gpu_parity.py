@@ -220,3 +220,129 @@ def test_small_decode_configs_every_output(idx):
         err = H.assert_close(got, H.decode_oracle(ls, st, q, H.default_scale(w.head_dim)), "bf16", st.shape.name)
         print("model %s max abs err %.2e" % (st.shape.name, err))
     ls.check_counters()
+
+
+# ---------------------------------------------------------------------------------
+# chunked causal prefill attention
+# ---------------------------------------------------------------------------------
+def _prefill_case(dtype, head_dim, block_size, n_q, n_kv, lens, q_starts, seed, scale=None):
+    """Sequences of `lens` tokens, all K/V appended; the chunk of sequence s is its rows
+    q_starts[s] .. lens[s]-1."""
+    lens, q_starts = np.asarray(lens, np.int32), np.asarray(q_starts, np.int32)
+    need = int(((lens + block_size - 1) // block_size).sum()) * n_kv
+    rng = np.random.Generator(np.random.PCG64(seed))
+    ls = H.Lockstep(need + 64, block_size, head_dim, dtype, wl.placement_order(rng, need + 64))
+    shape = wl.ModelShape("t", n_q, n_kv, head_dim)
+    job = H.open_job(ls, 0, shape, lens.size, int(lens.max()) + block_size)
+    H.extend(ls, job, q_starts, seed=seed * 10 + 1)        # earlier chunks
+    H.extend(ls, job, lens, seed=seed * 10 + 3)            # this chunk's K/V (append before attention)
+    q_lens = lens - q_starts
+    q = H.make_q(ls, job, seed * 10 + 5, n_rows=int(q_lens.sum()))
+    scale = H.default_scale(head_dim) if scale is None else scale
+    got = H.prefill_gpu(ls, job, q, q_lens, q_starts, scale)
+    want = H.prefill_oracle(ls, job, q, q_lens, q_starts, scale)
+    torch.cuda.synchronize()
+    return ls, job, q, got, want
+
+
+@pytest.mark.parametrize("dtype,head_dim,block_size,n_q,n_kv", [
+    ("bf16", 128, 16, 2, 2), ("bf16", 128, 16, 4, 2), ("bf16", 128, 16, 8, 2), ("bf16", 128, 16, 16, 2),
+    ("bf16", 128, 16, 6, 2), ("bf16", 128, 16, 5, 1), ("bf16", 64, 16, 4, 4), ("bf16", 64, 16, 8, 1),
+    ("fp32", 128, 16, 2, 2), ("fp32", 64, 8, 4, 2), ("bf16", 128, 8, 2, 2), ("bf16", 64, 32, 2, 1),
+])
+def test_prefill_matches_oracle_across_shapes(dtype, head_dim, block_size, n_q, n_kv):
+    # fresh prompts and later chunks; lengths around tile (16/32/64) and block boundaries; a 1-row chunk
+    lens =     [1, 15, 16, 17, 31, 33, 64, 65, 130, 200, 257, 300]
+    q_starts = [0,  0,  0,  3,  0, 32,  0, 64,   7, 128, 256, 299]
+    _say("prefill %s d=%d B=%d Hq=%d Hkv=%d" % (dtype, head_dim, block_size, n_q, n_kv))
+    ls, job, q, got, want = _prefill_case(dtype, head_dim, block_size, n_q, n_kv, lens, q_starts, seed=block_size + n_q)
+    err = H.assert_close(got, want, dtype)
+    # first row of a fresh prompt sees one key: it returns V[0] (exactly, even in bf16)
+    g = got.float().cpu().numpy()
+    v0 = np.stack([ls.orc.read_row(job.tables[0, h, 0], 0, 1) for h in range(n_kv)])
+    v0 = torch.from_numpy(v0.view(np.int16) if dtype == "bf16" else v0)
+    v0 = (v0.view(torch.bfloat16) if dtype == "bf16" else v0).float().numpy()
+    assert np.array_equal(g[0], np.repeat(v0, n_q // n_kv, axis=0))
+    print("max abs err %.2e" % err)
+
+
+@pytest.mark.parametrize("chunk", [1, 7, 16, 33, 64, 100])
+def test_chunked_prefill_equals_oracle_and_unchunked(chunk):
+    """Prompts processed in chunks of any size (alloc -> append -> attend per chunk) give the
+    rows an unchunked pass gives."""
+    lens = np.array([19, 150, 77], dtype=np.int32)
+    n_q, n_kv, d = 4, 2, 128
+    rng = np.random.Generator(np.random.PCG64(5))
+    ls = H.Lockstep(512, 16, d, "bf16", wl.placement_order(rng, 512))
+    job = H.open_job(ls, 0, wl.ModelShape("t", n_q, n_kv, d), 3, 160)
+    q_all = wl.randn_values(55, (int(lens.sum()), n_q, d)).cuda()
+    cu_all = np.concatenate([[0], np.cumsum(lens)])
+    got = torch.zeros_like(q_all)
+    done = np.zeros(3, dtype=np.int32)
+    step = 0
+    while (done < lens).any():
+        q_lens = np.minimum(chunk, lens - done).astype(np.int32)
+        H.extend(ls, job, done + q_lens, seed=1000 + step)
+        rows = np.concatenate([np.arange(cu_all[s] + done[s], cu_all[s] + done[s] + q_lens[s]) for s in range(3)])
+        rows_dev = torch.from_numpy(rows).cuda()
+        part = H.prefill_gpu(ls, job, q_all.index_select(0, rows_dev).contiguous(), q_lens, done, 0.09)
+        got.index_copy_(0, rows_dev, part)
+        done = done + q_lens
+        step += 1
+    want = H.prefill_oracle(ls, job, q_all, lens, np.zeros(3, np.int32), 0.09)
+    H.assert_close(got, want, "bf16")
+
+
+def test_prefill_rows_equal_decode_rows_on_gpu():
+    """A prefill row at position p and a decode step with context p+1 and the same query see the
+    same keys; the two kernels agree within the bf16 tolerance of each against the oracle."""
+    ls, job, q, got, want = _prefill_case("bf16", 128, 16, 4, 4, [90], [40], seed=9)
+    for r in (0, 17, 49):
+        dec = H.decode_gpu(ls, job, q[r:r + 1].contiguous(), H.default_scale(128), ctx_lens=np.array([40 + r + 1], np.int32))
+        assert (dec.float() - got[r:r + 1].float()).abs().max().item() <= 2e-2
+
+
+def test_small_config4_prefill_and_decode_share_the_pool():
+    """Shrunk configuration 4: one model runs chunked causal prefill while two others decode,
+    each on its own stream, all in one pool."""
+    w = wl.config(4, small=True)
+    _say("small config 4: %s" % [(j.kind, j.shape.name, j.lens.tolist()) for j in w.jobs])
+    ls = H.Lockstep(w.num_blocks, w.block_size, w.head_dim, "bf16", wl.placement_order(w.rng(), w.num_blocks))
+    pj, dj = w.jobs[0], w.jobs[1:]
+    scale = H.default_scale(w.head_dim)
+    dec_states = []
+    for j in dj:
+        st = H.open_job(ls, j.model_id, j.shape, j.n_seqs, int(j.lens.max()) + 16)
+        H.extend(ls, st, j.lens - 1, seed=w.seed * 100 + j.model_id)
+        dec_states.append(st)
+    pst = H.open_job(ls, pj.model_id, pj.shape, pj.n_seqs, int(pj.lens.max()) + 16)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    torch.cuda.synchronize()
+    # decode steps on two streams
+    dec_out = []
+    for j, st, stream in zip(dj, dec_states, streams[1:]):
+        with torch.cuda.stream(stream):
+            H.extend(ls, st, j.lens, seed=w.seed * 100 + 50 + j.model_id, stream=stream)
+            q = H.make_q(ls, st, w.seed * 100 + 70 + j.model_id)
+            dec_out.append((q, H.decode_gpu(ls, st, q, scale, stream=stream)))
+    # chunked prefill on the third
+    q_all = wl.randn_values(w.seed * 100 + 90, (int(pj.lens.sum()), pj.shape.n_q_heads, w.head_dim)).cuda()
+    cu_all = np.concatenate([[0], np.cumsum(pj.lens)])
+    got = torch.zeros_like(q_all)
+    done = np.zeros(pj.n_seqs, dtype=np.int32)
+    step = 0
+    with torch.cuda.stream(streams[0]):
+        while (done < pj.lens).any():
+            q_lens = np.minimum(pj.chunk, pj.lens - done).astype(np.int32)
+            H.extend(ls, pst, done + q_lens, seed=w.seed * 100 + 200 + step, stream=streams[0])
+            rows = np.concatenate([np.arange(cu_all[s] + done[s], cu_all[s] + done[s] + q_lens[s]) for s in range(pj.n_seqs)])
+            rows_dev = torch.from_numpy(rows).cuda()
+            part = H.prefill_gpu(ls, pst, q_all.index_select(0, rows_dev).contiguous(), q_lens, done, scale, stream=streams[0])
+            got.index_copy_(0, rows_dev, part)
+            done = done + q_lens
+            step += 1
+    torch.cuda.synchronize()
+    H.assert_close(got, H.prefill_oracle(ls, pst, q_all, pj.lens, np.zeros(pj.n_seqs, np.int32), scale), "bf16", "prefill")
+    for st, (q, o) in zip(dec_states, dec_out):
+        H.assert_close(o, H.decode_oracle(ls, st, q, scale), "bf16", st.shape.name)
+    ls.check_counters()
