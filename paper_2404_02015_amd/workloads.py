@@ -229,7 +229,7 @@ def build_tables(alloc: Callable[[int, int], np.ndarray], model_id: int, lens: n
 
 
 def grow_tables(alloc: Callable[[int, int], np.ndarray], model_id: int, tables: np.ndarray,
-                old_lens: np.ndarray, new_lens: np.ndarray, block_size: int) -> np.ndarray:
+                old_lens: np.ndarray, new_lens: np.ndarray, block_size: int, want_changed: bool = True) -> np.ndarray:
     """Extend `tables` in place for sequences growing from old_lens to new_lens tokens.
     One allocator call per sequence that needs blocks, ids head-major as in build_tables.
     Returns the flat indices of the entries that changed."""
@@ -242,7 +242,7 @@ def grow_tables(alloc: Callable[[int, int], np.ndarray], model_id: int, tables: 
             continue
         ids = np.asarray(alloc(model_id, (nb1 - nb0) * n_kv), dtype=np.int32)
         tables[s, :, nb0:nb1] = ids.reshape(n_kv, nb1 - nb0)
-        for h in range(n_kv):
+        for h in range(n_kv if want_changed else 0):
             base = (s * n_kv + h) * max_blocks
             changed.extend(range(base + nb0, base + nb1))
     return np.asarray(changed, dtype=np.int64)

@@ -113,7 +113,7 @@ def extend(ls: Lockstep, job: JobState, new_lens: np.ndarray, seed: int, on_devi
     new_lens = np.asarray(new_lens, dtype=np.int32)
     assert (new_lens >= job.lens).all()
     B, n_kv, d = ls.block_size, job.shape.n_kv_heads, ls.head_dim
-    wl.grow_tables(ls.alloc, job.model_id, job.tables, job.lens, new_lens, B)
+    wl.grow_tables(ls.alloc, job.model_id, job.tables, job.lens, new_lens, B, want_changed=False)
     job.tables_dev.copy_(torch.from_numpy(job.tables))
     add = (new_lens - job.lens).astype(np.int64)
     n_tokens = int(add.sum())
