@@ -37,6 +37,9 @@ from paper_2404_02015_amd import binding as mx  # noqa: E402
 from paper_2404_02015_amd import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per decode_attn launch on configuration 2, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (each scaled by a plain 1 GiB copy in the same run): 567 486 KiB x 2.000 fetched + 512 KiB written.
+MEASURED_TRAFFIC_CFG2 = {"bytes": 567486.0 * 1024 * 2.0 + 512.0 * 1024, "source": "profiles/decode_attn_config2_pmc.md"}
 
 
 class DecodeModel:
@@ -265,7 +268,9 @@ def main() -> int:
         "roofline": {
             "kernel": "decode_attn_kernel (+ decode_combine_kernel), one launch per model per step",
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None, "avg_launch_ms": float(np.mean(durs) * 1e3), "algorithmic_bytes_per_launch": float(np.mean(algo)),
+            "traffic": MEASURED_TRAFFIC_CFG2["bytes"] if args.config == 2 else None,
+            "traffic_source": MEASURED_TRAFFIC_CFG2["source"] if args.config == 2 else None,
+            "avg_launch_ms": float(np.mean(durs) * 1e3), "algorithmic_bytes_per_launch": float(np.mean(algo)),
         },
     }
     if not args.no_cpu_baseline:
