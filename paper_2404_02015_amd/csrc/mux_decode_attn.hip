@@ -138,6 +138,65 @@ __device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &tab
     len = min(max(len, 0), a.max_ctx_len);
 }
 
+// Longest sequence first: workgroups are dispatched in index order and a workgroup's time
+// grows with its context length, so the sequence served in turn r is the one with the r-th
+// longest context (ties by index).  Every workgroup ranks the batch itself from LDS, a few
+// hundred cycles for the batch sizes of a decode step; very large batches keep index order.
+__device__ __forceinline__ int pick_sequence(const DecodeArgs &a, int turn, int tid)
+{
+    if (a.cu_q_lens != nullptr || a.n_seqs <= 1 || a.n_seqs > kMaxRanked) return turn;
+    __shared__ int sm_len[kMaxRanked];
+    __shared__ int sm_pick;
+    for (int t = tid; t < a.n_seqs; t += kThreads) sm_len[t] = min(max(a.ctx_lens[t], 0), a.max_ctx_len);
+    __syncthreads();
+    for (int t = tid; t < a.n_seqs; t += kThreads) {
+        const int lt = sm_len[t];
+        int rank = 0;
+        for (int u = 0; u < a.n_seqs; ++u) {
+            const int lu = sm_len[u];
+            rank += (lu > lt || (lu == lt && u < t)) ? 1 : 0;
+        }
+        if (rank == turn) sm_pick = t;
+    }
+    __syncthreads();
+    return sm_pick;
+}
+
+// Last stage of a workgroup: every wave has left, per query head h, its running max, sum and
+// un-normalised accumulator in LDS; merge the waves and write either the final output row
+// (single span) or this span's partial result.
+template <bool BF16, int D, int GT>
+__device__ __forceinline__ void merge_waves_and_store(const DecodeArgs &a, const float (*sm_acc)[GT][D],
+                                                      const float (*sm_m)[GT], const float (*sm_l)[GT], int tid,
+                                                      int s, int head0, int heads_left, int split)
+{
+    for (int idx = tid; idx < GT * D; idx += kThreads) {
+        const int h = idx / D, c = idx % D;
+        if (h >= heads_left) continue;
+        float mm = sm_m[0][h];
+#pragma unroll
+        for (int k = 1; k < kWaves; ++k) mm = fmaxf(mm, sm_m[k][h]);
+        float o = 0.f, ll = 0.f;
+#pragma unroll
+        for (int k = 0; k < kWaves; ++k) {
+            const float wk = fast_exp2(sm_m[k][h] - mm);
+            o += sm_acc[k][h][c] * wk;
+            ll += sm_l[k][h] * wk;
+        }
+        const long long qrow = static_cast<long long>(s) * a.n_q_heads + head0 + h;
+        if (a.n_splits == 1) {
+            store_out<BF16>(a.out, qrow * D + c, ll > 0.f ? o / ll : 0.f);
+        } else {
+            const long long part = qrow * a.n_splits + split;
+            a.ws_acc[part * D + c] = o;
+            if (c == 0) {
+                a.ws_ml[part * 2] = mm;
+                a.ws_ml[part * 2 + 1] = ll;
+            }
+        }
+    }
+}
+
 // BF16: storage type; D: head size; BS: tokens per block at compile time (0 = run time);
 // GT: query heads of one KV group handled together.
 template <bool BF16, int D, int BS, int GT>
@@ -165,28 +224,7 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     const int kvh = w % a.n_kv_heads;
     const int turn = w / a.n_kv_heads;
 
-    // Longest sequence first: workgroups are dispatched in index order and a workgroup's time
-    // grows with its context length, so the sequence served in turn r is the one with the r-th
-    // longest context (ties by index).  Every workgroup ranks the batch itself from LDS, a few
-    // hundred cycles for the batch sizes of a decode step; very large batches keep index order.
-    int s = turn;
-    if (a.cu_q_lens == nullptr && a.n_seqs > 1 && a.n_seqs <= kMaxRanked) {
-        __shared__ int sm_len[kMaxRanked];
-        __shared__ int sm_pick;
-        for (int t = tid; t < a.n_seqs; t += kThreads) sm_len[t] = min(max(a.ctx_lens[t], 0), a.max_ctx_len);
-        __syncthreads();
-        for (int t = tid; t < a.n_seqs; t += kThreads) {
-            const int lt = sm_len[t];
-            int rank = 0;
-            for (int u = 0; u < a.n_seqs; ++u) {
-                const int lu = sm_len[u];
-                rank += (lu > lt || (lu == lt && u < t)) ? 1 : 0;
-            }
-            if (rank == turn) sm_pick = t;
-        }
-        __syncthreads();
-        s = sm_pick;
-    }
+    const int s = pick_sequence(a, turn, tid);
 
     // Block ids of this wave: block blk_lo + wave + kWaves * j sits in lane j.  The load does
     // not wait for the context length (any entry inside the table row may be read; entries
@@ -381,31 +419,200 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     }
     __syncthreads();
 
-    for (int idx = tid; idx < GT * D; idx += kThreads) {
-        const int h = idx / D, c = idx % D;
-        if (pass * GT + h >= group) continue;
-        float mm = sm_m[0][h];
+    merge_waves_and_store<BF16, D, GT>(a, sm_acc, sm_m, sm_l, tid, s, head0, group - pass * GT, split);
+}
+
+// Grouped-query decode on the matrix cores (bf16 pools, 16-token blocks, groups of >= 4
+// query heads).  With g heads per KV head the vector kernel above would spend g times the
+// arithmetic per byte and go ALU-bound; here the g heads of a group (padded to 16) are the
+// columns of two MFMA contractions per 16-token block, exactly as in the prefill kernel:
+//   S^T = K . Q^T   (v_mfma_f32_16x16x32_bf16, K rows from LDS, Q^T in registers)
+//   O^T = V^T . P^T (v_mfma_f32_16x16x16_bf16; the V^T operand - four tokens of one dim per
+//                    lane - is picked out of the row-major LDS tile with 2-byte reads, which are
+//                    conflict-free; P^T = the S^T registers after softmax)
+// Each wave streams its own blocks (same interleaving, id broadcast and register prefetch as
+// the vector kernel) through a private LDS tile; no barrier is needed inside the loop.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ unsigned pack2_bf16(float x, float y)
+{
+    return static_cast<unsigned>(to_bf16_rne(x)) | (static_cast<unsigned>(to_bf16_rne(y)) << 16);
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void decode_attn_group_kernel(const DecodeArgs a)
+{
+    constexpr int BS = 16, GT = 16;
+    constexpr int KC = D / 32, NT = D / 16;
+    constexpr int KROW = D * 2 + 16;           // padded K row in LDS (bytes)
+    constexpr int TILE = 2 * BS * KROW;        // one wave's K tile + V tile
+    constexpr int PPR = D * 2 / 16;            // 16-byte pieces per token row
+    constexpr int NP = BS * PPR / 64;          // pieces per lane per tile (K; same for V)
+    constexpr int MERGE = kWaves * GT * D * 4 + 2 * kWaves * GT * 4;
+    constexpr int SMEM = kWaves * TILE > MERGE ? kWaves * TILE : MERGE;
+    __shared__ __attribute__((aligned(16))) char smem[SMEM];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+
+    int w = blockIdx.x;
+    const int split = w % a.n_splits;  w /= a.n_splits;
+    const int pass = w % a.n_passes;   w /= a.n_passes;
+    const int kvh = w % a.n_kv_heads;
+    const int turn = w / a.n_kv_heads;
+    const int s = pick_sequence(a, turn, tid);
+
+    const int blk_lo = split * a.span_blocks;
+    int table_row, L;
+    resolve_row(a, s, table_row, L);
+    const int *row = a.tables + (static_cast<long long>(table_row) * a.n_kv_heads + kvh) * a.max_blocks;
+    int my_ids = 0;
+    {
+        const int col = blk_lo + wave + kWaves * lane;
+        if (col < a.max_blocks) my_ids = row[col];
+    }
+    const int n_blk_seq = (L + BS - 1) / BS;
+    if (a.n_splits > 1 && blk_lo >= n_blk_seq) return;
+    const int blk_hi = min(blk_lo + a.span_blocks, n_blk_seq);
+    const int n_mine = blk_hi - blk_lo > wave ? (blk_hi - blk_lo - wave + kWaves - 1) / kWaves : 0;
+
+    const int group = a.n_q_heads / a.n_kv_heads;
+    const int head0 = kvh * group + pass * GT;
+    const int heads_left = group - pass * GT;
+
+    // Q^T operand: lane (g, c) holds dims 32k + 8g .. +8 of head c (surplus columns repeat the last head)
+    bf16x8 qreg[KC];
+    {
+        const int qh = head0 + min(c, heads_left - 1);
+        const char *qrow = static_cast<const char *>(a.q) + (static_cast<long long>(s) * a.n_q_heads + qh) * (D * 2);
 #pragma unroll
-        for (int k = 1; k < kWaves; ++k) mm = fmaxf(mm, sm_m[k][h]);
-        float o = 0.f, ll = 0.f;
+        for (int k = 0; k < KC; ++k)
+            qreg[k] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qrow + (32 * k + 8 * g) * 2));
+    }
+
+    f32x4 acc[NT];
 #pragma unroll
-        for (int k = 0; k < kWaves; ++k) {
-            const float wk = fast_exp2(sm_m[k][h] - mm);
-            o += sm_acc[k][h][c] * wk;
-            ll += sm_l[k][h] * wk;
+    for (int n = 0; n < NT; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = kNegBig, l_run = 0.f;   // of head c; l_run is this lane's share of the sum
+
+    char *ktile = smem + wave * TILE;
+    char *vtile = ktile + BS * KROW;
+
+    auto load_tile = [&](int j, u32x4 (&k)[NP], u32x4 (&v)[NP]) {
+        int id = __builtin_amdgcn_readlane(my_ids, j);
+        id = min(max(id, 0), a.num_blocks - 1);
+        const char *t = a.kv_base + static_cast<long long>(id) * a.block_bytes + static_cast<unsigned>(lane * 16);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) k[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(t + i * 1024));
+#pragma unroll
+        for (int i = 0; i < NP; ++i)
+            v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(t + BS * D * 2 + i * 1024));
+    };
+
+    // n_valid: tokens of this block that belong to the sequence (BS except possibly in the last block)
+    auto consume = [&](const u32x4 (&k)[NP], const u32x4 (&v)[NP], int n_valid) {
+        // registers -> this wave's LDS tile, rows padded so that both access patterns below
+        // are free of bank conflicts
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int piece = lane + 64 * i;
+            const int tok = piece / PPR, pc = piece % PPR;
+            *reinterpret_cast<u32x4 *>(ktile + tok * KROW + pc * 16) = k[i];
+            const u32x4 vv = tok < n_valid ? v[i] : u32x4{0, 0, 0, 0};   // stale slots may hold NaN
+            *reinterpret_cast<u32x4 *>(vtile + tok * KROW + pc * 16) = vv;
         }
-        const long long qrow = static_cast<long long>(s) * a.n_q_heads + head0 + h;
-        if (a.n_splits == 1) {
-            store_out<BF16>(a.out, qrow * D + c, ll > 0.f ? o / ll : 0.f);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        f32x4 st = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KC; ++kk) {
+            const bf16x8 kop =
+                __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(ktile + c * KROW + (32 * kk + 8 * g) * 2));
+            st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[kk], st, 0, 0, 0);
+        }
+        float sc[4];
+        float mx = kNegBig;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float x = st[i] * a.scale_log2e;
+            if (4 * g + i >= n_valid) x = kNegBig;
+            sc[i] = x;
+            mx = fmaxf(mx, x);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = fast_exp2(m_run - m_new);
+        float psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float e = fast_exp2(sc[i] - m_new);
+            if (4 * g + i >= n_valid) e = 0.f;
+            sc[i] = e;
+            psum += e;
+        }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+            for (int n = 0; n < NT; ++n) acc[n] *= alpha;
+        }
+        const u32x2 pw = {pack2_bf16(sc[0], sc[1]), pack2_bf16(sc[2], sc[3])};
+        const s16x4 pop = __builtin_bit_cast(s16x4, pw);
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+            // V^T operand: dim 16n + c of tokens 4g .. 4g+3
+            const unsigned short *vcol = reinterpret_cast<const unsigned short *>(vtile + (4 * g) * KROW) + (16 * n + c);
+            s16x4 vop;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) vop[i] = static_cast<short>(vcol[i * (KROW / 2)]);
+            acc[n] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop, pop, acc[n], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    auto valid_in = [&](int j) { return min(BS, L - (blk_lo + wave + kWaves * j) * BS); };
+
+    if (n_mine > 0) {
+        u32x4 ka[NP], va[NP], kb[NP], vb[NP];
+        load_tile(0, ka, va);
+        int j = 0;
+        for (; j + 2 < n_mine; j += 2) {
+            load_tile(j + 1, kb, vb);
+            consume(ka, va, BS);
+            load_tile(j + 2, ka, va);
+            consume(kb, vb, BS);
+        }
+        if (j + 1 < n_mine) {
+            load_tile(j + 1, kb, vb);
+            consume(ka, va, BS);
+            consume(kb, vb, valid_in(j + 1));
         } else {
-            const long long part = qrow * a.n_splits + split;
-            a.ws_acc[part * D + c] = o;
-            if (c == 0) {
-                a.ws_ml[part * 2] = mm;
-                a.ws_ml[part * 2 + 1] = ll;
-            }
+            consume(ka, va, valid_in(j));
         }
     }
+
+    float l_tot = l_run + __shfl_xor(l_run, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    __syncthreads();   // every wave is done with its tile: the same LDS now carries the merge
+    float (*sm_acc)[GT][D] = reinterpret_cast<float (*)[GT][D]>(smem);
+    float (*sm_m)[GT] = reinterpret_cast<float (*)[GT]>(smem + kWaves * GT * D * 4);
+    float (*sm_l)[GT] = reinterpret_cast<float (*)[GT]>(smem + kWaves * GT * D * 4 + kWaves * GT * 4);
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sm_acc[wave][c][16 * n + 4 * g + i] = acc[n][i];
+    if (g == 0) {
+        sm_m[wave][c] = m_run;
+        sm_l[wave][c] = l_tot;
+    }
+    __syncthreads();
+    merge_waves_and_store<true, D, GT>(a, sm_acc, sm_m, sm_l, tid, s, head0, heads_left, split);
 }
 
 // Merge the spans of one (sequence, query head): thread c owns head dimension c.
@@ -459,6 +666,12 @@ void launch_by_block(int block_size, int gt, const DecodeArgs &a, unsigned grid,
         launch_by_heads<BF16, D, 0>(gt, a, grid, st);
 }
 
+// The matrix-core kernel covers bf16 pools with 16-token blocks and groups of >= 4 query heads.
+bool uses_group_kernel(const mux_pool *pool, int group)
+{
+    return pool->dtype == MUX_BF16 && pool->block_size == 16 && group >= 4;
+}
+
 int env_int(const char *name, int fallback)
 {
     const char *v = std::getenv(name);
@@ -474,6 +687,7 @@ mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_
     const int group = n_q_heads / n_kv_heads;
     int gt = 1;
     while (gt < group && gt < 8) gt *= 2;
+    if (uses_group_kernel(pool, group)) gt = 16;
     plan.heads_per_pass = gt;
     plan.n_passes = (group + gt - 1) / gt;
 
@@ -542,7 +756,11 @@ int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, co
     const bool bf16 = pool->dtype == MUX_BF16;
     const int gt = plan.heads_per_pass;
     const unsigned g = static_cast<unsigned>(grid);
-    if (bf16 && pool->head_dim == 128)
+    if (gt == 16 && pool->head_dim == 128)
+        hipLaunchKernelGGL((decode_attn_group_kernel<128>), dim3(g), dim3(kThreads), 0, st, a);
+    else if (gt == 16 && pool->head_dim == 64)
+        hipLaunchKernelGGL((decode_attn_group_kernel<64>), dim3(g), dim3(kThreads), 0, st, a);
+    else if (bf16 && pool->head_dim == 128)
         launch_by_block<true, 128>(pool->block_size, gt, a, g, st);
     else if (bf16 && pool->head_dim == 64)
         launch_by_block<true, 64>(pool->block_size, gt, a, g, st);
