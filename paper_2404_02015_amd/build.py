@@ -21,7 +21,7 @@ SOURCES = ["mux_api.cpp", "mux_kv_append.hip", "mux_decode_attn.hip", "mux_prefi
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-fvisibility=hidden",
+    "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-inline-asm", "-fvisibility=hidden",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

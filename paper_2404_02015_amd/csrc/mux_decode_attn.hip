@@ -32,6 +32,9 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+#ifndef MUX_GROUP_MIN_WAVES
+#define MUX_GROUP_MIN_WAVES 3
+#endif
 #ifndef MUX_DECODE_MIN_WAVES
 #define MUX_DECODE_MIN_WAVES 1
 #endif
@@ -443,7 +446,7 @@ __device__ __forceinline__ unsigned pack2_bf16(float x, float y)
 }
 
 template <int D>
-__global__ __launch_bounds__(kThreads) void decode_attn_group_kernel(const DecodeArgs a)
+__global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_group_kernel(const DecodeArgs a)
 {
     constexpr int BS = 16, GT = 16;
     constexpr int KC = D / 32, NT = D / 16;

@@ -7,23 +7,33 @@
 //
 // The work is two dense contractions per (query tile, KV tile), so it runs on the matrix cores
 // (v_mfma_f32_16x16x32_bf16), arranged so that no register shuffling sits between them:
-//   S^T = K . Q^T   A = K tile  [16 tokens x 32 dims per instruction, from LDS]
+//   S^T = K . Q^T   A = K tile  [16 tokens x 32 dims per instruction, 16-byte reads from LDS]
 //                   B = Q^T     [held in registers for the whole kernel]
 //                   C = S^T     lane (g, c) holds tokens 4g..4g+3 of query row c
-//   O^T = V^T . P^T A = V^T     [16 dims x 32 tokens, from an LDS copy transposed on store]
+//   O^T = V^T . P^T A = V^T     [16 dims x 32 tokens; ds_read_b64_tr_b16 hands each lane four
+//                                tokens of one dim straight out of the row-major LDS tile]
 //                   B = P^T     = the S^T registers after softmax, rounded to bf16 in place
 //                   C = O^T     lane (g, c) holds dims 4g..4g+3 of query row c
 // Both results keep the query row in the lane's low 4 bits, so the running max / sum of a row
 // and the rescaling of its accumulator never leave the lane group.
 //
-// A workgroup of 4 waves owns one (sequence, kv head) and a tile of 16-row slices: 4 row slices
-// of one head for multi-head attention, or fewer row slices times several query heads of the
-// group for grouped-query attention; all waves share the K/V tiles, which are fetched once per
-// workgroup with coalesced 16-byte loads, double-buffered in LDS, 32 tokens per step.
+// A workgroup of 4 waves owns one (sequence, kv head) and a tile of query-row slices; a wave
+// holds CB column blocks of 16 rows (CB = 2: each K / V^T operand read from LDS feeds two
+// MFMAs).  Multi-head attention: 4 slices of one head; grouped-query attention: several query
+// heads of the group share the K/V tiles.  K/V tiles are fetched once per workgroup, 32 tokens
+// per step, with global_load_lds_dwordx4: 16 bytes per lane go from HBM/L2 straight into LDS,
+// no registers in between, so several steps can be in flight (kBufs LDS buffers) while the
+// matrix cores work on the current one.  Such a load writes the lanes' data contiguously, so
+// rows cannot be padded; bank conflicts are avoided by an XOR swizzle of the 16-byte pieces
+// inside each row, applied on the global side of the copy.  Block ids are cached in LDS up
+// front.  The accumulator is rescaled lazily: the reference maximum of a row only moves
+// when a score exceeds it by more than 2^kLazyBits, so most steps skip the rescale.
 //
 // Pools in fp32 or with a block size other than 16 take a slow generic path (each query row
 // handled like a decode step); see mux_launch_prefill_attn.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "mux_internal.h"
 
@@ -32,14 +42,18 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
-constexpr int kBS = 16;            // tokens per block on this path
-constexpr int kKT = 32;            // tokens per pipeline step (two blocks)
+constexpr int kBS = 16;              // tokens per block on this path
+constexpr int kKT = 32;              // tokens per pipeline step (two blocks)
+constexpr int kMaxCachedIds = 2048;  // block ids kept in LDS (32 768 tokens of context)
+constexpr int kBufs = 3;             // LDS buffers: kBufs - 1 steps are in flight while one is consumed
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -3.0e38f;
+constexpr float kLazyBits = 8.0f;    // softmax weights may reach 2^8 before the row is rescaled
 
 struct PrefillArgs {
     const char *kv_base;
@@ -63,25 +77,77 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b)
     return __builtin_bit_cast(unsigned, v);
 }
 
-// D: head size.  HT: query heads per workgroup (1, 2 or 4); the other kWaves / HT waves take
-// further 16-row slices.
-template <int D, int HT>
-__global__ __launch_bounds__(kThreads) void prefill_attn_kernel(const PrefillArgs a)
+// Maximum over the four lanes l, l^16, l^32, l^48 (the lane groups that share a query row),
+// without a trip through LDS: v_permlane32_swap exchanges the upper half of one register with
+// the lower half of another, v_permlane16_swap the odd 16-lane rows with the even ones; with
+// both registers holding x, the two results hold "x of my half/row" and "x of the other".
+__device__ __forceinline__ float row_max_across_groups(float x)
 {
-    constexpr int RT = kWaves / HT;              // 16-row slices per workgroup
-    constexpr int QT = 16 * RT;                  // query rows per workgroup
+    typedef unsigned u32pair __attribute__((ext_vector_type(2)));
+    const unsigned u = __float_as_uint(x);
+    const u32pair h = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const float y = fmaxf(__uint_as_float(h[0]), __uint_as_float(h[1]));
+    const unsigned v = __float_as_uint(y);
+    const u32pair r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// Transposing LDS read: within each group of 16 lanes, lane i receives element (i % 4) of the
+// four 8-byte chunks addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12 of the group.
+__device__ __forceinline__ u32x2 lds_read_tr16(const char *p)
+{
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+    return __builtin_bit_cast(u32x2, r);
+}
+
+// The K/V tiles travel global -> LDS asynchronously and several of them are meant to stay in
+// flight across workgroup barriers.  The compiler cannot know which LDS buffer an in-flight copy
+// targets and would wait for all of them before every LDS read and every barrier, so the copy,
+// the barrier and the waits of the pipeline are issued by hand; the compiler still orders the
+// ordinary LDS reads and writes it generates itself ("memory" clobbers keep them in place).
+__device__ __forceinline__ void lds_dma16(const void *src, unsigned lds_addr)
+{
+    // every lane's 16 bytes at `src` land at LDS address lds_addr + 16 * lane (lds_addr is wave-uniform)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory", "m0");
+}
+__device__ __forceinline__ void raw_barrier() { asm volatile("s_barrier" ::: "memory"); }
+// s_waitcnt with one counter set and the others left at "do not wait"
+template <int N>
+__device__ __forceinline__ void wait_vmem()   // at most N vector-memory operations (incl. LDS copies) in flight
+{
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8)); }
+
+// D: head size.  HT: query heads per workgroup (1, 2 or 4); the other kWaves / HT waves take
+// further row slices.  CB: 16-row column blocks per wave.
+template <int D, int HT, int CB>
+__global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const PrefillArgs a)
+{
+    constexpr int RS = 16 * CB;                  // query rows per wave
+    constexpr int RT = kWaves / HT;              // row slices per workgroup
+    constexpr int QT = RS * RT;                  // query rows per workgroup
     constexpr int KC = D / 32;                   // 32-dim slabs of the head
     constexpr int NT = D / 16;                   // 16-dim slabs of the output
-    constexpr int KROW = D * 2 + 16;             // bytes per K row in LDS (padded: conflict-free 16-byte reads)
-    constexpr int VROW = kKT * 2 + 16;           // bytes per V^T row in LDS
-    constexpr int KBUF = kKT * KROW;
-    constexpr int VBUF = D * VROW;
+    constexpr int ROWB = D * 2;                  // bytes per token row (unpadded: see the swizzles below)
+    constexpr int KBUF = kKT * ROWB;
+    constexpr int VBUF = kKT * ROWB;
     constexpr int PIECES = kKT * D * 2 / 16;     // 16-byte pieces per K (or V) step
     constexpr int PPT = PIECES / kThreads;       // pieces per thread
     static_assert(PIECES % kThreads == 0, "tile must split evenly over the workgroup");
     constexpr int PPR = D * 2 / 16;              // pieces per token row
+    constexpr int RPC = 256 / ROWB;              // rows per 256-byte sweep over the 64 LDS banks
+    static_assert(PPT == 2 || PPT == 1, "a wave copies whole 1 KiB runs");
+    // Piece p of row r is stored at piece position p ^ swz(r).  For K the 16 lanes of an operand
+    // read take the same piece of 16 different rows: XOR with the row number spreads them over
+    // all banks.  For V a transposing read takes two adjacent pieces of 4 (or 8) consecutive rows:
+    // XOR with twice the row number keeps the pair adjacent and the rows apart.
+    auto kswz = [](int r) { return (r / RPC) % PPR; };
+    auto vswz = [](int r) { return 2 * ((r / RPC) % (PPR / 2)); };
 
-    __shared__ __attribute__((aligned(16))) char smem[2 * (KBUF + VBUF)];
+    __shared__ __attribute__((aligned(16))) char smem[kBufs * (KBUF + VBUF)];
+    __shared__ int sm_ids[kMaxCachedIds];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -103,168 +169,216 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(const PrefillArg
     int kv_end = start + row0 + rows_here;       // keys 0 .. kv_end-1 are visible to the last row
     kv_end = min(kv_end, a.max_blocks * kBS);
     const int n_steps = (kv_end + kKT - 1) / kKT;
+    if (n_steps <= 0) return;
     const int total_len = start + q_len;         // tokens of this sequence that hold real K/V
 
     const int group = a.n_q_heads / a.n_kv_heads;
-    const int slice = wave / HT;                 // which 16-row slice
+    const int slice = wave / HT;                 // which row slice
     const int head_in_group = pass * HT + wave % HT;
     const bool head_ok = head_in_group < group;
     const int head = kvh * group + min(head_in_group, group - 1);
-    const int my_row0 = row0 + slice * 16;       // first chunk row of this wave
+    const int my_row0 = row0 + slice * RS;       // first chunk row of this wave
     const bool wave_active = head_ok && my_row0 < q_len;
-    const int my_row = min(my_row0 + c, q_len - 1);   // clamp: surplus rows repeat the last one
-    const int my_pos = start + my_row;                // absolute position of this lane's row
-    const int wave_last_pos = start + min(my_row0 + 15, q_len - 1);
+    const int wave_first_pos = start + my_row0;
+    const int wave_last_pos = start + min(my_row0 + RS - 1, q_len - 1);
 
-    // Q^T operand: lane (g, c) holds dims 32k + 8g .. +8 of row c, for every slab k
-    bf16x8 qreg[KC];
-    {
-        const char *qrow = static_cast<const char *>(a.q) + (static_cast<long long>(q_lo + my_row) * a.n_q_heads + head) * (D * 2);
+    // Q^T operands: for column block b, lane (g, c) holds dims 32k + 8g .. +8 of row 16b + c
+    bf16x8 qreg[CB][KC];
+    int my_pos[CB];                              // absolute position of this lane's row in block b
+#pragma unroll
+    for (int b = 0; b < CB; ++b) {
+        const int r = min(my_row0 + 16 * b + c, q_len - 1);   // clamp: surplus rows repeat the last one
+        my_pos[b] = start + r;
+        const char *qrow = static_cast<const char *>(a.q) + (static_cast<long long>(q_lo + r) * a.n_q_heads + head) * (D * 2);
 #pragma unroll
         for (int k = 0; k < KC; ++k)
-            qreg[k] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qrow + (32 * k + 8 * g) * 2));
+            qreg[b][k] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qrow + (32 * k + 8 * g) * 2));
     }
 
-    f32x4 acc[NT];
+    f32x4 acc[CB][NT];
+    float m_ref[CB], l_run[CB];                  // reference max (log2 domain) and this lane's share of the row sum
 #pragma unroll
-    for (int n = 0; n < NT; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = kNegBig, l_run = 0.f;          // l_run: this lane's share of the row sum
+    for (int b = 0; b < CB; ++b) {
+        m_ref[b] = kNegBig;
+        l_run[b] = 0.f;
+#pragma unroll
+        for (int n = 0; n < NT; ++n) acc[b][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 
+    // Block ids of the whole key range go to LDS once, so that the K/V loads inside the loop
+    // do not wait for a table load first (contexts past kMaxCachedIds blocks read the table).
     const int *trow = a.tables + (static_cast<long long>(s) * a.n_kv_heads + kvh) * a.max_blocks;
+    const int n_ids = min(min(2 * n_steps, a.max_blocks), kMaxCachedIds);
+    for (int i = tid; i < n_ids; i += kThreads) sm_ids[i] = min(max(trow[i], 0), a.num_blocks - 1);
+    __syncthreads();
 
-    // global -> registers for one step (K and V pieces of two blocks)
-    u32x4 kreg[PPT], vreg[PPT];
-    auto fetch = [&](int step) {
+    // One step's K and V tiles, global -> LDS.  A wave-level load deposits lane l's 16 bytes at
+    // (uniform base) + 16 l, i.e. a contiguous 1 KiB run of the tile; the swizzle decides which
+    // piece of the row the lane fetches.  The step index is clamped so that every iteration
+    // issues the same number of loads and the wait counts below stay exact.
+    const unsigned smem_lds = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) char *)smem));
+    auto issue = [&](int step_raw, int buf) {
+        const int step = min(step_raw, n_steps - 1);
+        const unsigned kb = smem_lds + buf * (KBUF + VBUF);
+        const unsigned vb = kb + KBUF;
 #pragma unroll
         for (int p = 0; p < PPT; ++p) {
-            const int i = tid + kThreads * p;            // piece index inside the 32-token step
-            const int tok = i / PPR;                     // 0..31
+            const int run = wave * PPT + p;              // which 1 KiB run of the tile
+            const int slot = run * 64 + lane;            // 16-byte slot inside the tile
+            const int tok = slot / PPR, pos = slot % PPR;
             const int blk = step * 2 + tok / kBS;
-            int id = blk < a.max_blocks ? trow[blk] : 0;
-            id = min(max(id, 0), a.num_blocks - 1);      // a stale or corrupt entry must not leave the pool
-            const char *src = a.kv_base + static_cast<long long>(id) * a.block_bytes + (tok % kBS) * (D * 2) + (i % PPR) * 16;
-            kreg[p] = *reinterpret_cast<const u32x4 *>(src);
-            vreg[p] = *reinterpret_cast<const u32x4 *>(src + kBS * D * 2);
+            int id;                                      // a stale or corrupt entry must not leave the pool
+            if (blk < n_ids)
+                id = sm_ids[blk];
+            else
+                id = blk < a.max_blocks ? min(max(trow[blk], 0), a.num_blocks - 1) : 0;
+            const char *src = a.kv_base + static_cast<long long>(id) * a.block_bytes + (tok % kBS) * ROWB;
+            lds_dma16(src + (pos ^ kswz(tok)) * 16, kb + run * 1024);
+            lds_dma16(src + kBS * ROWB + (pos ^ vswz(tok)) * 16, vb + run * 1024);
         }
     };
-    // registers -> LDS: K rows as they are, V transposed ([dim][token]); slots past the
-    // sequence's tokens hold stale bytes (possibly NaN) and are zeroed so that 0 * x stays 0
-    auto stage = [&](int step, int buf) {
-        char *kb = smem + buf * (KBUF + VBUF);
-        char *vb = kb + KBUF;
-#pragma unroll
-        for (int p = 0; p < PPT; ++p) {
-            const int i = tid + kThreads * p;
-            const int tok = i / PPR, piece = i % PPR;
-            const bool real = step * kKT + tok < total_len;
-            const u32x4 kk = real ? kreg[p] : u32x4{0, 0, 0, 0};
-            const u32x4 vv = real ? vreg[p] : u32x4{0, 0, 0, 0};
-            *reinterpret_cast<u32x4 *>(kb + tok * KROW + piece * 16) = kk;
-            unsigned short *vt = reinterpret_cast<unsigned short *>(vb + (piece * 8) * VROW + tok * 2);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                vt[(2 * e) * (VROW / 2)] = static_cast<unsigned short>(vv[e] & 0xffffu);
-                vt[(2 * e + 1) * (VROW / 2)] = static_cast<unsigned short>(vv[e] >> 16);
-            }
-        }
-    };
+    constexpr int LPS = 2 * PPT;                         // copies per step per lane
 
-    if (n_steps > 0) fetch(0);
+    wait_vmem<0>();   // q rows and table entries have arrived: from here on only tile copies are in flight
+    for (int t = 0; t < kBufs - 1; ++t) issue(t, t);
     for (int step = 0; step < n_steps; ++step) {
-        const int buf = step & 1;
-        stage(step, buf);
-        if (step + 1 < n_steps) fetch(step + 1);
-        __syncthreads();
+        const int buf = step % kBufs;
+        // this wave's copies for `step` have landed once only the younger steps' copies are in flight
+        wait_vmem<(kBufs - 2) * LPS>();
+        raw_barrier();     // everyone's copies for `step` are in LDS, and everyone is done with step - 1 ...
+        issue(step + kBufs - 1, (step + kBufs - 1) % kBufs);   // ... so its buffer can be refilled
         const int kv0 = step * kKT;
+        if (kv0 + kKT > total_len) {
+            // slots past the sequence's tokens hold stale bytes (possibly NaN): zero those V rows
+            // so that 0 * x stays 0 (their scores are masked: they lie beyond every row's position)
+            char *vz = smem + buf * (KBUF + VBUF) + KBUF;
+            const int first = max(total_len - kv0, 0) * PPR;
+            for (int i = first + tid; i < kKT * PPR; i += kThreads) *reinterpret_cast<u32x4 *>(vz + i * 16) = u32x4{0, 0, 0, 0};
+            wait_lds();
+            raw_barrier();
+        }
         if (wave_active && kv0 <= wave_last_pos) {
             const char *kb = smem + buf * (KBUF + VBUF);
             const char *vb = kb + KBUF;
-            // S^T for the two 16-token halves
-            f32x4 st[2];
+            // S^T for the two 16-token halves and the CB column blocks
+            f32x4 st[CB][2];
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                st[hf] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int k = 0; k < KC; ++k) {
-                    const bf16x8 kop = __builtin_bit_cast(
-                        bf16x8, *reinterpret_cast<const u32x4 *>(kb + (hf * 16 + c) * KROW + (32 * k + 8 * g) * 2));
-                    st[hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[k], st[hf], 0, 0, 0);
-                }
-            }
-            // scale, causal mask (only steps that touch the diagonal), online softmax
-            const bool diag = kv0 + kKT - 1 > start + my_row0;   // wave-uniform
-            float sc[8];
-            float mx = kNegBig;
+            for (int b = 0; b < CB; ++b) st[b][0] = st[b][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float x = st[hf][i] * a.scale_log2e;
-                    if (diag && kv0 + hf * 16 + 4 * g + i > my_pos) x = kNegBig;
-                    sc[hf * 4 + i] = x;
-                    mx = fmaxf(mx, x);
+                for (int k = 0; k < KC; ++k) {
+                    const int kr = hf * 16 + c;
+                    const bf16x8 kop = __builtin_bit_cast(
+                        bf16x8, *reinterpret_cast<const u32x4 *>(kb + kr * ROWB + (((4 * k + g) ^ kswz(kr)) * 16)));
+#pragma unroll
+                    for (int b = 0; b < CB; ++b)
+                        st[b][hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[b][k], st[b][hf], 0, 0, 0);
                 }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            float psum = 0.f;
+            // causal mask (only steps that touch the diagonal; a separate code path, so that the
+            // other steps carry no compares), lazy online softmax
+            bf16x8 pop[CB];
+            auto softmax = [&](auto diag_tag) {
+                constexpr bool DIAG = decltype(diag_tag)::value;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                float e = __builtin_amdgcn_exp2f(sc[j] - m_new);
-                if (diag && sc[j] == kNegBig) e = 0.f;
-                sc[j] = e;
-                psum += e;
-            }
-            l_run = l_run * alpha + psum;
-            m_run = m_new;
-            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+                for (int b = 0; b < CB; ++b) {
+                    float sc[8];
+                    float mx = kNegBig;
 #pragma unroll
-                for (int n = 0; n < NT; ++n) acc[n] *= alpha;
-            }
-            // P^T operand: k-slot j of lane group g is token 4g+j of half 0 (j < 4) or half 1
-            u32x4 pw;
-            pw[0] = pack_bf16(sc[0], sc[1]);
-            pw[1] = pack_bf16(sc[2], sc[3]);
-            pw[2] = pack_bf16(sc[4], sc[5]);
-            pw[3] = pack_bf16(sc[6], sc[7]);
-            const bf16x8 pop = __builtin_bit_cast(bf16x8, pw);
+                    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            float x = st[b][hf][i];
+                            if (DIAG && kv0 + hf * 16 + 4 * g + i > my_pos[b]) x = kNegBig;
+                            sc[hf * 4 + i] = x;
+                            mx = fmaxf(mx, x);
+                        }
+                    mx = row_max_across_groups(mx);
+                    mx *= a.scale_log2e;                       // scale > 0: the max commutes with it
+                    if (__builtin_amdgcn_ballot_w64(mx > m_ref[b] + kLazyBits) != 0) {
+                        const float m_new = fmaxf(m_ref[b], mx);
+                        const float alpha = __builtin_amdgcn_exp2f(m_ref[b] - m_new);
+                        l_run[b] *= alpha;
+#pragma unroll
+                        for (int n = 0; n < NT; ++n) acc[b][n] *= alpha;
+                        m_ref[b] = m_new;
+                    }
+                    float psum = 0.f;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[j], a.scale_log2e, -m_ref[b]));
+                        if (DIAG && sc[j] == kNegBig) e = 0.f;
+                        sc[j] = e;
+                        psum += e;
+                    }
+                    l_run[b] += psum;
+                    // P^T operand: k-slot j of lane group g is token 4g+j of half 0 (j < 4) or half 1
+                    const u32x4 pw = {pack_bf16(sc[0], sc[1]), pack_bf16(sc[2], sc[3]), pack_bf16(sc[4], sc[5]),
+                                      pack_bf16(sc[6], sc[7])};
+                    pop[b] = __builtin_bit_cast(bf16x8, pw);
+                }
+            };
+            if (kv0 + kKT - 1 > wave_first_pos)   // wave-uniform
+                softmax(std::true_type{});
+            else
+                softmax(std::false_type{});
 #pragma unroll
             for (int n = 0; n < NT; ++n) {
-                const char *vrow = vb + (16 * n + c) * VROW + (4 * g) * 2;
-                const u32x2 lo = *reinterpret_cast<const u32x2 *>(vrow);        // tokens 4g..4g+3 of half 0
-                const u32x2 hi = *reinterpret_cast<const u32x2 *>(vrow + 32);   // same of half 1
+                // V^T operand: lane (g, j) points at dims 16n + 4(j%4) .. +3 of token 4g + j/4; the
+                // transposing read returns dim 16n + c of tokens 4g .. 4g+3 to lane (g, c)
+                const int vr = 4 * g + (c >> 2);                        // row inside a half; halves are 16 rows apart,
+                const int vpiece = (2 * n + ((c & 3) >> 1)) ^ vswz(vr);  // which leaves the swizzle unchanged
+                const char *vsrc = vb + vr * ROWB + vpiece * 16 + (c & 1) * 8;
+                const u32x2 lo = lds_read_tr16(vsrc);                 // half 0
+                const u32x2 hi = lds_read_tr16(vsrc + 16 * ROWB);     // half 1
                 const bf16x8 vop = __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], hi[0], hi[1]});
-                acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop, acc[n], 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < CB; ++b)
+                    acc[b][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop[b], acc[b][n], 0, 0, 0);
             }
         }
     }
 
+    wait_vmem<0>();   // the clamped copies issued past the last step must land before the LDS is given back
     if (!wave_active) return;
-    float l_tot = l_run + __shfl_xor(l_run, 16);
-    l_tot += __shfl_xor(l_tot, 32);
-    if (my_row0 + c >= q_len) return;            // surplus row of a ragged tile
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    char *orow = static_cast<char *>(a.out) + (static_cast<long long>(q_lo + my_row) * a.n_q_heads + head) * (D * 2);
 #pragma unroll
-    for (int n = 0; n < NT; ++n) {
-        u32x2 o;
-        o[0] = pack_bf16(acc[n][0] * inv, acc[n][1] * inv);
-        o[1] = pack_bf16(acc[n][2] * inv, acc[n][3] * inv);
-        *reinterpret_cast<u32x2 *>(orow + (16 * n + 4 * g) * 2) = o;   // dims 16n+4g .. +3 of this row
+    for (int b = 0; b < CB; ++b) {
+        float l_tot = l_run[b] + __shfl_xor(l_run[b], 16);
+        l_tot += __shfl_xor(l_tot, 32);
+        const int r = my_row0 + 16 * b + c;
+        if (r >= q_len) continue;                // surplus row of a ragged tile
+        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        char *orow = static_cast<char *>(a.out) + (static_cast<long long>(q_lo + r) * a.n_q_heads + head) * (D * 2);
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+            u32x2 o;
+            o[0] = pack_bf16(acc[b][n][0] * inv, acc[b][n][1] * inv);
+            o[1] = pack_bf16(acc[b][n][2] * inv, acc[b][n][3] * inv);
+            *reinterpret_cast<u32x2 *>(orow + (16 * n + 4 * g) * 2) = o;   // dims 16n+4g .. +3 of this row
+        }
     }
 }
 
-template <int D, int HT>
-void launch_mfma(const PrefillArgs &a, int max_q_len, hipStream_t st, PrefillArgs &scratch)
+template <int D, int HT, int CB>
+void launch_mfma(PrefillArgs a, int max_q_len, hipStream_t st)
 {
-    constexpr int QT = 16 * (kWaves / HT);
-    scratch = a;
-    scratch.n_row_tiles = (max_q_len + QT - 1) / QT;
+    constexpr int QT = 16 * CB * (kWaves / HT);
+    a.n_row_tiles = (max_q_len + QT - 1) / QT;
     const int group = a.n_q_heads / a.n_kv_heads;
-    scratch.n_passes = (group + HT - 1) / HT;
-    const long long grid = static_cast<long long>(scratch.n_row_tiles) * a.n_seqs * a.n_kv_heads * scratch.n_passes;
-    hipLaunchKernelGGL((prefill_attn_kernel<D, HT>), dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, st, scratch);
+    a.n_passes = (group + HT - 1) / HT;
+    const long long grid = static_cast<long long>(a.n_row_tiles) * a.n_seqs * a.n_kv_heads * a.n_passes;
+    hipLaunchKernelGGL((prefill_attn_kernel<D, HT, CB>), dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, st, a);
+}
+
+template <int D, int CB>
+void launch_by_heads(int ht, const PrefillArgs &a, int max_q_len, hipStream_t st)
+{
+    if (ht == 4)
+        launch_mfma<D, 4, CB>(a, max_q_len, st);
+    else if (ht == 2)
+        launch_mfma<D, 2, CB>(a, max_q_len, st);
+    else
+        launch_mfma<D, 1, CB>(a, max_q_len, st);
 }
 
 }  // namespace
@@ -302,19 +416,18 @@ int mux_launch_prefill_attn(const mux_pool *pool, void *out, const void *q, cons
     a.scale_log2e = scale * kLog2e;
     const int group = n_q_heads / n_kv_heads;
     const int ht = group >= 4 ? 4 : (group >= 2 ? 2 : 1);
-    const long long rows_per_wg = 16 * (kWaves / ht);
+    // two column blocks per wave once the chunks are long enough to fill them
+    const int cb = max_q_len >= 32 * (kWaves / ht) ? 2 : 1;
+    const long long rows_per_wg = 16 * cb * (kWaves / ht);
     const long long grid = ((max_q_len + rows_per_wg - 1) / rows_per_wg) * n_seqs * n_kv_heads * ((group + ht - 1) / ht);
     if (grid > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    PrefillArgs launched;
     if (pool->head_dim == 128) {
-        if (ht == 4) launch_mfma<128, 4>(a, max_q_len, st, launched);
-        else if (ht == 2) launch_mfma<128, 2>(a, max_q_len, st, launched);
-        else launch_mfma<128, 1>(a, max_q_len, st, launched);
+        if (cb == 2) launch_by_heads<128, 2>(ht, a, max_q_len, st);
+        else launch_by_heads<128, 1>(ht, a, max_q_len, st);
     } else if (pool->head_dim == 64) {
-        if (ht == 4) launch_mfma<64, 4>(a, max_q_len, st, launched);
-        else if (ht == 2) launch_mfma<64, 2>(a, max_q_len, st, launched);
-        else launch_mfma<64, 1>(a, max_q_len, st, launched);
+        if (cb == 2) launch_by_heads<64, 2>(ht, a, max_q_len, st);
+        else launch_by_heads<64, 1>(ht, a, max_q_len, st);
     } else {
         return MUX_ERR_UNSUPPORTED;
     }
