@@ -33,6 +33,7 @@
 // handled like a decode step); see mux_launch_prefill_attn.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <type_traits>
 
 #include "mux_internal.h"
@@ -49,8 +50,11 @@ constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kBS = 16;              // tokens per block on this path
 constexpr int kKT = 32;              // tokens per pipeline step (two blocks)
-constexpr int kMaxCachedIds = 2048;  // block ids kept in LDS (32 768 tokens of context)
-constexpr int kBufs = 3;             // LDS buffers: kBufs - 1 steps are in flight while one is consumed
+constexpr int kMaxCachedIds = 1024;  // block ids kept in LDS (16 384 tokens of context)
+#ifndef MUX_PREFILL_BUFS
+#define MUX_PREFILL_BUFS 4
+#endif
+constexpr int kBufs = MUX_PREFILL_BUFS;  // LDS buffers: kBufs - 1 steps are in flight while one is consumed
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -3.0e38f;
 constexpr float kLazyBits = 8.0f;    // softmax weights may reach 2^8 before the row is rescaled
@@ -67,6 +71,7 @@ struct PrefillArgs {
     int n_seqs, total_q, n_q_heads, n_kv_heads, max_blocks;
     int n_row_tiles;   // ceil(max_q_len / rows per workgroup)
     int n_passes;      // head passes per kv head
+    int tile_bundle;   // row tiles of one unit dispatched back to back (see the kernel's blockIdx mapping)
     float scale_log2e;
 };
 
@@ -146,19 +151,34 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const Prefill
     auto kswz = [](int r) { return (r / RPC) % PPR; };
     auto vswz = [](int r) { return 2 * ((r / RPC) % (PPR / 2)); };
 
-    __shared__ __attribute__((aligned(16))) char smem[kBufs * (KBUF + VBUF)];
-    __shared__ int sm_ids[kMaxCachedIds];
+    // dynamic LDS (the launcher sizes it): kBufs tile buffers, then the block-id cache
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int *sm_ids = reinterpret_cast<int *>(smem + kBufs * (KBUF + VBUF));
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c = lane & 15;
 
-    // blockIdx -> (row tile, sequence, kv head, pass); later row tiles (more keys) first
-    int w = blockIdx.x;
+    // blockIdx -> (sequence, kv head, pass, row tile).  Two concerns shape the order.  Balance:
+    // later row tiles see more keys, so they must be dispatched first.  L2 reuse: workgroups go
+    // to the 8 XCDs round-robin and every XCD has its own L2, so row tiles that read the same
+    // K/V (same sequence, kv head, pass) should sit on ONE XCD and run at the same time.  Hence:
+    // row tiles are taken in bundles of a.tile_bundle, heaviest bundle first; within a bundle all
+    // (sequence, head, pass) units are listed, each unit's tiles in consecutive slots of the XCD
+    // that owns the unit.  Small launches use bundles of 1 (pure heaviest-first: the tail of the
+    // launch matters most), large ones bundle all tiles of a unit (L2 reuse matters most).
+    constexpr int kXcds = 8;
+    const int kPair = a.tile_bundle;
+    const int n_units = a.n_seqs * a.n_kv_heads * a.n_passes;
+    const int units_per_xcd = (n_units + kXcds - 1) / kXcds;
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int pair = slot / (units_per_xcd * kPair), rem = slot % (units_per_xcd * kPair);
+    const int tile = a.n_row_tiles - 1 - (pair * kPair + rem % kPair);
+    int w = (rem / kPair) * kXcds + xcd;   // which (sequence, kv head, pass)
+    if (tile < 0 || w >= n_units) return;
     const int pass = w % a.n_passes;      w /= a.n_passes;
     const int kvh = w % a.n_kv_heads;     w /= a.n_kv_heads;
-    const int s = w % a.n_seqs;           w /= a.n_seqs;
-    const int tile = a.n_row_tiles - 1 - w;
+    const int s = w;
 
     const int q_lo = a.cu_q_lens[s];
     const int q_len = min(a.cu_q_lens[s + 1], a.total_q) - q_lo;   // never past the packed q / out
@@ -366,8 +386,16 @@ void launch_mfma(PrefillArgs a, int max_q_len, hipStream_t st)
     a.n_row_tiles = (max_q_len + QT - 1) / QT;
     const int group = a.n_q_heads / a.n_kv_heads;
     a.n_passes = (group + HT - 1) / HT;
-    const long long grid = static_cast<long long>(a.n_row_tiles) * a.n_seqs * a.n_kv_heads * a.n_passes;
-    hipLaunchKernelGGL((prefill_attn_kernel<D, HT, CB>), dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, st, a);
+    const long long units = static_cast<long long>(a.n_seqs) * a.n_kv_heads * a.n_passes;
+    // 2 workgroups fit a CU; with fewer than ~4 rounds of workgroups balance beats L2 reuse
+    a.tile_bundle = units * a.n_row_tiles <= 4 * 2 * 256 ? 1 : a.n_row_tiles;
+    const long long bundles = (a.n_row_tiles + a.tile_bundle - 1) / a.tile_bundle;
+    const long long grid = (units + 7) / 8 * 8 * bundles * a.tile_bundle;   // see the blockIdx mapping in the kernel
+    constexpr int kLds = kBufs * 2 * kKT * D * 2 + kMaxCachedIds * 4;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_attn_kernel<D, HT, CB>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    (void)attr;   // more than 64 KiB of LDS per workgroup has to be granted once per kernel
+    hipLaunchKernelGGL((prefill_attn_kernel<D, HT, CB>), dim3(static_cast<unsigned>(grid)), dim3(kThreads), kLds, st, a);
 }
 
 template <int D, int CB>
@@ -417,9 +445,10 @@ int mux_launch_prefill_attn(const mux_pool *pool, void *out, const void *q, cons
     const int group = n_q_heads / n_kv_heads;
     const int ht = group >= 4 ? 4 : (group >= 2 ? 2 : 1);
     // two column blocks per wave once the chunks are long enough to fill them
-    const int cb = max_q_len >= 32 * (kWaves / ht) ? 2 : 1;
+    static const int forced_cb = std::getenv("MUX_PREFILL_CB") ? std::atoi(std::getenv("MUX_PREFILL_CB")) : 0;
+    const int cb = forced_cb ? forced_cb : (max_q_len >= 32 * (kWaves / ht) ? 2 : 1);
     const long long rows_per_wg = 16 * cb * (kWaves / ht);
-    const long long grid = ((max_q_len + rows_per_wg - 1) / rows_per_wg) * n_seqs * n_kv_heads * ((group + ht - 1) / ht);
+    const long long grid = ((max_q_len + rows_per_wg - 1) / rows_per_wg + 1) * (static_cast<long long>(n_seqs) * n_kv_heads * ((group + ht - 1) / ht) + 7);
     if (grid > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (pool->head_dim == 128) {
