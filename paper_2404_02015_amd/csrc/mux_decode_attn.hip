@@ -431,14 +431,36 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
 // columns of two MFMA contractions per 16-token block, exactly as in the prefill kernel:
 //   S^T = K . Q^T   (v_mfma_f32_16x16x32_bf16, K rows from LDS, Q^T in registers)
 //   O^T = V^T . P^T (v_mfma_f32_16x16x16_bf16; the V^T operand - four tokens of one dim per
-//                    lane - is picked out of the row-major LDS tile with 2-byte reads, which are
-//                    conflict-free; P^T = the S^T registers after softmax)
+//                    lane - comes out of the row-major LDS tile through the transposing read
+//                    ds_read_b64_tr_b16; P^T = the S^T registers after softmax)
 // Each wave streams its own blocks (same interleaving, id broadcast and register prefetch as
 // the vector kernel) through a private LDS tile; no barrier is needed inside the loop.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+// Maximum over the four lanes l, l^16, l^32, l^48 without a trip through LDS: with both
+// operands holding x, v_permlane32_swap / v_permlane16_swap leave "x of my half / row" in one
+// result and "x of the other half / row" in the other.
+__device__ __forceinline__ float row_max_across_groups(float x)
+{
+    typedef unsigned u32pair __attribute__((ext_vector_type(2)));
+    const unsigned u = __float_as_uint(x);
+    const u32pair h = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const float y = fmaxf(__uint_as_float(h[0]), __uint_as_float(h[1]));
+    const unsigned v = __float_as_uint(y);
+    const u32pair r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// Transposing LDS read: within each group of 16 lanes, lane i receives element (i % 4) of the
+// four 8-byte chunks addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12 of the group.
+__device__ __forceinline__ s16x4 lds_read_tr16(const char *p)
+{
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+}
 
 __device__ __forceinline__ unsigned pack2_bf16(float x, float y)
 {
@@ -451,7 +473,8 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
     constexpr int BS = 16, GT = 16;
     constexpr int KC = D / 32, NT = D / 16;
     constexpr int KROW = D * 2 + 16;           // padded K row in LDS (bytes)
-    constexpr int TILE = 2 * BS * KROW;        // one wave's K tile + V tile
+    constexpr int VROW = D * 2 + 32;           // padded V row in LDS: keeps the transposing reads conflict-free
+    constexpr int TILE = BS * KROW + BS * VROW;  // one wave's K tile + V tile
     constexpr int PPR = D * 2 / 16;            // 16-byte pieces per token row
     constexpr int NP = BS * PPR / 64;          // pieces per lane per tile (K; same for V)
     constexpr int MERGE = kWaves * GT * D * 4 + 2 * kWaves * GT * 4;
@@ -526,7 +549,7 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
             const int tok = piece / PPR, pc = piece % PPR;
             *reinterpret_cast<u32x4 *>(ktile + tok * KROW + pc * 16) = k[i];
             const u32x4 vv = tok < n_valid ? v[i] : u32x4{0, 0, 0, 0};   // stale slots may hold NaN
-            *reinterpret_cast<u32x4 *>(vtile + tok * KROW + pc * 16) = vv;
+            *reinterpret_cast<u32x4 *>(vtile + tok * VROW + pc * 16) = vv;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -547,8 +570,7 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
             sc[i] = x;
             mx = fmaxf(mx, x);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = row_max_across_groups(mx);
         const float m_new = fmaxf(m_run, mx);
         const float alpha = fast_exp2(m_run - m_new);
         float psum = 0.f;
@@ -569,11 +591,9 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
         const s16x4 pop = __builtin_bit_cast(s16x4, pw);
 #pragma unroll
         for (int n = 0; n < NT; ++n) {
-            // V^T operand: dim 16n + c of tokens 4g .. 4g+3
-            const unsigned short *vcol = reinterpret_cast<const unsigned short *>(vtile + (4 * g) * KROW) + (16 * n + c);
-            s16x4 vop;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) vop[i] = static_cast<short>(vcol[i * (KROW / 2)]);
+            // V^T operand: lane (g, j) points at dims 16n + 4(j%4) .. +3 of token 4g + j/4; the
+            // transposing read hands dim 16n + c of tokens 4g .. 4g+3 to lane (g, c)
+            const s16x4 vop = lds_read_tr16(vtile + (4 * g + (c >> 2)) * VROW + (16 * n + 4 * (c & 3)) * 2);
             acc[n] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop, pop, acc[n], 0, 0, 0);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
