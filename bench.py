@@ -45,7 +45,7 @@ MEASURED_TRAFFIC_CFG2 = {"bytes": 567486.0 * 1024 * 2.0 + 512.0 * 1024, "source"
 class DecodeModel:
     """Device state of one colocated model: tables, lengths, per-step inputs, its stream."""
 
-    def __init__(self, pool, job: wl.ModelJob, block_size: int, total_steps: int, seed: int, device: str):
+    def __init__(self, pool, job: wl.ModelJob, block_size: int, total_steps: int, seed: int, device: str, bank=None):
         self.pool, self.job, self.B = pool, job, block_size
         self.shape = job.shape
         self.n = job.n_seqs
@@ -61,14 +61,21 @@ class DecodeModel:
                                       block_size, self.max_blocks)
         self.tables_dev = torch.from_numpy(self.tables).to(device)
         # history K/V ~ N(0,1), drawn on the device sequence by sequence and appended
-        for s0 in range(0, self.n, 8):
-            s1 = min(self.n, s0 + 8)
+        per_call = 8 if bank is None else 2
+        for s0 in range(0, self.n, per_call):
+            s1 = min(self.n, s0 + per_call)
             cnt = self.lens[s0:s1].astype(np.int64)
             nt = int(cnt.sum())
             if nt == 0:
                 continue
-            k = torch.randn(nt, n_kv, d, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
-            v = torch.randn(nt, n_kv, d, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+            if bank is None:
+                k = torch.randn(nt, n_kv, d, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+                v = torch.randn(nt, n_kv, d, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+            else:  # slices of a pre-drawn bank of N(0,1) values (tens of GB of fresh normals would take minutes)
+                need = nt * n_kv * d
+                off = ((seed + s0) * 7919) % (bank[0].numel() - need)
+                off -= off % 8
+                k, v = bank[0][off:off + need].view(nt, n_kv, d), bank[1][off:off + need].view(nt, n_kv, d)
             seq = np.repeat(np.arange(s0, s1, dtype=np.int32), cnt)
             pos = (np.arange(nt, dtype=np.int64) - np.repeat(np.cumsum(cnt) - cnt, cnt)).astype(np.int32)
             mx.mux_kv_append(pool, k, v, torch.from_numpy(seq).to(device), torch.from_numpy(pos).to(device),
@@ -81,15 +88,21 @@ class DecodeModel:
         self.out = torch.empty(self.n, n_q, d, device=device, dtype=torch.bfloat16)
         self.tok_seq = torch.arange(self.n, dtype=torch.int32, device=device)
         # row 0: position of the token appended this step, row 1: context length after the append
-        self.pos_len = torch.stack([torch.from_numpy(self.lens - 1), torch.from_numpy(self.lens)]).to(device).contiguous()
+        # per step: positions of the appended tokens and context lengths after the append (known
+        # in advance: every sequence grows by one token per step), so no kernel has to bump them
+        steps = np.arange(1, total_steps + 1, dtype=np.int32)[:, None]
+        self.pos_steps = torch.from_numpy(self.lens[None, :] + steps - 1).to(device)
+        self.len_steps = torch.from_numpy(self.lens[None, :] + steps).to(device)
+        self.pos_len = torch.stack([self.pos_steps[0] - 1, self.len_steps[0] - 1]).contiguous()   # state before step 0
         max_final = int(job.lens.max()) + total_steps + 1
         ws = mx.mux_decode_workspace_bytes(pool, self.n, n_q, n_kv, max_final)
         self.workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=device)
-        # pinned staging ring for table patches (ids are written here by mux_alloc_blocks itself)
+        # pinned staging ring for table patches: per step [flat table indices | ids], the ids written
+        # there by mux_alloc_blocks itself; one host-to-device copy per step
         cap = self.n * n_kv
-        self.pin_ids = torch.empty(total_steps, cap, dtype=torch.int32, pin_memory=True)
-        self.pin_idx = torch.empty(total_steps, cap, dtype=torch.int64, pin_memory=True)
-        self.pin_ids_np, self.pin_idx_np = self.pin_ids.numpy(), self.pin_idx.numpy()
+        self.pin_patch = torch.empty(total_steps, 2 * cap, dtype=torch.int32, pin_memory=True)
+        self.pin_patch_np = self.pin_patch.numpy()
+        assert self.n * n_kv * self.max_blocks < 2 ** 31
         self.flat_tables = self.tables_dev.view(-1)
         self.head_base = (np.arange(n_kv, dtype=np.int64) * self.max_blocks)
         self.scale = 1.0 / math.sqrt(d)
@@ -108,18 +121,17 @@ class DecodeModel:
         crossing = np.nonzero((new_lens - 1) % self.B == 0)[0]
         with torch.cuda.stream(self.stream):
             if crossing.size:
-                cnt = 0
+                # new blocks: ids from the block manager (written straight into pinned memory), then
+                # one host-to-device copy and a scatter into the device table
+                cnt, total = 0, int(crossing.size) * n_kv
                 for s in crossing:
-                    ids = self.pin_ids_np[i, cnt:cnt + n_kv]
-                    mx.mux_alloc_blocks(self.pool, self.job.model_id, n_kv, ids)
+                    mx.mux_alloc_blocks(self.pool, self.job.model_id, n_kv, self.pin_patch_np[i, total + cnt:total + cnt + n_kv])
                     col = int(new_lens[s] - 1) // self.B
-                    self.pin_idx_np[i, cnt:cnt + n_kv] = (int(s) * n_kv * self.max_blocks + col) + self.head_base
+                    self.pin_patch_np[i, cnt:cnt + n_kv] = (int(s) * n_kv * self.max_blocks + col) + self.head_base
                     cnt += n_kv
-                idx_dev = self.pin_idx[i, :cnt].to(self.device, non_blocking=True)
-                ids_dev = self.pin_ids[i, :cnt].to(self.device, non_blocking=True)
-                self.flat_tables.index_copy_(0, idx_dev, ids_dev)
-            self.pos_len.add_(1)
-            mx.mux_kv_append(self.pool, self.k_steps[i], self.v_steps[i], self.tok_seq, self.pos_len[0], self.tables_dev,
+                patch = self.pin_patch[i, :2 * total].to(self.device, non_blocking=True)
+                self.flat_tables.index_put_((patch[:total],), patch[total:])
+            mx.mux_kv_append(self.pool, self.k_steps[i], self.v_steps[i], self.tok_seq, self.pos_steps[i], self.tables_dev,
                              stream=self.stream)
             max_ctx = int(new_lens.max())
             if after is not None:
@@ -127,7 +139,7 @@ class DecodeModel:
             e0, e1 = torch.cuda.Event(enable_timing=record), torch.cuda.Event(enable_timing=record)
             if record:
                 e0.record(self.stream)
-            mx.mux_decode_attn(self.pool, self.out, self.q_steps[i], self.tables_dev, self.pos_len[1], max_ctx, self.scale,
+            mx.mux_decode_attn(self.pool, self.out, self.q_steps[i], self.tables_dev, self.len_steps[i], max_ctx, self.scale,
                                self.workspace, stream=self.stream)
             e1.record(self.stream)
             if record:
@@ -136,17 +148,98 @@ class DecodeModel:
         return int(new_lens.astype(np.int64).sum()) * self.kv_bytes_per_token, e1
 
 
+class PrefillModel:
+    """A model running chunked causal prefill on its own stream.  All prompts are processed chunk
+    by chunk; benchmark step i runs chunk stage i mod n_stages (append the chunk's K/V, then
+    attend), so the cycle of stages repeats over the step loop."""
+
+    def __init__(self, pool, job: wl.ModelJob, block_size: int, seed: int, device: str):
+        self.pool, self.job, self.B, self.shape = pool, job, block_size, job.shape
+        n_kv, n_q, d = self.shape.n_kv_heads, self.shape.n_q_heads, self.shape.head_dim
+        lens = job.lens.astype(np.int32)
+        self.stream = torch.cuda.Stream()
+        self.scale = 1.0 / math.sqrt(d)
+        max_blocks = wl.max_blocks_for(lens, block_size)
+        tables = wl.build_tables(lambda m, k: mx.mux_alloc_blocks(pool, m, k), job.model_id, lens, n_kv, block_size, max_blocks)
+        self.tables_dev = torch.from_numpy(tables).to(device)
+        g = torch.Generator(device=device)
+        g.manual_seed(seed)
+        self.stages = []
+        done = np.zeros(lens.size, dtype=np.int32)
+        while (done < lens).any():
+            ql = np.minimum(job.chunk, lens - done).astype(np.int32)
+            cu = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
+            nt = int(cu[-1])
+            seq = np.repeat(np.arange(lens.size, dtype=np.int32), ql)
+            pos = (np.repeat(done, ql) + np.arange(nt) - np.repeat(cu[:-1], ql)).astype(np.int32)
+            flops = sum(n_q * 4 * d * (int(ql[i]) * int(done[i]) + int(ql[i]) * (int(ql[i]) + 1) // 2) for i in range(lens.size))
+            st = {
+                "k": torch.randn(nt, n_kv, d, generator=g, device=device).to(torch.bfloat16),
+                "v": torch.randn(nt, n_kv, d, generator=g, device=device).to(torch.bfloat16),
+                "q": torch.randn(nt, n_q, d, generator=g, device=device).to(torch.bfloat16),
+                "seq": torch.from_numpy(seq).to(device), "pos": torch.from_numpy(pos).to(device),
+                "cu": torch.from_numpy(cu).to(device), "start": torch.from_numpy(done.copy()).to(device),
+                "max_q": int(ql.max()), "max_ctx": int((done + ql).max()), "flops": flops,
+                "kv_bytes": int((done + ql)[ql > 0].astype(np.int64).sum()) * 2 * n_kv * d * 2,
+            }
+            st["out"] = torch.empty_like(st["q"])
+            self.stages.append(st)
+            done = done + ql
+        # the first pass over the stages fills the cache (later stages read earlier chunks)
+        for st in self.stages:
+            mx.mux_kv_append(pool, st["k"], st["v"], st["seq"], st["pos"], self.tables_dev)
+        torch.cuda.synchronize()
+        self.step_no = 0
+        self.events = []
+
+    def step(self, record: bool):
+        st = self.stages[self.step_no % len(self.stages)]
+        self.step_no += 1
+        with torch.cuda.stream(self.stream):
+            mx.mux_kv_append(self.pool, st["k"], st["v"], st["seq"], st["pos"], self.tables_dev, stream=self.stream)
+            e0, e1 = torch.cuda.Event(enable_timing=record), torch.cuda.Event(enable_timing=record)
+            if record:
+                e0.record(self.stream)
+            mx.mux_prefill_attn(self.pool, st["out"], st["q"], st["cu"], st["start"], self.tables_dev, st["max_q"],
+                                st["max_ctx"], self.scale, None, stream=self.stream)
+            if record:
+                e1.record(self.stream)
+                self.events.append((e0, e1, st["flops"], st["kv_bytes"]))
+
+
 def build_workload(cfg_index: int, total_steps: int, device: str = "cuda"):
+    """Pool, decode models and (configuration 4) the prefill model of one configuration."""
     w = wl.config(cfg_index)
     decode_jobs = [j for j in w.jobs if j.kind == "decode"]
+    prefill_jobs = [j for j in w.jobs if j.kind == "prefill"]
     growth = sum(j.n_seqs * j.shape.n_kv_heads * (total_steps // w.block_size + 2) for j in decode_jobs)
-    num_blocks = max(w.num_blocks, w.demand_blocks() + growth)
     block_bytes = 2 * w.block_size * w.head_dim * 2
+    bank = None
+    if w.num_blocks > 0:
+        num_blocks = max(w.num_blocks, w.demand_blocks() + growth)
+    else:  # a fraction of the free device memory, read at run time
+        free_bytes, _ = torch.cuda.mem_get_info()
+        num_blocks = int(w.hbm_fraction * free_bytes) // block_bytes
     kv = torch.empty(num_blocks * block_bytes, dtype=torch.uint8, device=device)
-    order = wl.placement_order(w.rng(), num_blocks)
-    pool = mx.mux_pool_create(kv, num_blocks, w.block_size, w.head_dim, mx.MUX_BF16, order)
-    models = [DecodeModel(pool, j, w.block_size, total_steps, w.seed * 1000 + j.model_id, device) for j in decode_jobs]
-    return w, pool, models
+    rng = w.rng()
+    if w.placement == "churn":
+        pool = mx.mux_pool_create(kv, num_blocks, w.block_size, w.head_dim, mx.MUX_BF16, None)
+
+        def try_alloc(m, n):
+            rc, ids = mx.mux_alloc_blocks_status(pool, m, n)
+            return ids if rc == mx.MUX_OK else None
+
+        wl.run_churn(rng, w.churn_ops, 4096, try_alloc, lambda m, ids: mx.mux_free_blocks(pool, m, ids), n_models=len(w.jobs))
+        g = torch.Generator(device=device)
+        g.manual_seed(w.seed)
+        bank = (torch.randn(1 << 28, generator=g, device=device).to(torch.bfloat16),
+                torch.randn(1 << 28, generator=g, device=device).to(torch.bfloat16))
+    else:
+        pool = mx.mux_pool_create(kv, num_blocks, w.block_size, w.head_dim, mx.MUX_BF16, wl.placement_order(rng, num_blocks))
+    models = [DecodeModel(pool, j, w.block_size, total_steps, w.seed * 1000 + j.model_id, device, bank) for j in decode_jobs]
+    prefills = [PrefillModel(pool, j, w.block_size, w.seed * 1000 + j.model_id, device) for j in prefill_jobs]
+    del bank
+    return w, pool, models, prefills
 
 
 def cpu_baseline(models, budget_s: float = 12.0):
@@ -215,7 +308,7 @@ def main() -> int:
         return 2
     mx.load()
     total = args.steps + args.warmup
-    w, pool, models = build_workload(args.config, total)
+    w, pool, models, prefills = build_workload(args.config, total)
 
     # Every model has its own stream and nothing orders the streams against each other: the
     # small kernels of one model overlap with the other's decode attention, and the decode
@@ -223,13 +316,19 @@ def main() -> int:
     # orders them explicitly through events; the cross-stream waits cost 15-50 us per launch.)
     last = None
     for _ in range(args.warmup):
+        for pm in prefills:
+            pm.step(record=False)
         for m in models:
             _, ev = m.step(record=False, after=last)
             last = ev if args.chain_decode else None
     torch.cuda.synchronize()
+    ref = torch.cuda.Event(enable_timing=True)
+    ref.record()
     t0 = time.perf_counter()
     kv_bytes = 0
     for _ in range(args.steps):
+        for pm in prefills:   # prefill jobs are scheduled first (Section 3.3: prefill is prioritised)
+            pm.step(record=True)
         for m in models:
             b, ev = m.step(record=True, after=last)
             last = ev if args.chain_decode else None
@@ -252,6 +351,16 @@ def main() -> int:
             durs.append(e0.elapsed_time(e1) * 1e-3)
             algo.append(b)
     achieved = float(np.sum(algo) / np.sum(durs) / 1e9)
+    # time during which at least one decode kernel was running (launches of different models may overlap)
+    spans = sorted((ref.elapsed_time(e0), ref.elapsed_time(e1)) for m in models for e0, e1, _ in m.decode_events)
+    busy, cur_lo, cur_hi = 0.0, None, None
+    for lo, hi in spans:
+        if cur_hi is None or lo > cur_hi:
+            busy += 0.0 if cur_hi is None else cur_hi - cur_lo
+            cur_lo, cur_hi = lo, hi
+        else:
+            cur_hi = max(cur_hi, hi)
+    busy += cur_hi - cur_lo
     n_seqs = sum(m.n for m in models)
     result = {
         "metric": "decode-attn KV GB/s (% of HBM peak) + tokens/s, multi-LLM mixed batch",
@@ -261,7 +370,9 @@ def main() -> int:
         "config": {
             "workload": "config %d: %s; block_size %d; %d head-blocks, seeded random placement; per step and model: "
                         "alloc -> table patch -> kv_append(1 token/seq) -> decode_attn, one stream per model, decode kernels %s"
-                        % (args.config, ", ".join("%s x%d seqs" % (m.shape.name, m.n) for m in models), w.block_size,
+                        % (args.config, ", ".join(["%s x%d decoding seqs" % (m.shape.name, m.n) for m in models] +
+                                                  ["%s x%d prompts in chunks of %d" % (pm.shape.name, pm.job.n_seqs, pm.job.chunk)
+                                                   for pm in prefills]), w.block_size,
                            pool.num_blocks, "chained by events" if args.chain_decode else "unordered across streams"),
             "layers": 1,
         },
@@ -274,8 +385,19 @@ def main() -> int:
             "traffic": MEASURED_TRAFFIC_CFG2["bytes"] if args.config == 2 else None,
             "traffic_source": MEASURED_TRAFFIC_CFG2["source"] if args.config == 2 else None,
             "avg_launch_ms": float(np.mean(durs) * 1e3), "algorithmic_bytes_per_launch": float(np.mean(algo)),
+            "launches": len(durs), "decode_busy_ms_per_step": busy / args.steps,
+            "achieved_while_any_decode_runs": float(np.sum(algo) / (busy * 1e-3) / 1e9),
         },
     }
+    if prefills:
+        ev = [e for pm in prefills for e in pm.events]
+        t = sum(e0.elapsed_time(e1) for e0, e1, _, _ in ev) * 1e-3
+        fl = sum(f for _, _, f, _ in ev)
+        result["prefill"] = {
+            "kernel": "prefill_attn_kernel, one launch per chunk stage", "launches": len(ev), "tflops": fl / t / 1e12,
+            "bound": "mfma", "peak_tflops": 2500.0, "frac": fl / t / 2.5e15, "avg_launch_ms": t / len(ev) * 1e3,
+            "flops_per_launch": fl / len(ev), "kv_bytes_per_launch": sum(b for _, _, _, b in ev) / len(ev),
+        }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(models)
     print(json.dumps(result))
