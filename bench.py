@@ -97,12 +97,12 @@ class DecodeModel:
         max_final = int(job.lens.max()) + total_steps + 1
         ws = mx.mux_decode_workspace_bytes(pool, self.n, n_q, n_kv, max_final)
         self.workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=device)
-        # pinned staging ring for table patches: per step [flat table indices | ids], the ids written
-        # there by mux_alloc_blocks itself; one host-to-device copy per step
+        # pinned staging ring for table patches: flat table indices and the ids, which
+        # mux_alloc_blocks writes there itself
         cap = self.n * n_kv
-        self.pin_patch = torch.empty(total_steps, 2 * cap, dtype=torch.int32, pin_memory=True)
-        self.pin_patch_np = self.pin_patch.numpy()
-        assert self.n * n_kv * self.max_blocks < 2 ** 31
+        self.pin_idx = torch.empty(total_steps, cap, dtype=torch.int64, pin_memory=True)
+        self.pin_ids = torch.empty(total_steps, cap, dtype=torch.int32, pin_memory=True)
+        self.pin_idx_np, self.pin_ids_np = self.pin_idx.numpy(), self.pin_ids.numpy()
         self.flat_tables = self.tables_dev.view(-1)
         self.head_base = (np.arange(n_kv, dtype=np.int64) * self.max_blocks)
         self.scale = 1.0 / math.sqrt(d)
@@ -122,15 +122,16 @@ class DecodeModel:
         with torch.cuda.stream(self.stream):
             if crossing.size:
                 # new blocks: ids from the block manager (written straight into pinned memory), then
-                # one host-to-device copy and a scatter into the device table
-                cnt, total = 0, int(crossing.size) * n_kv
+                # two small host-to-device copies and a scatter into the device table
+                cnt = 0
                 for s in crossing:
-                    mx.mux_alloc_blocks(self.pool, self.job.model_id, n_kv, self.pin_patch_np[i, total + cnt:total + cnt + n_kv])
+                    mx.mux_alloc_blocks(self.pool, self.job.model_id, n_kv, self.pin_ids_np[i, cnt:cnt + n_kv])
                     col = int(new_lens[s] - 1) // self.B
-                    self.pin_patch_np[i, cnt:cnt + n_kv] = (int(s) * n_kv * self.max_blocks + col) + self.head_base
+                    self.pin_idx_np[i, cnt:cnt + n_kv] = (int(s) * n_kv * self.max_blocks + col) + self.head_base
                     cnt += n_kv
-                patch = self.pin_patch[i, :2 * total].to(self.device, non_blocking=True)
-                self.flat_tables.index_put_((patch[:total],), patch[total:])
+                idx_dev = self.pin_idx[i, :cnt].to(self.device, non_blocking=True)
+                ids_dev = self.pin_ids[i, :cnt].to(self.device, non_blocking=True)
+                self.flat_tables.index_copy_(0, idx_dev, ids_dev)
             mx.mux_kv_append(self.pool, self.k_steps[i], self.v_steps[i], self.tok_seq, self.pos_steps[i], self.tables_dev,
                              stream=self.stream)
             max_ctx = int(new_lens.max())
@@ -292,6 +293,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", choices=["all", "decode", "prefill"], default="all",
+                    help="run only the decode models or only the prefill model of the configuration")
     ap.add_argument("--chain-decode", action="store_true",
                     help="make each decode kernel wait for the previous model's (adds cross-stream event latency)")
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 1 GiB device copies after the timed loop")
@@ -309,6 +312,12 @@ def main() -> int:
     mx.load()
     total = args.steps + args.warmup
     w, pool, models, prefills = build_workload(args.config, total)
+    step_models = [] if args.only == "prefill" else models
+    if args.only == "decode":
+        prefills = []
+    if not step_models and not prefills:
+        print("bench.py: configuration %d has nothing to run with --only %s" % (args.config, args.only), file=sys.stderr)
+        return 2
 
     # Every model has its own stream and nothing orders the streams against each other: the
     # small kernels of one model overlap with the other's decode attention, and the decode
@@ -318,7 +327,7 @@ def main() -> int:
     for _ in range(args.warmup):
         for pm in prefills:
             pm.step(record=False)
-        for m in models:
+        for m in step_models:
             _, ev = m.step(record=False, after=last)
             last = ev if args.chain_decode else None
     torch.cuda.synchronize()
@@ -329,7 +338,7 @@ def main() -> int:
     for _ in range(args.steps):
         for pm in prefills:   # prefill jobs are scheduled first (Section 3.3: prefill is prioritised)
             pm.step(record=True)
-        for m in models:
+        for m in step_models:
             b, ev = m.step(record=True, after=last)
             last = ev if args.chain_decode else None
             kv_bytes += b
@@ -345,23 +354,34 @@ def main() -> int:
         torch.cuda.synchronize()
 
     # dominant kernel: decode attention (main kernel + span combine), HIP-event durations
-    durs, algo = [], []
-    for m in models:
-        for e0, e1, b in m.decode_events:
-            durs.append(e0.elapsed_time(e1) * 1e-3)
-            algo.append(b)
-    achieved = float(np.sum(algo) / np.sum(durs) / 1e9)
-    # time during which at least one decode kernel was running (launches of different models may overlap)
-    spans = sorted((ref.elapsed_time(e0), ref.elapsed_time(e1)) for m in models for e0, e1, _ in m.decode_events)
-    busy, cur_lo, cur_hi = 0.0, None, None
-    for lo, hi in spans:
-        if cur_hi is None or lo > cur_hi:
-            busy += 0.0 if cur_hi is None else cur_hi - cur_lo
-            cur_lo, cur_hi = lo, hi
-        else:
-            cur_hi = max(cur_hi, hi)
-    busy += cur_hi - cur_lo
-    n_seqs = sum(m.n for m in models)
+    roofline = None
+    if step_models:
+        durs, algo = [], []
+        for m in step_models:
+            for e0, e1, b in m.decode_events:
+                durs.append(e0.elapsed_time(e1) * 1e-3)
+                algo.append(b)
+        achieved = float(np.sum(algo) / np.sum(durs) / 1e9)
+        # time during which at least one decode kernel was running (launches of different models may overlap)
+        spans = sorted((ref.elapsed_time(e0), ref.elapsed_time(e1)) for m in step_models for e0, e1, _ in m.decode_events)
+        busy, cur_lo, cur_hi = 0.0, None, None
+        for lo, hi in spans:
+            if cur_hi is None or lo > cur_hi:
+                busy += 0.0 if cur_hi is None else cur_hi - cur_lo
+                cur_lo, cur_hi = lo, hi
+            else:
+                cur_hi = max(cur_hi, hi)
+        busy += cur_hi - cur_lo
+        roofline = {
+            "kernel": "decode_attn_kernel (+ decode_combine_kernel), one launch per model per step",
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_CFG2["bytes"] if args.config == 2 else None,
+            "traffic_source": MEASURED_TRAFFIC_CFG2["source"] if args.config == 2 else None,
+            "avg_launch_ms": float(np.mean(durs) * 1e3), "algorithmic_bytes_per_launch": float(np.mean(algo)),
+            "launches": len(durs), "decode_busy_ms_per_step": busy / args.steps,
+            "achieved_while_any_decode_runs": float(np.sum(algo) / (busy * 1e-3) / 1e9),
+        }
+    n_seqs = sum(m.n for m in step_models)
     result = {
         "metric": "decode-attn KV GB/s (% of HBM peak) + tokens/s, multi-LLM mixed batch",
         "value": kv_bytes / dt / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -379,15 +399,7 @@ def main() -> int:
         "pct_hbm_peak": 100.0 * kv_bytes / dt / 1e9 / HBM_PEAK_GBS,
         "tokens_per_s": n_seqs * args.steps / dt,
         "host_enqueue_ms_per_step": t_enqueued / args.steps * 1e3,
-        "roofline": {
-            "kernel": "decode_attn_kernel (+ decode_combine_kernel), one launch per model per step",
-            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_CFG2["bytes"] if args.config == 2 else None,
-            "traffic_source": MEASURED_TRAFFIC_CFG2["source"] if args.config == 2 else None,
-            "avg_launch_ms": float(np.mean(durs) * 1e3), "algorithmic_bytes_per_launch": float(np.mean(algo)),
-            "launches": len(durs), "decode_busy_ms_per_step": busy / args.steps,
-            "achieved_while_any_decode_runs": float(np.sum(algo) / (busy * 1e-3) / 1e9),
-        },
+        "roofline": roofline,
     }
     if prefills:
         ev = [e for pm in prefills for e in pm.events]
@@ -398,6 +410,11 @@ def main() -> int:
             "bound": "mfma", "peak_tflops": 2500.0, "frac": fl / t / 2.5e15, "avg_launch_ms": t / len(ev) * 1e3,
             "flops_per_launch": fl / len(ev), "kv_bytes_per_launch": sum(b for _, _, _, b in ev) / len(ev),
         }
+        if roofline is None:   # prefill only: the MFMA-bound kernel is the dominant one
+            result["metric"], result["unit"], result["value"] = "prefill-attn causal TFLOP/s (% of MFMA peak)", "TFLOP/s", fl / t / 1e12
+            result["dtype"] = "bf16 MFMA, f32 accumulate"
+            result["roofline"] = {"kernel": "prefill_attn_kernel", "bound": "mfma", "achieved": fl / t / 1e12, "peak": 2500.0,
+                                  "unit": "TFLOP/s", "frac": fl / t / 2.5e15, "traffic": None}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(models)
     print(json.dumps(result))
