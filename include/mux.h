@@ -138,6 +138,28 @@ MUX_API size_t mux_decode_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs
                                   int32_t n_kv_heads, int32_t max_ctx_len);
 
 /* ---------------------------------------------------------------------------------
+ * Fused decoding step (Section 3.4, Implementation: in one decoding step an engine fills the
+ * new token's K/V into its blocks and runs attention over them; here both happen in one
+ * launch, for all layers of the model at once).  Equivalent to, for every layer l:
+ *     mux_kv_append(k_new[l], v_new[l], tok_seq = 0..n_seqs-1, tok_pos = ctx_lens - 1, block_tables[l])
+ *     mux_decode_attn(out[l], q[l], block_tables[l], ctx_lens)
+ * with the same results bit for bit in the pool and the same outputs.
+ *
+ * out, q: DEVICE [n_layers][n_seqs][n_q_heads][head_dim]; k_new, v_new: DEVICE
+ * [n_layers][n_seqs][n_kv_heads][head_dim]; block_tables: DEVICE [n_layers][n_seqs][n_kv_heads]
+ * [max_blocks] (every layer has its own blocks); ctx_lens: DEVICE [n_seqs], lengths AFTER the
+ * append (the new token sits at position ctx_lens[s] - 1; sequences with ctx_lens[s] == 0
+ * append nothing and return zeros).  The blocks of the new positions must already be in the
+ * tables.  workspace: at least mux_decode_step_workspace_bytes(...) bytes, 16-byte aligned.
+ * ------------------------------------------------------------------------------- */
+MUX_API int mux_decode_step(mux_pool_t *pool, void *out, const void *q, const void *k_new, const void *v_new,
+                    const int32_t *block_tables, const int32_t *ctx_lens, int32_t n_layers, int32_t n_seqs,
+                    int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len,
+                    float scale, void *workspace, size_t workspace_bytes, void *stream);
+MUX_API size_t mux_decode_step_workspace_bytes(const mux_pool_t *pool, int32_t n_layers, int32_t n_seqs,
+                                       int32_t n_q_heads, int32_t n_kv_heads, int32_t max_ctx_len);
+
+/* ---------------------------------------------------------------------------------
  * Chunked causal prefill attention (Section 2.1: prefill processes the prompt tokens
  * in parallel).  Sequence s contributes the query rows cu_q_lens[s] .. cu_q_lens[s+1]-1
  * of the packed q; row r of that chunk sits at absolute position p = q_start[s] + r and

@@ -23,7 +23,8 @@ MUX_BF16, MUX_FP32 = 0, 1
 EXPORTS = [
     "mux_pool_create", "mux_pool_destroy", "mux_pool_num_free", "mux_pool_num_used", "mux_pool_block_bytes",
     "mux_alloc_blocks", "mux_free_blocks", "mux_kv_append", "mux_decode_attn", "mux_decode_workspace_bytes",
-    "mux_prefill_attn", "mux_prefill_workspace_bytes", "mux_status_string",
+    "mux_prefill_attn", "mux_prefill_workspace_bytes", "mux_status_string", "mux_decode_step",
+    "mux_decode_step_workspace_bytes",
 ]
 
 
@@ -60,6 +61,9 @@ def load() -> C.CDLL:
     L.mux_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, sz, vp]
     L.mux_decode_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     L.mux_decode_workspace_bytes.restype = sz
+    L.mux_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, sz, vp]
+    L.mux_decode_step_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
+    L.mux_decode_step_workspace_bytes.restype = sz
     L.mux_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp, sz, vp]
     L.mux_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
     L.mux_prefill_workspace_bytes.restype = sz
@@ -203,6 +207,29 @@ def mux_decode_attn(pool: Pool, out: torch.Tensor, q: torch.Tensor, block_tables
                                 _dev(block_tables, torch.int32), _dev(ctx_lens, torch.int32), n_seqs, n_q, n_kv,
                                 max_blocks, max_ctx_len, scale, _dev(workspace), ws_bytes, _stream(stream))
     _check(rc, "mux_decode_attn")
+
+
+def mux_decode_step_workspace_bytes(pool: Pool, n_layers: int, n_seqs: int, n_q_heads: int, n_kv_heads: int,
+                                    max_ctx_len: int) -> int:
+    return load().mux_decode_step_workspace_bytes(pool.handle, n_layers, n_seqs, n_q_heads, n_kv_heads, max_ctx_len)
+
+
+def mux_decode_step(pool: Pool, out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                    block_tables: torch.Tensor, ctx_lens: torch.Tensor, max_ctx_len: int, scale: float,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """All tensors carry a leading layer dimension: q/out [layers][seqs][Hq][d], k_new/v_new
+    [layers][seqs][Hkv][d], block_tables [layers][seqs][Hkv][max_blocks]; ctx_lens [seqs]."""
+    n_layers, n_seqs, n_q, d = q.shape
+    n_layers2, n_seqs2, n_kv, max_blocks = block_tables.shape
+    if (d != pool.head_dim or (n_layers2, n_seqs2) != (n_layers, n_seqs) or out.shape != q.shape
+            or k_new.shape != (n_layers, n_seqs, n_kv, d) or v_new.shape != k_new.shape or ctx_lens.numel() != n_seqs):
+        raise MuxError(MUX_ERR_INVALID, "mux_decode_step")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().mux_decode_step(_device_pool(pool), _dev(out, pool.torch_dtype), _dev(q, pool.torch_dtype),
+                                _dev(k_new, pool.torch_dtype), _dev(v_new, pool.torch_dtype),
+                                _dev(block_tables, torch.int32), _dev(ctx_lens, torch.int32), n_layers, n_seqs, n_q, n_kv,
+                                max_blocks, max_ctx_len, scale, _dev(workspace), ws_bytes, _stream(stream))
+    _check(rc, "mux_decode_step")
 
 
 def mux_prefill_workspace_bytes(pool: Pool, n_seqs: int, total_q: int, max_ctx_len: int, n_q_heads: int,

@@ -186,6 +186,34 @@ int mux_decode_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *b
                                   max_blocks, max_ctx_len, scale, workspace, stream);
 }
 
+size_t mux_decode_step_workspace_bytes(const mux_pool_t *pool, int32_t n_layers, int32_t n_seqs, int32_t n_q_heads,
+                                       int32_t n_kv_heads, int32_t max_ctx_len)
+{
+    if (!pool || n_layers <= 0 || n_seqs <= 0 || !heads_ok(n_q_heads, n_kv_heads) || max_ctx_len <= 0) return 0;
+    if (static_cast<int64_t>(n_layers) * n_seqs > INT32_MAX) return 0;
+    return mux_plan_decode(pool, n_layers * n_seqs, n_q_heads, n_kv_heads, max_ctx_len).workspace_bytes;
+}
+
+int mux_decode_step(mux_pool_t *pool, void *out, const void *q, const void *k_new, const void *v_new,
+                    const int32_t *block_tables, const int32_t *ctx_lens, int32_t n_layers, int32_t n_seqs,
+                    int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len, float scale,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!pool || n_layers < 0 || n_seqs < 0 || !heads_ok(n_q_heads, n_kv_heads) || max_blocks < 0 || max_ctx_len < 0)
+        return MUX_ERR_INVALID;
+    if (n_layers == 0 || n_seqs == 0) return MUX_OK;
+    if (static_cast<int64_t>(n_layers) * n_seqs > INT32_MAX) return MUX_ERR_UNSUPPORTED;
+    if (!out || !q || !k_new || !v_new || !block_tables || !ctx_lens) return MUX_ERR_INVALID;
+    if (!aligned16(out) || !aligned16(q) || !aligned16(k_new) || !aligned16(v_new)) return MUX_ERR_INVALID;
+    if (max_ctx_len > static_cast<int64_t>(max_blocks) * pool->block_size) return MUX_ERR_INVALID;
+    const mux_decode_plan plan = mux_plan_decode(pool, n_layers * n_seqs, n_q_heads, n_kv_heads, std::max(max_ctx_len, 1));
+    if (plan.workspace_bytes > 0) {
+        if (!workspace || workspace_bytes < plan.workspace_bytes || !aligned16(workspace)) return MUX_ERR_INVALID;
+    }
+    return mux_launch_decode_step(pool, plan, out, q, k_new, v_new, block_tables, ctx_lens, n_layers, n_seqs, n_q_heads,
+                                  n_kv_heads, max_blocks, max_ctx_len, scale, workspace, stream);
+}
+
 size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs, int32_t total_q, int32_t max_ctx_len,
                                    int32_t n_q_heads, int32_t n_kv_heads)
 {

@@ -113,7 +113,13 @@ struct DecodeArgs {
     const int *cu_q_lens;
     const int *q_start;
     int n_table_seqs;       // sequences in the block table (== n_seqs for decode)
-    int n_seqs;             // rows of q / out
+    int n_seqs;             // sequences (entries of ctx_lens); rows of q / out = n_seqs * n_layers
+    // fused step: rows are laid out [layer][sequence]; every row's new K/V (k_new / v_new,
+    // [rows][n_kv_heads][D]) is written to position len - 1 of its blocks by the workgroup that
+    // reads that block, and used from registers.  Plain decode: n_layers = 1, k_new = null.
+    int n_layers;
+    const void *k_new;
+    const void *v_new;
     int n_q_heads, n_kv_heads, max_blocks, max_ctx_len;
     float scale_log2e;
     int span_blocks;  // blocks per workgroup span
@@ -128,7 +134,7 @@ __device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &tab
 {
     if (a.cu_q_lens == nullptr) {
         table_row = r;
-        len = a.ctx_lens[r];
+        len = a.ctx_lens[r % a.n_seqs];
     } else {
         int lo = 0, hi = a.n_table_seqs - 1;  // last sequence whose first row is <= r
         while (lo < hi) {
@@ -227,7 +233,8 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     const int kvh = w % a.n_kv_heads;
     const int turn = w / a.n_kv_heads;
 
-    const int s = pick_sequence(a, turn, tid);
+    // row of q / out / the table: layers take turns on the sequence whose turn it is
+    const int s = (turn % a.n_layers) * a.n_seqs + pick_sequence(a, turn / a.n_layers, tid);
 
     // Block ids of this wave: block blk_lo + wave + kWaves * j sits in lane j.  The load does
     // not wait for the context length (any entry inside the table row may be read; entries
@@ -341,10 +348,29 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
             for (int g = 0; g < NG; ++g)
                 v[g] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(t + kTileBytes + g * 1024));
         };
-        // Every block but the wave's last one is full, so only the last may need masking.
+        // Every block but the wave's last one is full, so only the last may need masking; it is
+        // also the only one that can hold the token a fused step appends.
         auto consume_full = [&](const u32x4 (&k)[NG], const u32x4 (&v)[NG]) { fold(k, v, std::false_type{}, BS); };
-        auto consume_last = [&](int j, const u32x4 (&k)[NG], const u32x4 (&v)[NG]) {
-            const int n_valid = L - (blk_lo + wave + kWaves * j) * BS;  // wave-uniform, >= 1
+        auto consume_last = [&](int j, u32x4 (&k)[NG], u32x4 (&v)[NG]) {
+            const int blk = blk_lo + wave + kWaves * j;
+            const int n_valid = L - blk * BS;  // wave-uniform, >= 1
+            if (a.k_new != nullptr && blk == n_blk_seq - 1) {
+                // the new token's row: take it from k_new / v_new, and let pass 0 store it in the pool
+                const int r = n_valid - 1;
+                char *tile = const_cast<char *>(tile_ptr(j));
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+                    if (g * RPL + rg == r) {
+                        const long long src = ((static_cast<long long>(s) * a.n_kv_heads + kvh) * D + c0) * EB;
+                        k[g] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.k_new) + src);
+                        v[g] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.v_new) + src);
+                        if (pass == 0) {
+                            char *dst = tile + static_cast<long long>(r) * (D * EB) + c0 * EB;
+                            *reinterpret_cast<u32x4 *>(dst) = k[g];
+                            *reinterpret_cast<u32x4 *>(dst + kTileBytes) = v[g];
+                        }
+                    }
+            }
             if (n_valid >= BS)
                 fold(k, v, std::false_type{}, BS);
             else
@@ -385,6 +411,15 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
                     const char *src = t + static_cast<long long>(r0) * (D * EB) + lane * 16;
                     k[0] = *reinterpret_cast<const u32x4 *>(src);
                     v[0] = *reinterpret_cast<const u32x4 *>(src + tile_bytes);
+                    if (a.k_new != nullptr && first_tok + r0 + rg == L - 1) {  // the token a fused step appends
+                        const long long nsrc = ((static_cast<long long>(s) * a.n_kv_heads + kvh) * D + c0) * EB;
+                        k[0] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.k_new) + nsrc);
+                        v[0] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.v_new) + nsrc);
+                        if (pass == 0) {
+                            *reinterpret_cast<u32x4 *>(const_cast<char *>(src)) = k[0];
+                            *reinterpret_cast<u32x4 *>(const_cast<char *>(src) + tile_bytes) = v[0];
+                        }
+                    }
                 }
                 fold(k, v, std::true_type{}, rows_here - r0);
             }
@@ -490,7 +525,8 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
     const int pass = w % a.n_passes;   w /= a.n_passes;
     const int kvh = w % a.n_kv_heads;
     const int turn = w / a.n_kv_heads;
-    const int s = pick_sequence(a, turn, tid);
+    // row of q / out / the table: layers take turns on the sequence whose turn it is
+    const int s = (turn % a.n_layers) * a.n_seqs + pick_sequence(a, turn / a.n_layers, tid);
 
     const int blk_lo = split * a.span_blocks;
     int table_row, L;
@@ -539,6 +575,29 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
             v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(t + BS * D * 2 + i * 1024));
     };
 
+    // A fused step appends one token: the wave that reads the sequence's last block takes that
+    // row from k_new / v_new (and, in pass 0, stores it in the pool).
+    auto patch_new_row = [&](int j, u32x4 (&k)[NP], u32x4 (&v)[NP]) {
+        const int blk = blk_lo + wave + kWaves * j;
+        if (a.k_new == nullptr || blk != n_blk_seq - 1) return;
+        const int r = L - 1 - blk * BS;
+        int id = __builtin_amdgcn_readlane(my_ids, j);
+        id = min(max(id, 0), a.num_blocks - 1);
+        char *tile = const_cast<char *>(a.kv_base) + static_cast<long long>(id) * a.block_bytes;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int piece = lane + 64 * i;
+            if (piece / PPR != r) continue;
+            const long long src = ((static_cast<long long>(s) * a.n_kv_heads + kvh) * D) * 2 + (piece % PPR) * 16;
+            k[i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.k_new) + src);
+            v[i] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.v_new) + src);
+            if (pass == 0) {
+                char *dst = tile + piece * 16;
+                *reinterpret_cast<u32x4 *>(dst) = k[i];
+                *reinterpret_cast<u32x4 *>(dst + BS * D * 2) = v[i];
+            }
+        }
+    };
     // n_valid: tokens of this block that belong to the sequence (BS except possibly in the last block)
     auto consume = [&](const u32x4 (&k)[NP], const u32x4 (&v)[NP], int n_valid) {
         // registers -> this wave's LDS tile, rows padded so that both access patterns below
@@ -614,8 +673,10 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
         if (j + 1 < n_mine) {
             load_tile(j + 1, kb, vb);
             consume(ka, va, BS);
+            patch_new_row(j + 1, kb, vb);
             consume(kb, vb, valid_in(j + 1));
         } else {
+            patch_new_row(j, ka, va);
             consume(ka, va, valid_in(j));
         }
     }
@@ -746,9 +807,14 @@ namespace {
 int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q, const int32_t *tables,
                 const int32_t *ctx_lens, const int32_t *cu_q_lens, const int32_t *q_start, int32_t n_table_seqs,
                 int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len,
-                float scale, void *workspace, void *stream)
+                float scale, void *workspace, void *stream, int32_t n_layers = 1, const void *k_new = nullptr,
+                const void *v_new = nullptr)
 {
     DecodeArgs a{};
+    a.n_layers = n_layers;
+    a.k_new = k_new;
+    a.v_new = v_new;
+    const long long n_rows = static_cast<long long>(n_seqs) * n_layers;
     a.cu_q_lens = cu_q_lens;
     a.q_start = q_start;
     a.n_table_seqs = n_table_seqs;
@@ -771,9 +837,9 @@ int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, co
     a.n_passes = plan.n_passes;
     if (plan.n_splits > 1) {
         a.ws_acc = static_cast<float *>(workspace);
-        a.ws_ml = a.ws_acc + static_cast<size_t>(n_seqs) * n_q_heads * plan.n_splits * pool->head_dim;
+        a.ws_ml = a.ws_acc + static_cast<size_t>(n_rows) * n_q_heads * plan.n_splits * pool->head_dim;
     }
-    const long long grid = static_cast<long long>(n_seqs) * n_kv_heads * plan.n_passes * plan.n_splits;
+    const long long grid = n_rows * n_kv_heads * plan.n_passes * plan.n_splits;
     if (grid > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf16 = pool->dtype == MUX_BF16;
@@ -795,7 +861,8 @@ int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, co
         return MUX_ERR_UNSUPPORTED;
     if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
     if (plan.n_splits > 1) {
-        const unsigned rows = static_cast<unsigned>(n_seqs) * static_cast<unsigned>(n_q_heads);
+        if (n_rows * n_q_heads > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
+        const unsigned rows = static_cast<unsigned>(n_rows * n_q_heads);
         if (pool->head_dim == 128) {
             if (bf16)
                 hipLaunchKernelGGL((decode_combine_kernel<true, 128>), dim3(rows), dim3(128), 0, st, a);
@@ -833,4 +900,15 @@ int mux_launch_prefill_rows_as_decode(const mux_pool *pool, void *out, const voi
     const mux_decode_plan plan = mux_plan_decode(pool, total_q, n_q_heads, n_kv_heads, max_ctx_len);
     return launch_rows(pool, plan, out, q, tables, nullptr, cu_q_lens, q_start, n_seqs, total_q, n_q_heads, n_kv_heads,
                        max_blocks, max_ctx_len, scale, workspace, stream);
+}
+
+// Fused decoding step over n_layers layers: rows are [layer][sequence]; the plan is made for
+// n_layers * n_seqs rows.
+int mux_launch_decode_step(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q, const void *k_new,
+                           const void *v_new, const int32_t *tables, const int32_t *ctx_lens, int32_t n_layers,
+                           int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len,
+                           float scale, void *workspace, void *stream)
+{
+    return launch_rows(pool, plan, out, q, tables, ctx_lens, nullptr, nullptr, n_seqs, n_seqs, n_q_heads, n_kv_heads,
+                       max_blocks, max_ctx_len, scale, workspace, stream, n_layers, k_new, v_new);
 }

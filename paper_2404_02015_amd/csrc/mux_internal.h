@@ -47,6 +47,11 @@ int mux_launch_decode_attn(const mux_pool *pool, const mux_decode_plan &plan, vo
                            int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len, float scale,
                            void *workspace, void *stream);
 
+int mux_launch_decode_step(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q, const void *k_new,
+                           const void *v_new, const int32_t *tables, const int32_t *ctx_lens, int32_t n_layers,
+                           int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len,
+                           float scale, void *workspace, void *stream);
+
 int mux_launch_prefill_attn(const mux_pool *pool, void *out, const void *q, const int32_t *cu_q_lens,
                             const int32_t *q_start, const int32_t *tables, int32_t n_seqs, int32_t total_q,
                             int32_t max_q_len, int32_t max_ctx_len, int32_t n_q_heads, int32_t n_kv_heads,

@@ -346,3 +346,59 @@ def test_small_config4_prefill_and_decode_share_the_pool():
     for st, (q, o) in zip(dec_states, dec_out):
         H.assert_close(o, H.decode_oracle(ls, st, q, scale), "bf16", st.shape.name)
     ls.check_counters()
+
+
+# ---------------------------------------------------------------------------------
+# fused decoding step: append + attention for all layers in one launch
+# ---------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,head_dim,block_size,n_q,n_kv,n_layers", [
+    ("bf16", 128, 16, 4, 4, 1), ("bf16", 128, 16, 4, 4, 3), ("bf16", 128, 16, 16, 2, 2), ("bf16", 128, 16, 40, 1, 2),
+    ("bf16", 128, 16, 6, 2, 2), ("bf16", 64, 16, 8, 2, 2), ("fp32", 128, 16, 2, 2, 2), ("bf16", 128, 8, 4, 2, 2),
+    ("fp32", 64, 1, 2, 1, 2), ("bf16", 128, 16, 36, 2, 1),
+])
+def test_fused_step_equals_append_then_decode(dtype, head_dim, block_size, n_q, n_kv, n_layers):
+    """mux_decode_step must leave the pool bit-identical to mux_kv_append (checked against the
+    oracle's pool) and return what the oracle's append-then-attend returns, layer by layer."""
+    _say("fused step %s d=%d B=%d Hq=%d Hkv=%d layers=%d" % (dtype, head_dim, block_size, n_q, n_kv, n_layers))
+    # lengths AFTER the step: an idle sequence (0), a first token (1), block boundaries, long ones with several spans
+    new_lens = np.array([0, 1, 2, block_size, block_size + 1, 2 * block_size + 1, 64, 65, 257, 1000, 1489], dtype=np.int32)
+    old_lens = np.maximum(new_lens - 1, 0)
+    n = new_lens.size
+    need = int(((new_lens + block_size - 1) // block_size).sum()) * n_kv * n_layers
+    rng = np.random.Generator(np.random.PCG64(n_q + n_layers))
+    ls = H.Lockstep(need + 64, block_size, head_dim, dtype, wl.placement_order(rng, need + 64))
+    shape = wl.ModelShape("t", n_q, n_kv, head_dim)
+    layers = [H.open_job(ls, 0, shape, n, int(new_lens.max()) + block_size) for _ in range(n_layers)]
+    for l, st in enumerate(layers):
+        H.extend(ls, st, old_lens, seed=100 + 7 * l)              # history (per layer its own values and blocks)
+    for st in layers:                                             # blocks for the new positions, no data yet
+        wl.grow_tables(ls.alloc, 0, st.tables, old_lens, new_lens, block_size, want_changed=False)
+        st.tables_dev.copy_(torch.from_numpy(st.tables))
+    tables_dev = torch.stack([st.tables_dev for st in layers]).contiguous()
+    k_new = wl.randn_values(901, (n_layers, n, n_kv, head_dim), dtype).cuda()
+    v_new = wl.randn_values(902, (n_layers, n, n_kv, head_dim), dtype).cuda()
+    q = wl.randn_values(903, (n_layers, n, n_q, head_dim), dtype).cuda()
+    out = torch.full_like(q, float("nan"))
+    lens_dev = torch.from_numpy(new_lens).cuda()
+    scale = H.default_scale(head_dim)
+    ws = mx.mux_decode_step_workspace_bytes(ls.lib, n_layers, n, n_q, n_kv, int(new_lens.max()))
+    wsb = torch.empty(max(ws, 16), dtype=torch.uint8, device="cuda")
+    mx.mux_decode_step(ls.lib, out, q, k_new, v_new, tables_dev, lens_dev, int(new_lens.max()), scale, wsb)
+    torch.cuda.synchronize()
+    # oracle: append the new token of every active sequence, then attend
+    active = np.nonzero(new_lens > 0)[0].astype(np.int32)
+    for l, st in enumerate(layers):
+        ls.orc.kv_append(H.to_oracle(k_new[l])[active], H.to_oracle(v_new[l])[active], active, new_lens[active] - 1, st.tables)
+        want = ls.orc.decode_attn(H.to_oracle(q[l]), st.tables, new_lens, n_q, scale)
+        H.assert_close(out[l], want, dtype, "layer %d" % l)
+    # pool bytes: everything the oracle holds must be in the device pool, bit for bit, and nothing else changed
+    got = ls.pool_image()
+    want_img = np.full_like(got, H.SENTINEL16)
+    for st in layers:
+        for s in range(n):
+            for pos in range(int(new_lens[s])):
+                for h in range(n_kv):
+                    bid = st.tables[s, h, pos // block_size]
+                    for which in (0, 1):
+                        want_img[bid, which, pos % block_size] = ls.orc.read_row(bid, pos % block_size, which).view(np.uint16)
+    assert np.array_equal(got, want_img)
