@@ -127,8 +127,9 @@ MUX_API int mux_kv_append(mux_pool_t *pool, const void *k_new, const void *v_new
  * ctx_lens: DEVICE int32 [n_seqs].  max_ctx_len: HOST upper bound on ctx_lens, used
  * to size the grid and the split of long contexts without reading device memory
  * (tokens beyond it are ignored).  workspace: DEVICE scratch of at least
- * mux_decode_workspace_bytes(...) bytes, 16-byte aligned, private to this call until
- * it has finished on `stream`; may be NULL when that function returns 0.
+ * mux_decode_workspace_bytes(...) bytes (never 0: it holds the call's work list and, for
+ * long contexts, the partial results of the spans), 16-byte aligned, private to this call
+ * until it has finished on `stream`.
  * ------------------------------------------------------------------------------- */
 MUX_API int mux_decode_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *block_tables,
                     const int32_t *ctx_lens, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads,

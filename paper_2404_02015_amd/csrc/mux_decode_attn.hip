@@ -6,9 +6,10 @@
 //
 // Shape of the work: for multi-head models every K/V byte is used once, about one flop per
 // byte, so the kernel is a gather at HBM speed.  Design:
-//   - a workgroup of 4 waves owns one (sequence, kv head, span of the context); long
-//     contexts are split into spans so that every workgroup has a bounded, similar amount
-//     of bytes to read and the grid is far larger than the 256 CUs;
+//   - a workgroup of 4 waves works on one (sequence, kv head, span of the context) at a time;
+//     long contexts are split into spans; the launch holds as many workgroups as fit on the
+//     GPU and each walks its share of a longest-first list of spans that a small kernel
+//     prepares (see decode_plan_kernel and take_work);
 //   - a wave reads whole blocks: each load instruction is 64 lanes x 16 bytes = 1 KiB of
 //     contiguous tile, i.e. RPL = 1024 / row_bytes full rows; a 16-token block of 128 bf16
 //     is 4 loads of K and 4 of V, all issued before any of them is used, and the next
@@ -23,7 +24,10 @@
 // All arithmetic is fp32; the output is rounded once to the storage type.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
+#include <map>
+#include <mutex>
 #include <type_traits>
 
 #include "mux_internal.h"
@@ -33,14 +37,13 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 #ifndef MUX_GROUP_MIN_WAVES
-#define MUX_GROUP_MIN_WAVES 3
+#define MUX_GROUP_MIN_WAVES 2
 #endif
 #ifndef MUX_DECODE_MIN_WAVES
 #define MUX_DECODE_MIN_WAVES 1
 #endif
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
-constexpr int kMaxRanked = 1024;               // largest batch ordered longest-first inside the kernel
 constexpr int kMaxWaveBlocks = 64;              // block ids a wave keeps in one register
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -3.0e38f;             // "no score seen yet"; finite so that differences stay finite
@@ -125,8 +128,12 @@ struct DecodeArgs {
     int span_blocks;  // blocks per workgroup span
     int n_splits;
     int n_passes;
-    float *ws_acc;  // [n_seqs][n_q_heads][n_splits][D]
-    float *ws_ml;   // [n_seqs][n_q_heads][n_splits][2]
+    float *ws_acc;  // [rows][n_q_heads][n_splits][D]
+    float *ws_ml;   // [rows][n_q_heads][n_splits][2]
+    // work list written by decode_plan_kernel: plan[1] = number of units, then from plan + 4 the
+    // units as (row, split) pairs, longest first
+    int *plan;
+    int grid_wgs;   // workgroups of the attention launch
 };
 
 // Row r of q/out -> (block-table row, context length).
@@ -147,28 +154,106 @@ __device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &tab
     len = min(max(len, 0), a.max_ctx_len);
 }
 
-// Longest sequence first: workgroups are dispatched in index order and a workgroup's time
-// grows with its context length, so the sequence served in turn r is the one with the r-th
-// longest context (ties by index).  Every workgroup ranks the batch itself from LDS, a few
-// hundred cycles for the batch sizes of a decode step; very large batches keep index order.
-__device__ __forceinline__ int pick_sequence(const DecodeArgs &a, int turn, int tid)
+// Scheduling.  A unit of work is one span of one row (sequence): all its kv heads and head
+// passes.  Spans differ in length by orders of magnitude inside one batch, so the order in
+// which they are started decides how long the GPU idles at the end of a launch.  A one-workgroup
+// kernel lists the units longest first (all full spans, then the last span of every row by
+// falling length; rows with an empty context get a unit too, so that their zeros are written),
+// and the attention kernel is launched with exactly as many workgroups as are resident at once,
+// each of which walks a fixed share of that list (see take_work).  No workgroup is ever started
+// for an empty span, and the longest units are never started last.
+__global__ __launch_bounds__(256) void decode_plan_kernel(const DecodeArgs a)
 {
-    if (a.cu_q_lens != nullptr || a.n_seqs <= 1 || a.n_seqs > kMaxRanked) return turn;
-    __shared__ int sm_len[kMaxRanked];
-    __shared__ int sm_pick;
-    for (int t = tid; t < a.n_seqs; t += kThreads) sm_len[t] = min(max(a.ctx_lens[t], 0), a.max_ctx_len);
+    __shared__ int sm_scan[256];
+    __shared__ int sm_bin[kWaves * kMaxWaveBlocks + 1];   // by length of the last span, 0 .. span_blocks
+    __shared__ int sm_base;
+    const int tid = threadIdx.x;
+    const int B = a.block_size, span = a.span_blocks;
+    const int n_rows = a.n_seqs * a.n_layers;
+    int2 *units = reinterpret_cast<int2 *>(a.plan + 4);
+    auto shape_of = [&](int r, int &full, int &rem) {   // full spans before the last one, blocks in the last one
+        int table_row, len;
+        resolve_row(a, r, table_row, len);
+        const int blocks = (len + B - 1) / B;
+        full = blocks > 0 ? (blocks - 1) / span : 0;
+        rem = blocks - full * span;
+    };
+    for (int i = tid; i <= span; i += 256) sm_bin[i] = 0;
+    if (tid == 0) sm_base = 0;
     __syncthreads();
-    for (int t = tid; t < a.n_seqs; t += kThreads) {
-        const int lt = sm_len[t];
-        int rank = 0;
-        for (int u = 0; u < a.n_seqs; ++u) {
-            const int lu = sm_len[u];
-            rank += (lu > lt || (lu == lt && u < t)) ? 1 : 0;
+    // full spans, in row order (256 rows at a time, workgroup-wide inclusive scan of their counts)
+    for (int r0 = 0; r0 < n_rows; r0 += 256) {
+        const int r = r0 + tid;
+        int full = 0, rem = 0;
+        if (r < n_rows) {
+            shape_of(r, full, rem);
+            atomicAdd(&sm_bin[rem], 1);
         }
-        if (rank == turn) sm_pick = t;
+        if (a.n_splits == 1) continue;   // a single span per row: there are no full spans to list
+        sm_scan[tid] = full;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {
+            const int below = tid >= off ? sm_scan[tid - off] : 0;
+            __syncthreads();
+            sm_scan[tid] += below;
+            __syncthreads();
+        }
+        const int first = sm_base + sm_scan[tid] - full;
+        for (int p = 0; p < full; ++p) units[first + p] = int2{r, p};
+        __syncthreads();
+        if (tid == 255) sm_base += sm_scan[255];
+        __syncthreads();
     }
     __syncthreads();
-    return sm_pick;
+    const int n_full = sm_base;
+    // last spans: counting sort by falling length
+    if (tid == 0) {
+        int run = n_full;
+        for (int b = span; b >= 0; --b) {
+            const int c = sm_bin[b];
+            sm_bin[b] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    for (int r = tid; r < n_rows; r += 256) {
+        int full, rem;
+        shape_of(r, full, rem);
+        units[atomicAdd(&sm_bin[rem], 1)] = int2{r, full};
+    }
+    if (tid == 0) a.plan[1] = n_full + n_rows;
+}
+
+// Work distribution inside the attention kernels.  Piece w of the work is unit w / (kv heads x
+// head passes) of the list, for one kv head and one pass.  With G workgroups, workgroup i takes
+// pieces i, 2G-1-i, 2G+i, 4G-1-i, ...: the list is dealt out in rounds whose direction
+// alternates, so the workgroup that got the longest piece of one round gets the shortest of the
+// next and the shares come out nearly equal.  The assignment is fixed: a shared counter that
+// workgroups claim pieces from was measured to cost ~25 % on short launches, since a thousand
+// device-wide atomics on one address take tens of microseconds to drain and every load issued
+// behind one waits for it.
+struct WorkCursor {
+    int round;     // pieces this workgroup has taken so far
+};
+
+__device__ __forceinline__ bool take_work(const DecodeArgs &a, int tid, WorkCursor &cur, bool first, int &row, int &split,
+                                          int &kvh, int &pass)
+{
+    __syncthreads();   // the previous piece's LDS is no longer in use
+    const int G = a.grid_wgs;
+    const int k = first ? 0 : cur.round;
+    int w = k * G + ((k & 1) ? G - 1 - static_cast<int>(blockIdx.x) : static_cast<int>(blockIdx.x));
+    cur.round = k + 1;
+    const int per_unit = a.n_kv_heads * a.n_passes;
+    const int n_units = __builtin_amdgcn_readfirstlane(a.plan[1]);
+    if (w / per_unit >= n_units) return false;
+    const int2 u = reinterpret_cast<const int2 *>(a.plan + 4)[w / per_unit];
+    w %= per_unit;
+    row = __builtin_amdgcn_readfirstlane(u.x);
+    split = __builtin_amdgcn_readfirstlane(u.y);
+    pass = w % a.n_passes;
+    kvh = w / a.n_passes;
+    return true;
 }
 
 // Last stage of a workgroup: every wave has left, per query head h, its running max, sum and
@@ -226,22 +311,17 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     const int rg = lane / LPR;            // row slot of this lane inside a load
     const int c0 = (lane % LPR) * EPL;    // first head dimension of this lane
 
-    // blockIdx -> (sequence, kv head, pass, split), split fastest
-    int w = blockIdx.x;
-    const int split = w % a.n_splits;  w /= a.n_splits;
-    const int pass = w % a.n_passes;   w /= a.n_passes;
-    const int kvh = w % a.n_kv_heads;
-    const int turn = w / a.n_kv_heads;
-
-    // row of q / out / the table: layers take turns on the sequence whose turn it is
-    const int s = (turn % a.n_layers) * a.n_seqs + pick_sequence(a, turn / a.n_layers, tid);
-
+    int s, split, kvh, pass;   // s: row of q / out / the table
+    WorkCursor cursor{0};
+    for (bool first = true; take_work(a, tid, cursor, first, s, split, kvh, pass); first = false) {
     // Block ids of this wave: block blk_lo + wave + kWaves * j sits in lane j.  The load does
     // not wait for the context length (any entry inside the table row may be read; entries
     // past the sequence's blocks are never used), so the two latencies overlap.
     const int blk_lo = split * a.span_blocks;
     int table_row, L;
     resolve_row(a, s, table_row, L);
+    table_row = __builtin_amdgcn_readfirstlane(table_row);   // same for every lane: keep the block loop scalar
+    L = __builtin_amdgcn_readfirstlane(L);
     const int *row = a.tables + (static_cast<long long>(table_row) * a.n_kv_heads + kvh) * a.max_blocks;
     int my_ids = 0;
     {
@@ -249,8 +329,7 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
         if (col < a.max_blocks) my_ids = row[col];
     }
     const int n_blk_seq = (L + B - 1) / B;
-    if (a.n_splits > 1 && blk_lo >= n_blk_seq) return;  // nothing of this sequence falls in the span
-    const int blk_hi = min(blk_lo + a.span_blocks, n_blk_seq);
+    const int blk_hi = min(blk_lo + a.span_blocks, n_blk_seq);   // blk_lo < n_blk_seq unless the context is empty
 
     const int group = a.n_q_heads / a.n_kv_heads;
     const int head0 = kvh * group + pass * GT;  // first query head of this pass
@@ -458,6 +537,7 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     __syncthreads();
 
     merge_waves_and_store<BF16, D, GT>(a, sm_acc, sm_m, sm_l, tid, s, head0, group - pass * GT, split);
+    }   // next piece of work
 }
 
 // Grouped-query decode on the matrix cores (bf16 pools, 16-token blocks, groups of >= 4
@@ -520,17 +600,14 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c = lane & 15;
 
-    int w = blockIdx.x;
-    const int split = w % a.n_splits;  w /= a.n_splits;
-    const int pass = w % a.n_passes;   w /= a.n_passes;
-    const int kvh = w % a.n_kv_heads;
-    const int turn = w / a.n_kv_heads;
-    // row of q / out / the table: layers take turns on the sequence whose turn it is
-    const int s = (turn % a.n_layers) * a.n_seqs + pick_sequence(a, turn / a.n_layers, tid);
-
+    int s, split, kvh, pass;   // s: row of q / out / the table
+    WorkCursor cursor{0};
+    for (bool first = true; take_work(a, tid, cursor, first, s, split, kvh, pass); first = false) {
     const int blk_lo = split * a.span_blocks;
     int table_row, L;
     resolve_row(a, s, table_row, L);
+    table_row = __builtin_amdgcn_readfirstlane(table_row);   // same for every lane: keep the block loop scalar
+    L = __builtin_amdgcn_readfirstlane(L);
     const int *row = a.tables + (static_cast<long long>(table_row) * a.n_kv_heads + kvh) * a.max_blocks;
     int my_ids = 0;
     {
@@ -538,7 +615,6 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
         if (col < a.max_blocks) my_ids = row[col];
     }
     const int n_blk_seq = (L + BS - 1) / BS;
-    if (a.n_splits > 1 && blk_lo >= n_blk_seq) return;
     const int blk_hi = min(blk_lo + a.span_blocks, n_blk_seq);
     const int n_mine = blk_hi - blk_lo > wave ? (blk_hi - blk_lo - wave + kWaves - 1) / kWaves : 0;
 
@@ -697,6 +773,7 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
     }
     __syncthreads();
     merge_waves_and_store<true, D, GT>(a, sm_acc, sm_m, sm_l, tid, s, head0, heads_left, split);
+    }   // next piece of work
 }
 
 // Merge the spans of one (sequence, query head): thread c owns head dimension c.
@@ -724,30 +801,23 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const DecodeArgs a)
     store_out<BF16>(a.out, static_cast<long long>(qrow) * D + c, ll > 0.f ? o / ll : 0.f);
 }
 
-template <bool BF16, int D, int BS, int GT>
-void launch_one(const DecodeArgs &a, unsigned grid, hipStream_t st)
-{
-    hipLaunchKernelGGL((decode_attn_kernel<BF16, D, BS, GT>), dim3(grid), dim3(kThreads), 0, st, a);
-}
+using AttnKernel = void (*)(DecodeArgs);
 
 template <bool BF16, int D, int BS>
-void launch_by_heads(int gt, const DecodeArgs &a, unsigned grid, hipStream_t st)
+AttnKernel kernel_by_heads(int gt)
 {
     switch (gt) {
-        case 1: launch_one<BF16, D, BS, 1>(a, grid, st); break;
-        case 2: launch_one<BF16, D, BS, 2>(a, grid, st); break;
-        case 4: launch_one<BF16, D, BS, 4>(a, grid, st); break;
-        default: launch_one<BF16, D, BS, 8>(a, grid, st); break;
+        case 1: return decode_attn_kernel<BF16, D, BS, 1>;
+        case 2: return decode_attn_kernel<BF16, D, BS, 2>;
+        case 4: return decode_attn_kernel<BF16, D, BS, 4>;
+        default: return decode_attn_kernel<BF16, D, BS, 8>;
     }
 }
 
 template <bool BF16, int D>
-void launch_by_block(int block_size, int gt, const DecodeArgs &a, unsigned grid, hipStream_t st)
+AttnKernel kernel_by_block(int block_size, int gt)
 {
-    if (block_size == 16)
-        launch_by_heads<BF16, D, 16>(gt, a, grid, st);
-    else
-        launch_by_heads<BF16, D, 0>(gt, a, grid, st);
+    return block_size == 16 ? kernel_by_heads<BF16, D, 16>(gt) : kernel_by_heads<BF16, D, 0>(gt);
 }
 
 // The matrix-core kernel covers bf16 pools with 16-token blocks and groups of >= 4 query heads.
@@ -760,6 +830,34 @@ int env_int(const char *name, int fallback)
 {
     const char *v = std::getenv(name);
     return v && *v ? std::atoi(v) : fallback;
+}
+
+// Workgroups of `fn` the current GPU holds at once: compute units x the occupancy the runtime
+// reports for the kernel (asked once per kernel; MUX_DECODE_WG_PER_CU overrides it).  The
+// attention launch has exactly this many workgroups, so all of them start together and each
+// walks its own share of the work list.
+long long resident_workgroups(AttnKernel fn)
+{
+    static std::mutex mu;
+    static std::map<AttnKernel, long long> known;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = known.find(fn);
+    if (it != known.end()) return it->second;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
+    static const int forced = env_int("MUX_DECODE_WG_PER_CU", 0);
+    if (forced > 0)
+        per_cu = forced;
+    else if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fn), kThreads, 0) !=
+                 hipSuccess ||
+             per_cu <= 0)
+        per_cu = 2;
+    (void)hipGetLastError();
+    const long long n = static_cast<long long>(cus) * per_cu;
+    known[fn] = n;
+    return n;
 }
 
 }  // namespace
@@ -798,8 +896,11 @@ mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_
     plan.span_tokens = static_cast<int32_t>(span * B);
     plan.n_splits = static_cast<int32_t>((ctx_blocks + span - 1) / span);
     if (plan.n_splits < 1) plan.n_splits = 1;
-    plan.workspace_bytes =
+    // work list: header (4 ints) + one (row, span) pair per possible unit
+    plan.plan_bytes = (16 + static_cast<size_t>(n_seqs) * plan.n_splits * 8 + 15) / 16 * 16;
+    const size_t partials =
         plan.n_splits > 1 ? static_cast<size_t>(n_seqs) * n_q_heads * plan.n_splits * (pool->head_dim + 2) * sizeof(float) : 0;
+    plan.workspace_bytes = plan.plan_bytes + partials;
     return plan;
 }
 
@@ -835,30 +936,37 @@ int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, co
     a.span_blocks = plan.span_tokens / pool->block_size;
     a.n_splits = plan.n_splits;
     a.n_passes = plan.n_passes;
+    a.plan = static_cast<int *>(workspace);
     if (plan.n_splits > 1) {
-        a.ws_acc = static_cast<float *>(workspace);
+        a.ws_acc = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.plan_bytes);
         a.ws_ml = a.ws_acc + static_cast<size_t>(n_rows) * n_q_heads * plan.n_splits * pool->head_dim;
     }
-    const long long grid = n_rows * n_kv_heads * plan.n_passes * plan.n_splits;
-    if (grid > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
+    if (n_rows * plan.n_splits * n_kv_heads * plan.n_passes > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf16 = pool->dtype == MUX_BF16;
     const int gt = plan.heads_per_pass;
-    const unsigned g = static_cast<unsigned>(grid);
+    AttnKernel fn = nullptr;
     if (gt == 16 && pool->head_dim == 128)
-        hipLaunchKernelGGL((decode_attn_group_kernel<128>), dim3(g), dim3(kThreads), 0, st, a);
+        fn = decode_attn_group_kernel<128>;
     else if (gt == 16 && pool->head_dim == 64)
-        hipLaunchKernelGGL((decode_attn_group_kernel<64>), dim3(g), dim3(kThreads), 0, st, a);
+        fn = decode_attn_group_kernel<64>;
     else if (bf16 && pool->head_dim == 128)
-        launch_by_block<true, 128>(pool->block_size, gt, a, g, st);
+        fn = kernel_by_block<true, 128>(pool->block_size, gt);
     else if (bf16 && pool->head_dim == 64)
-        launch_by_block<true, 64>(pool->block_size, gt, a, g, st);
+        fn = kernel_by_block<true, 64>(pool->block_size, gt);
     else if (!bf16 && pool->head_dim == 128)
-        launch_by_block<false, 128>(pool->block_size, gt, a, g, st);
+        fn = kernel_by_block<false, 128>(pool->block_size, gt);
     else if (!bf16 && pool->head_dim == 64)
-        launch_by_block<false, 64>(pool->block_size, gt, a, g, st);
+        fn = kernel_by_block<false, 64>(pool->block_size, gt);
     else
         return MUX_ERR_UNSUPPORTED;
+    // as many workgroups as are resident at once (they walk the work list); never more than there is work
+    const long long most = n_rows * plan.n_splits * n_kv_heads * plan.n_passes;
+    const unsigned g = static_cast<unsigned>(std::min<long long>(most, resident_workgroups(fn)));
+    a.grid_wgs = static_cast<int>(g);
+    hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(256), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
+    hipLaunchKernelGGL(fn, dim3(g), dim3(kThreads), 0, st, a);
     if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
     if (plan.n_splits > 1) {
         if (n_rows * n_q_heads > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;

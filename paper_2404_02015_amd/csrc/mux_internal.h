@@ -38,7 +38,8 @@ struct mux_decode_plan {
     int32_t n_splits;      // ceil(max_ctx_len / span_tokens)
     int32_t heads_per_pass;  // query heads of one KV group handled together by a workgroup
     int32_t n_passes;        // ceil(group / heads_per_pass)
-    size_t workspace_bytes;  // 0 when n_splits == 1
+    size_t plan_bytes;       // work list at the start of the workspace (16-byte multiple)
+    size_t workspace_bytes;  // plan_bytes + fp32 partial results of the spans (when n_splits > 1)
 };
 mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads,
                                 int32_t max_ctx_len);

@@ -145,16 +145,21 @@ def test_kernel_calls_reject_bad_host_arguments_before_launching():
     lib = mx.load()
     h = p.handle
     fake = 4096  # never dereferenced: every call below fails its host-side checks first
-    assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 6, 4, 4, 64, 1.0, None, 0, None) == mx.MUX_ERR_INVALID  # 6 % 4
-    assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 4, 4, 4, 65, 1.0, None, 0, None) == mx.MUX_ERR_INVALID  # hint > table
-    assert lib.mux_decode_attn(h, fake + 2, fake, fake, fake, 2, 4, 4, 4, 64, 1.0, None, 0, None) == mx.MUX_ERR_INVALID  # alignment
-    assert lib.mux_decode_attn(h, None, fake, fake, fake, 2, 4, 4, 4, 64, 1.0, None, 0, None) == mx.MUX_ERR_INVALID
+    big = 1 << 30
+    assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 6, 4, 4, 64, 1.0, fake, big, None) == mx.MUX_ERR_INVALID  # 6 % 4
+    assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 4, 4, 4, 65, 1.0, fake, big, None) == mx.MUX_ERR_INVALID  # hint > table
+    assert lib.mux_decode_attn(h, fake + 2, fake, fake, fake, 2, 4, 4, 4, 64, 1.0, fake, big, None) == mx.MUX_ERR_INVALID  # alignment
+    assert lib.mux_decode_attn(h, None, fake, fake, fake, 2, 4, 4, 4, 64, 1.0, fake, big, None) == mx.MUX_ERR_INVALID
     assert lib.mux_decode_attn(h, fake, fake, fake, fake, 0, 4, 4, 4, 64, 1.0, None, 0, None) == mx.MUX_OK           # empty batch
-    # long contexts need a workspace
+    # every decode call needs its workspace (work list, and partial results for long contexts)
     need = lib.mux_decode_workspace_bytes(h, 2, 4, 4, 4096)
     assert need > 0
     assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 4, 4, 256, 4096, 1.0, None, 0, None) == mx.MUX_ERR_INVALID
     assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 4, 4, 256, 4096, 1.0, fake, need - 1, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_decode_attn(h, fake, fake, fake, fake, 2, 4, 4, 256, 4096, 1.0, fake + 4, need, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_decode_step(h, fake, fake, fake, fake, fake, fake, 2, 2, 6, 4, 4, 64, 1.0, fake, big, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_decode_step(h, fake, fake, None, fake, fake, fake, 2, 2, 4, 4, 4, 64, 1.0, fake, big, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_decode_step(h, fake, fake, fake, fake, fake, fake, 0, 2, 4, 4, 4, 64, 1.0, None, 0, None) == mx.MUX_OK
     assert lib.mux_kv_append(h, fake, fake, fake, fake, fake, -1, 1, 4, 4, None) == mx.MUX_ERR_INVALID
     assert lib.mux_kv_append(h, fake, fake, fake, fake, fake, 0, 1, 4, 4, None) == mx.MUX_OK
     assert lib.mux_kv_append(h, fake + 8, fake, fake, fake, fake, 3, 1, 4, 4, None) == mx.MUX_ERR_INVALID
@@ -171,7 +176,7 @@ def test_kernel_calls_reject_bad_host_arguments_before_launching():
 def test_decode_plan_workspace_is_monotone_and_bounded():
     p = host_pool(64)
     lib = mx.load()
-    assert lib.mux_decode_workspace_bytes(p.handle, 4096, 32, 32, 16) == 0      # one span: no workspace
+    assert 0 < lib.mux_decode_workspace_bytes(p.handle, 4096, 32, 32, 16) <= 16 + 4096 * 8   # one span: only the work list
     prev = 0
     for ctx in (1024, 4096, 16384):
         b = lib.mux_decode_workspace_bytes(p.handle, 64, 32, 32, ctx)
