@@ -39,6 +39,7 @@
 #define ORACLE_OK 0
 #define ORACLE_ERR_INVALID (-1)
 #define ORACLE_ERR_NOMEM (-2)
+#define ORACLE_ERR_QUOTA (-3)
 #define ORACLE_ERR_UNSUPPORTED (-5)
 
 #define ORACLE_BF16 0
@@ -55,6 +56,8 @@ typedef struct oracle_pool {
     int64_t n_free;
     int32_t *owner;      /* -1 = free, else the model that holds the block */
     int64_t used[ORACLE_MAX_MODELS];
+    int64_t quota[ORACLE_MAX_MODELS]; /* cap on used[m]; -1 = none (Section 3.3: token block quota) */
+    int64_t peak[ORACLE_MAX_MODELS];  /* largest used[m] since the last quota adaptation */
     uint8_t **tile;      /* tile[id] = K rows [block_size][head_dim], then V rows; NULL until written */
 } oracle_pool;
 
@@ -83,6 +86,7 @@ int oracle_pool_create(oracle_pool **out, int64_t num_blocks, int32_t block_size
     p->tile = (uint8_t **)calloc((size_t)num_blocks, sizeof(uint8_t *));
     if (!p->free_stack || !p->owner || !p->tile) return ORACLE_ERR_INVALID;
     for (int64_t i = 0; i < num_blocks; ++i) p->owner[i] = -1;
+    for (int m = 0; m < ORACLE_MAX_MODELS; ++m) p->quota[m] = -1;
     if (init_free_order) {
         /* must be a permutation of [0, num_blocks) */
         for (int64_t i = 0; i < num_blocks; ++i) {
@@ -128,6 +132,8 @@ int oracle_alloc_blocks(oracle_pool *p, int32_t model_id, int64_t n, int32_t *ou
     if (!p || model_id < 0 || model_id >= ORACLE_MAX_MODELS || n < 0) return ORACLE_ERR_INVALID;
     if (n == 0) return ORACLE_OK;
     if (!out_ids) return ORACLE_ERR_INVALID;
+    /* the model's own quota is looked at first: a request beyond it is refused whatever the pool holds */
+    if (p->quota[model_id] >= 0 && p->used[model_id] + n > p->quota[model_id]) return ORACLE_ERR_QUOTA;
     if (n > p->n_free) return ORACLE_ERR_NOMEM;
     for (int64_t i = 0; i < n; ++i) {
         int32_t id = p->free_stack[--p->n_free];
@@ -135,6 +141,7 @@ int oracle_alloc_blocks(oracle_pool *p, int32_t model_id, int64_t n, int32_t *ou
         out_ids[i] = id;
     }
     p->used[model_id] += n;
+    if (p->used[model_id] > p->peak[model_id]) p->peak[model_id] = p->used[model_id];
     return ORACLE_OK;
 }
 
@@ -161,6 +168,125 @@ int oracle_free_blocks(oracle_pool *p, int32_t model_id, int64_t n, const int32_
         p->free_stack[p->n_free++] = ids[i];
     }
     p->used[model_id] -= n;
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Token-block quotas (Section 3.3: every LLM of a unit gets a quota of token  */
+/* blocks so that the shared cache is split fairly; Algorithm 3 initialises    */
+/* the quotas, checks them before a job runs and adapts them periodically by   */
+/* moving blocks from LLMs that use little of theirs to LLMs that use most).   */
+/* The paper gives no formula; the rules below are this build's reading:       */
+/*  - a quota caps the blocks a model holds; lowering it takes nothing back;   */
+/*  - initial quotas split the pool in proportion to caller-given weights      */
+/*    (request rate x blocks per token: usage normalised by rate is then equal)*/
+/*    by the largest-remainder rule, ties to the lower model id;               */
+/*  - utilisation of a model = peak blocks held since the last adaptation /    */
+/*    quota; a model below `low` gives away floor(step x (quota - peak)); the  */
+/*    blocks collected go to the models at or above `high` (and holding at     */
+/*    least one block) in proportion to their peaks, largest remainder, ties   */
+/*    to the lower id; without givers or takers nothing moves; peaks restart   */
+/*    from the current usage.                                                  */
+/* ------------------------------------------------------------------------- */
+
+int oracle_set_quota(oracle_pool *p, int32_t model_id, int64_t max_blocks)
+{
+    if (!p || model_id < 0 || model_id >= ORACLE_MAX_MODELS) return ORACLE_ERR_INVALID;
+    if (max_blocks < -1 || max_blocks > p->num_blocks) return ORACLE_ERR_INVALID;
+    p->quota[model_id] = max_blocks;
+    return ORACLE_OK;
+}
+
+int64_t oracle_get_quota(const oracle_pool *p, int32_t model_id)
+{
+    if (!p || model_id < 0 || model_id >= ORACLE_MAX_MODELS) return ORACLE_ERR_INVALID - 1; /* -2: not a quota value */
+    return p->quota[model_id];
+}
+
+int64_t oracle_peak_used(const oracle_pool *p, int32_t model_id)
+{
+    if (!p || model_id < 0 || model_id >= ORACLE_MAX_MODELS) return ORACLE_ERR_INVALID;
+    return p->peak[model_id];
+}
+
+int oracle_init_quotas(oracle_pool *p, int32_t n_models, const double *weights)
+{
+    if (!p || n_models <= 0 || n_models > ORACLE_MAX_MODELS || !weights) return ORACLE_ERR_INVALID;
+    double total = 0.0;
+    for (int m = 0; m < n_models; ++m) {
+        if (!(weights[m] >= 0.0) || isinf(weights[m])) return ORACLE_ERR_INVALID;
+        total += weights[m];
+    }
+    if (!(total > 0.0) || isinf(total)) return ORACLE_ERR_INVALID;
+    double frac[ORACLE_MAX_MODELS];
+    int64_t given = 0;
+    for (int m = 0; m < n_models; ++m) {
+        double share = (double)p->num_blocks * weights[m] / total;
+        double whole = floor(share);
+        p->quota[m] = (int64_t)whole;
+        frac[m] = share - whole;
+        given += p->quota[m];
+    }
+    /* the blocks left over go, one each, to the largest fractional parts (first one wins a tie) */
+    for (int64_t left = p->num_blocks - given; left > 0; --left) {
+        int best = -1;
+        for (int m = 0; m < n_models; ++m)
+            if (frac[m] >= 0.0 && (best < 0 || frac[m] > frac[best])) best = m;
+        if (best < 0) { /* rounding left more blocks than models: start another round */
+            for (int m = 0; m < n_models; ++m) frac[m] = 0.0;
+            best = 0;
+        }
+        p->quota[best] += 1;
+        frac[best] = -1.0;
+    }
+    return ORACLE_OK;
+}
+
+int oracle_adapt_quotas(oracle_pool *p, int32_t n_models, double low, double high, double step, int64_t *moved)
+{
+    if (!p || n_models <= 0 || n_models > ORACLE_MAX_MODELS) return ORACLE_ERR_INVALID;
+    if (!(low >= 0.0) || !(high >= low) || isinf(high) || !(step >= 0.0) || !(step <= 1.0)) return ORACLE_ERR_INVALID;
+    for (int m = 0; m < n_models; ++m)
+        if (p->quota[m] < 0) return ORACLE_ERR_INVALID;
+    int64_t give[ORACLE_MAX_MODELS], take_weight[ORACLE_MAX_MODELS];
+    int64_t pot = 0, weight_sum = 0;
+    for (int m = 0; m < n_models; ++m) {
+        double q = (double)p->quota[m], pk = (double)p->peak[m];
+        give[m] = 0;
+        take_weight[m] = 0;
+        if (pk < low * q) {
+            give[m] = (int64_t)floor(step * (q - pk));
+            pot += give[m];
+        } else if (p->peak[m] > 0 && pk >= high * q) {
+            take_weight[m] = p->peak[m];
+            weight_sum += p->peak[m];
+        }
+    }
+    int64_t total_moved = 0;
+    if (pot > 0 && weight_sum > 0) {
+        int64_t rest[ORACLE_MAX_MODELS];
+        int64_t handed = 0;
+        for (int m = 0; m < n_models; ++m) {
+            p->quota[m] -= give[m];
+            rest[m] = -1;
+            if (take_weight[m] > 0) {
+                int64_t part = pot * take_weight[m] / weight_sum;
+                rest[m] = pot * take_weight[m] % weight_sum;
+                p->quota[m] += part;
+                handed += part;
+            }
+        }
+        for (int64_t left = pot - handed; left > 0; --left) {
+            int best = -1;
+            for (int m = 0; m < n_models; ++m)
+                if (rest[m] >= 0 && (best < 0 || rest[m] > rest[best])) best = m;
+            p->quota[best] += 1;
+            rest[best] = -1;
+        }
+        total_moved = pot;
+    }
+    for (int m = 0; m < n_models; ++m) p->peak[m] = p->used[m];
+    if (moved) *moved = total_moved;
     return ORACLE_OK;
 }
 

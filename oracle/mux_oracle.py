@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mux_oracle.c")
 _LIB = os.path.join(_HERE, "libmux_oracle.so")
 
-OK, ERR_INVALID, ERR_NOMEM, ERR_UNSUPPORTED = 0, -1, -2, -5
+OK, ERR_INVALID, ERR_NOMEM, ERR_QUOTA, ERR_UNSUPPORTED = 0, -1, -2, -3, -5
 BF16, FP32 = 0, 1
 
 
@@ -52,6 +52,13 @@ def lib():
         L.oracle_pool_num_used.restype = i64
         L.oracle_alloc_blocks.argtypes = [vp, i32, i64, vp]
         L.oracle_free_blocks.argtypes = [vp, i32, i64, vp]
+        L.oracle_set_quota.argtypes = [vp, i32, i64]
+        L.oracle_get_quota.argtypes = [vp, i32]
+        L.oracle_get_quota.restype = i64
+        L.oracle_peak_used.argtypes = [vp, i32]
+        L.oracle_peak_used.restype = i64
+        L.oracle_init_quotas.argtypes = [vp, i32, vp]
+        L.oracle_adapt_quotas.argtypes = [vp, i32, C.c_double, C.c_double, C.c_double, C.POINTER(i64)]
         L.oracle_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32]
         L.oracle_read_row.argtypes = [vp, i32, i32, i32, vp]
         L.oracle_drop_tiles.argtypes = [vp, i64, vp]
@@ -134,6 +141,27 @@ class OraclePool:
         rc = self.free_status(model_id, ids)
         if rc != OK:
             raise OracleError(rc, "oracle_free_blocks")
+
+    # -- token-block quotas --------------------------------------------------
+    def set_quota(self, model_id: int, max_blocks: int) -> int:
+        """max_blocks = -1 removes the quota.  Returns the status."""
+        return lib().oracle_set_quota(self._h, model_id, max_blocks)
+
+    def get_quota(self, model_id: int) -> int:
+        return lib().oracle_get_quota(self._h, model_id)
+
+    def peak_used(self, model_id: int) -> int:
+        return lib().oracle_peak_used(self._h, model_id)
+
+    def init_quotas(self, weights) -> int:
+        w = np.ascontiguousarray(weights, dtype=np.float64)
+        return lib().oracle_init_quotas(self._h, w.size, _ptr(w))
+
+    def adapt_quotas(self, n_models: int, low: float, high: float, step: float):
+        """Returns (status, blocks moved)."""
+        moved = C.c_int64(-1)
+        rc = lib().oracle_adapt_quotas(self._h, n_models, low, high, step, C.byref(moved))
+        return rc, moved.value
 
     # -- data path ---------------------------------------------------------
     def _elems(self, a) -> np.ndarray:
