@@ -52,7 +52,7 @@ typedef enum {
     MUX_OK = 0,
     MUX_ERR_INVALID = -1,     /* bad argument; unknown, foreign, repeated or already-free block id */
     MUX_ERR_NOMEM = -2,       /* not enough free blocks; ALL-OR-NOTHING: nothing changed */
-    MUX_ERR_QUOTA = -3,       /* reserved for per-model token-block quotas (Section 3.3) */
+    MUX_ERR_QUOTA = -3,       /* the request would take the model past its token-block quota; nothing changed */
     MUX_ERR_HIP = -4,         /* a HIP runtime call or kernel launch failed */
     MUX_ERR_UNSUPPORTED = -5  /* shape or dtype outside what the kernels are built for */
 } mux_status_t;
@@ -90,12 +90,46 @@ MUX_API int64_t mux_pool_block_bytes(const mux_pool_t *pool);
  * so the last id freed is the first one handed out again.
  *
  * out_ids / ids: HOST arrays of n int32.  n == 0 is a no-op.
- * mux_alloc_blocks: fewer than n free blocks -> MUX_ERR_NOMEM, pool and out_ids
- * untouched.  mux_free_blocks: an id that is out of range, not currently held by
+ * mux_alloc_blocks: a model with a quota (below) that would hold more than it ->
+ * MUX_ERR_QUOTA; else fewer than n free blocks -> MUX_ERR_NOMEM; in both cases pool and
+ * out_ids are untouched.  mux_free_blocks: an id that is out of range, not currently held by
  * `model_id`, or named twice in the call -> MUX_ERR_INVALID, nothing changed.
  * ------------------------------------------------------------------------------- */
 MUX_API int mux_alloc_blocks(mux_pool_t *pool, int32_t model_id, int64_t n, int32_t *out_ids);
 MUX_API int mux_free_blocks(mux_pool_t *pool, int32_t model_id, int64_t n, const int32_t *ids);
+
+/* ---------------------------------------------------------------------------------
+ * Token-block quotas (Section 3.3 and Algorithm 3: every LLM of a unit gets a quota of
+ * token blocks so that the shared cache is split fairly; the scheduler initialises the
+ * quotas, checks them before it runs a job, and periodically moves blocks from LLMs that
+ * use little of their quota to LLMs that use most of theirs).  Host calls; they never
+ * touch device memory.  The paper gives no formulas; the rules are:
+ *
+ * mux_pool_set_quota: cap on the blocks `model_id` may hold, 0..num_blocks, or -1 for
+ *   none (the state of a fresh pool).  A quota below the current holding takes nothing
+ *   back: allocations fail with MUX_ERR_QUOTA until enough blocks were freed.
+ * mux_pool_get_quota: *out = the quota or -1.   mux_pool_peak_used: *out = the largest
+ *   number of blocks the model held since the last mux_pool_adapt_quotas (or creation).
+ * mux_pool_init_quotas: models 0..n_models-1 share ALL num_blocks in proportion to
+ *   weights[m] (host array of n_models finite doubles >= 0 with a positive sum; the
+ *   paper normalises block usage by request rate, so pass rate x blocks per token):
+ *   floor(num_blocks * w / sum) each, the blocks left over one each to the largest
+ *   fractional parts, ties to the lower model id.
+ * mux_pool_adapt_quotas: utilisation of a model = peak / quota.  A model with
+ *   peak < low * quota gives away floor(step * (quota - peak)) blocks of quota; the blocks
+ *   collected go to the models with peak > 0 and peak >= high * quota in proportion to
+ *   their peaks (integer largest remainder, ties to the lower id).  Without givers or
+ *   takers nothing moves.  The sum of quotas is unchanged, no quota drops below its
+ *   model's peak, peaks restart from the current holdings.  *moved (may be NULL) = blocks
+ *   of quota moved.  Needs 0 <= low <= high < inf, 0 <= step <= 1 and a quota on every
+ *   model 0..n_models-1; else MUX_ERR_INVALID and nothing changes.
+ * ------------------------------------------------------------------------------- */
+MUX_API int mux_pool_set_quota(mux_pool_t *pool, int32_t model_id, int64_t max_blocks);
+MUX_API int mux_pool_get_quota(const mux_pool_t *pool, int32_t model_id, int64_t *out);
+MUX_API int mux_pool_peak_used(const mux_pool_t *pool, int32_t model_id, int64_t *out);
+MUX_API int mux_pool_init_quotas(mux_pool_t *pool, int32_t n_models, const double *weights);
+MUX_API int mux_pool_adapt_quotas(mux_pool_t *pool, int32_t n_models, double low, double high, double step,
+                                  int64_t *moved);
 
 /* ---------------------------------------------------------------------------------
  * KV append (Section 3.4, Implementation: the engine fills K/V into the blocks it

@@ -24,7 +24,8 @@ EXPORTS = [
     "mux_pool_create", "mux_pool_destroy", "mux_pool_num_free", "mux_pool_num_used", "mux_pool_block_bytes",
     "mux_alloc_blocks", "mux_free_blocks", "mux_kv_append", "mux_decode_attn", "mux_decode_workspace_bytes",
     "mux_prefill_attn", "mux_prefill_workspace_bytes", "mux_status_string", "mux_decode_step",
-    "mux_decode_step_workspace_bytes",
+    "mux_decode_step_workspace_bytes", "mux_pool_set_quota", "mux_pool_get_quota", "mux_pool_peak_used",
+    "mux_pool_init_quotas", "mux_pool_adapt_quotas",
 ]
 
 
@@ -51,6 +52,11 @@ def load() -> C.CDLL:
     L.mux_pool_destroy.argtypes = [vp]
     L.mux_pool_num_free.argtypes = [vp]
     L.mux_pool_num_free.restype = i64
+    L.mux_pool_set_quota.argtypes = [vp, i32, i64]
+    L.mux_pool_get_quota.argtypes = [vp, i32, C.POINTER(i64)]
+    L.mux_pool_peak_used.argtypes = [vp, i32, C.POINTER(i64)]
+    L.mux_pool_init_quotas.argtypes = [vp, i32, vp]
+    L.mux_pool_adapt_quotas.argtypes = [vp, i32, C.c_double, C.c_double, C.c_double, C.POINTER(i64)]
     L.mux_pool_num_used.argtypes = [vp, i32]
     L.mux_pool_num_used.restype = i64
     L.mux_pool_block_bytes.argtypes = [vp]
@@ -154,6 +160,39 @@ def mux_pool_num_free(pool: Pool) -> int:
 
 def mux_pool_num_used(pool: Pool, model_id: int) -> int:
     return load().mux_pool_num_used(pool.handle, model_id)
+
+
+def mux_pool_set_quota(pool: Pool, model_id: int, max_blocks: int) -> int:
+    """max_blocks = -1 removes the quota.  Returns the status."""
+    return load().mux_pool_set_quota(pool.handle, model_id, max_blocks)
+
+
+def _read_i64(fn, pool: Pool, model_id: int, what: str) -> int:
+    out = C.c_int64()
+    rc = fn(pool.handle, model_id, C.byref(out))
+    if rc != MUX_OK:
+        raise MuxError(rc, what)
+    return out.value
+
+
+def mux_pool_get_quota(pool: Pool, model_id: int) -> int:
+    return _read_i64(load().mux_pool_get_quota, pool, model_id, "mux_pool_get_quota")
+
+
+def mux_pool_peak_used(pool: Pool, model_id: int) -> int:
+    return _read_i64(load().mux_pool_peak_used, pool, model_id, "mux_pool_peak_used")
+
+
+def mux_pool_init_quotas(pool: Pool, weights) -> int:
+    w = np.ascontiguousarray(weights, dtype=np.float64)
+    return load().mux_pool_init_quotas(pool.handle, w.size, w.ctypes.data)
+
+
+def mux_pool_adapt_quotas(pool: Pool, n_models: int, low: float, high: float, step: float):
+    """Returns (status, blocks of quota moved)."""
+    moved = C.c_int64(-1)
+    rc = load().mux_pool_adapt_quotas(pool.handle, n_models, low, high, step, C.byref(moved))
+    return rc, moved.value
 
 
 def mux_alloc_blocks_status(pool: Pool, model_id: int, n: int, out: Optional[np.ndarray] = None):

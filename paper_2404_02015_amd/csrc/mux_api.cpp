@@ -5,6 +5,7 @@
 // allocation sits on the serving path; engines request blocks, fill them, keep them across
 // a request's prefill and decoding jobs and release them when the request finishes.
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <new>
 
@@ -28,6 +29,24 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 }  // namespace
 
+namespace {
+bool model_in_range(int32_t m) { return m >= 0 && m < MUX_MAX_MODELS; }
+
+// Deal `total` indivisible blocks out to `n` claimants: claimant i already has whole[i] and a
+// remainder key[i] (larger = closer to one more block; negative = takes no part).  The blocks
+// go one each to the largest keys, the lower index first among equals.
+template <class Key>
+void deal_leftovers(int64_t total, std::vector<int64_t> &whole, const std::vector<Key> &key)
+{
+    std::vector<int32_t> order;
+    for (size_t i = 0; i < key.size(); ++i)
+        if (!(key[i] < Key(0))) order.push_back(static_cast<int32_t>(i));
+    if (order.empty()) return;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[a] > key[b]; });
+    for (size_t k = 0; total > 0; k = (k + 1) % order.size(), --total) whole[order[k]] += 1;
+}
+}  // namespace
+
 extern "C" {
 
 int mux_pool_create(mux_pool_t **out, void *kv_base, size_t kv_bytes, int64_t num_blocks, int32_t block_size,
@@ -48,6 +67,8 @@ int mux_pool_create(mux_pool_t **out, void *kv_base, size_t kv_bytes, int64_t nu
         p->holder.assign(static_cast<size_t>(num_blocks), mux_pool::kFree);
         p->free_ids.resize(static_cast<size_t>(num_blocks));
         p->used_by_model.assign(MUX_MAX_MODELS, 0);
+        p->quota_of_model.assign(MUX_MAX_MODELS, mux_pool::kNoQuota);
+        p->peak_of_model.assign(MUX_MAX_MODELS, 0);
     } catch (const std::bad_alloc &) {
         delete p;
         return MUX_ERR_INVALID;
@@ -108,6 +129,8 @@ int mux_alloc_blocks(mux_pool_t *pool, int32_t model_id, int64_t n, int32_t *out
     if (n == 0) return MUX_OK;
     if (!out_ids) return MUX_ERR_INVALID;
     std::lock_guard<std::mutex> g(pool->lock);
+    const int64_t cap = pool->quota_of_model[model_id];
+    if (cap != mux_pool::kNoQuota && n > cap - pool->used_by_model[model_id]) return MUX_ERR_QUOTA;
     const size_t have = pool->free_ids.size();
     if (static_cast<uint64_t>(n) > have) return MUX_ERR_NOMEM;
     const int32_t *top = pool->free_ids.data() + have;  // one past the id popped first
@@ -118,7 +141,8 @@ int mux_alloc_blocks(mux_pool_t *pool, int32_t model_id, int64_t n, int32_t *out
         out_ids[i] = id;
     }
     pool->free_ids.resize(have - static_cast<size_t>(n));
-    pool->used_by_model[model_id] += n;
+    const int64_t now = (pool->used_by_model[model_id] += n);
+    pool->peak_of_model[model_id] = std::max(pool->peak_of_model[model_id], now);
     return MUX_OK;
 }
 
@@ -143,6 +167,98 @@ int mux_free_blocks(mux_pool_t *pool, int32_t model_id, int64_t n, const int32_t
     for (int64_t i = 0; i < n; ++i) holder[ids[i]] = mux_pool::kFree;
     pool->free_ids.insert(pool->free_ids.end(), ids, ids + n);
     pool->used_by_model[model_id] -= n;
+    return MUX_OK;
+}
+
+int mux_pool_set_quota(mux_pool_t *pool, int32_t model_id, int64_t max_blocks)
+{
+    if (!pool || !model_in_range(model_id)) return MUX_ERR_INVALID;
+    if (max_blocks != mux_pool::kNoQuota && (max_blocks < 0 || max_blocks > pool->num_blocks)) return MUX_ERR_INVALID;
+    std::lock_guard<std::mutex> g(pool->lock);
+    pool->quota_of_model[model_id] = max_blocks;
+    return MUX_OK;
+}
+
+int mux_pool_get_quota(const mux_pool_t *pool, int32_t model_id, int64_t *out)
+{
+    if (!pool || !model_in_range(model_id) || !out) return MUX_ERR_INVALID;
+    std::lock_guard<std::mutex> g(pool->lock);
+    *out = pool->quota_of_model[model_id];
+    return MUX_OK;
+}
+
+int mux_pool_peak_used(const mux_pool_t *pool, int32_t model_id, int64_t *out)
+{
+    if (!pool || !model_in_range(model_id) || !out) return MUX_ERR_INVALID;
+    std::lock_guard<std::mutex> g(pool->lock);
+    *out = pool->peak_of_model[model_id];
+    return MUX_OK;
+}
+
+int mux_pool_init_quotas(mux_pool_t *pool, int32_t n_models, const double *weights)
+{
+    if (!pool || n_models <= 0 || n_models > MUX_MAX_MODELS || !weights) return MUX_ERR_INVALID;
+    double sum = 0.0;
+    for (int32_t m = 0; m < n_models; ++m) {
+        if (!std::isfinite(weights[m]) || weights[m] < 0.0) return MUX_ERR_INVALID;
+        sum += weights[m];
+    }
+    if (!std::isfinite(sum) || !(sum > 0.0)) return MUX_ERR_INVALID;
+    std::vector<int64_t> whole(static_cast<size_t>(n_models));
+    std::vector<double> part(static_cast<size_t>(n_models));
+    int64_t dealt = 0;
+    for (int32_t m = 0; m < n_models; ++m) {
+        const double share = static_cast<double>(pool->num_blocks) * weights[m] / sum;
+        const double fl = std::floor(share);
+        whole[m] = static_cast<int64_t>(fl);
+        part[m] = share - fl;
+        dealt += whole[m];
+    }
+    deal_leftovers(pool->num_blocks - dealt, whole, part);
+    std::lock_guard<std::mutex> g(pool->lock);
+    std::copy(whole.begin(), whole.end(), pool->quota_of_model.begin());
+    return MUX_OK;
+}
+
+int mux_pool_adapt_quotas(mux_pool_t *pool, int32_t n_models, double low, double high, double step, int64_t *moved)
+{
+    if (!pool || n_models <= 0 || n_models > MUX_MAX_MODELS) return MUX_ERR_INVALID;
+    if (!(low >= 0.0) || !(high >= low) || !std::isfinite(high) || !(step >= 0.0) || !(step <= 1.0))
+        return MUX_ERR_INVALID;
+    std::lock_guard<std::mutex> g(pool->lock);
+    const size_t n = static_cast<size_t>(n_models);
+    for (size_t m = 0; m < n; ++m)
+        if (pool->quota_of_model[m] == mux_pool::kNoQuota) return MUX_ERR_INVALID;
+    // who gives how much, and who takes with which weight
+    std::vector<int64_t> gives(n, 0), gets(n, 0), rest(n, -1);
+    int64_t collected = 0, demand = 0;
+    for (size_t m = 0; m < n; ++m) {
+        const double quota = static_cast<double>(pool->quota_of_model[m]);
+        const double peak = static_cast<double>(pool->peak_of_model[m]);
+        if (peak < low * quota) {
+            gives[m] = static_cast<int64_t>(std::floor(step * (quota - peak)));
+            collected += gives[m];
+        } else if (pool->peak_of_model[m] > 0 && peak >= high * quota) {
+            demand += pool->peak_of_model[m];
+            rest[m] = 0;   // marks a taker until its remainder is known
+        }
+    }
+    int64_t total = 0;
+    if (collected > 0 && demand > 0) {
+        int64_t dealt = 0;
+        for (size_t m = 0; m < n; ++m) {
+            if (rest[m] < 0) continue;
+            const int64_t scaled = collected * pool->peak_of_model[m];   // < 2^62: both factors fit 31 bits
+            gets[m] = scaled / demand;
+            rest[m] = scaled % demand;
+            dealt += gets[m];
+        }
+        deal_leftovers(collected - dealt, gets, rest);
+        for (size_t m = 0; m < n; ++m) pool->quota_of_model[m] += gets[m] - gives[m];
+        total = collected;
+    }
+    for (size_t m = 0; m < n; ++m) pool->peak_of_model[m] = pool->used_by_model[m];
+    if (moved) *moved = total;
     return MUX_OK;
 }
 

@@ -22,9 +22,12 @@ struct mux_pool {
     std::vector<int32_t> free_ids;          // LIFO: back() is handed out next
     std::vector<int32_t> holder;            // per block: model id, kFree, or kPending during a free call
     std::vector<int64_t> used_by_model;     // MUX_MAX_MODELS counters
+    std::vector<int64_t> quota_of_model;    // cap on used_by_model, kNoQuota = none
+    std::vector<int64_t> peak_of_model;     // high-water mark of used_by_model since the last quota adaptation
 
     static constexpr int32_t kFree = -1;
     static constexpr int32_t kPending = -2;
+    static constexpr int64_t kNoQuota = -1;
 };
 
 // Kernel launchers (defined in the .hip files).  They validate nothing; the C entry
