@@ -111,10 +111,12 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const char *p)
 // targets and would wait for all of them before every LDS read and every barrier, so the copy,
 // the barrier and the waits of the pipeline are issued by hand; the compiler still orders the
 // ordinary LDS reads and writes it generates itself ("memory" clobbers keep them in place).
-__device__ __forceinline__ void lds_dma16(const void *src, unsigned lds_addr)
+// A lane's source is base (wave-uniform, scalar registers) + offset (per lane); its 16 bytes
+// land at LDS address lds_addr + 16 * lane (lds_addr is wave-uniform).
+__device__ __forceinline__ void lds_dma16(const char *base, unsigned offset, unsigned lds_addr)
 {
-    // every lane's 16 bytes at `src` land at LDS address lds_addr + 16 * lane (lds_addr is wave-uniform)
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(offset), "s"(base), "s"(lds_addr) : "memory", "m0");
 }
 __device__ __forceinline__ void raw_barrier() { asm volatile("s_barrier" ::: "memory"); }
 // s_waitcnt with one counter set and the others left at "do not wait"
@@ -127,8 +129,11 @@ __device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xF | (0
 
 // D: head size.  HT: query heads per workgroup (1, 2 or 4); the other kWaves / HT waves take
 // further row slices.  CB: 16-row column blocks per wave.
+#ifndef MUX_PREFILL_MIN_WGS
+#define MUX_PREFILL_MIN_WGS 2
+#endif
 template <int D, int HT, int CB>
-__global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const PrefillArgs a)
+__global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_kernel(const PrefillArgs a)
 {
     constexpr int RS = 16 * CB;                  // query rows per wave
     constexpr int RT = kWaves / HT;              // row slices per workgroup
@@ -215,15 +220,20 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const Prefill
             qreg[b][k] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qrow + (32 * k + 8 * g) * 2));
     }
 
-    f32x4 acc[CB][NT];
-    float m_ref[CB], l_run[CB];                  // reference max (log2 domain) and this lane's share of the row sum
+    // O^T accumulators, and the row sums of P as one more output slab: with an all-ones A
+    // operand the matrix core adds up the (bf16-rounded, as in the numerator) weights of a row
+    // over all 32 tokens of a step, so the sum costs no vector instructions and needs no
+    // exchange between lane groups (every element of l_acc[b] of lane (g, c) is the sum of row c)
+    f32x4 acc[CB][NT], l_acc[CB];
+    float m_ref[CB];                             // reference max (log2 domain)
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
         m_ref[b] = kNegBig;
-        l_run[b] = 0.f;
+        l_acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int n = 0; n < NT; ++n) acc[b][n] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
 
     // Block ids of the whole key range go to LDS once, so that the K/V loads inside the loop
     // do not wait for a table load first (contexts past kMaxCachedIds blocks read the table).
@@ -234,39 +244,51 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const Prefill
 
     // One step's K and V tiles, global -> LDS.  A wave-level load deposits lane l's 16 bytes at
     // (uniform base) + 16 l, i.e. a contiguous 1 KiB run of the tile; the swizzle decides which
-    // piece of the row the lane fetches.  The step index is clamped so that every iteration
-    // issues the same number of loads and the wait counts below stay exact.
+    // piece of the row the lane fetches.  The runs of one wave lie inside ONE block, so the block
+    // address is wave-uniform (scalar registers) and the lane's part of the address - its row
+    // inside the block and its swizzled piece - is the same in every step (two registers per run).
+    // The step index is clamped so that every iteration issues the same number of loads and the
+    // wait counts below stay exact.
+    constexpr int TPR = 64 / PPR;                        // tokens per 1 KiB run
+    static_assert(kBS % (PPT * TPR) == 0, "the runs of a wave must not straddle blocks");
+    const int my_blk = wave * PPT * TPR / kBS;           // which of the step's two blocks this wave copies
+    unsigned koff[PPT], voff[PPT];
+#pragma unroll
+    for (int p = 0; p < PPT; ++p) {
+        const int slot = (wave * PPT + p) * 64 + lane;   // 16-byte slot inside the tile
+        const int tok = slot / PPR, pos = slot % PPR;
+        koff[p] = (tok % kBS) * ROWB + (pos ^ kswz(tok)) * 16;
+        voff[p] = kBS * ROWB + (tok % kBS) * ROWB + (pos ^ vswz(tok)) * 16;
+    }
     const unsigned smem_lds = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) char *)smem));
-    auto issue = [&](int step_raw, int buf) {
-        const int step = min(step_raw, n_steps - 1);
+    auto block_id = [&](int step_raw) {                  // id of this wave's block in a step (same in all lanes)
+        const int blk = min(step_raw, n_steps - 1) * 2 + my_blk;
+        if (blk < n_ids) return sm_ids[blk];
+        return blk < a.max_blocks ? min(max(trow[blk], 0), a.num_blocks - 1) : 0;   // a stale or corrupt entry must not leave the pool
+    };
+    auto issue = [&](int id, int buf) {
+        const char *base = a.kv_base + static_cast<long long>(__builtin_amdgcn_readfirstlane(id)) * a.block_bytes;
         const unsigned kb = smem_lds + buf * (KBUF + VBUF);
         const unsigned vb = kb + KBUF;
 #pragma unroll
         for (int p = 0; p < PPT; ++p) {
             const int run = wave * PPT + p;              // which 1 KiB run of the tile
-            const int slot = run * 64 + lane;            // 16-byte slot inside the tile
-            const int tok = slot / PPR, pos = slot % PPR;
-            const int blk = step * 2 + tok / kBS;
-            int id;                                      // a stale or corrupt entry must not leave the pool
-            if (blk < n_ids)
-                id = sm_ids[blk];
-            else
-                id = blk < a.max_blocks ? min(max(trow[blk], 0), a.num_blocks - 1) : 0;
-            const char *src = a.kv_base + static_cast<long long>(id) * a.block_bytes + (tok % kBS) * ROWB;
-            lds_dma16(src + (pos ^ kswz(tok)) * 16, kb + run * 1024);
-            lds_dma16(src + kBS * ROWB + (pos ^ vswz(tok)) * 16, vb + run * 1024);
+            lds_dma16(base, koff[p], kb + run * 1024);
+            lds_dma16(base, voff[p], vb + run * 1024);
         }
     };
     constexpr int LPS = 2 * PPT;                         // copies per step per lane
 
     wait_vmem<0>();   // q rows and table entries have arrived: from here on only tile copies are in flight
-    for (int t = 0; t < kBufs - 1; ++t) issue(t, t);
+    for (int t = 0; t < kBufs - 1; ++t) issue(block_id(t), t);
+    int next_id = block_id(kBufs - 1);   // fetched one iteration ahead of its use
     for (int step = 0; step < n_steps; ++step) {
         const int buf = step % kBufs;
         // this wave's copies for `step` have landed once only the younger steps' copies are in flight
         wait_vmem<(kBufs - 2) * LPS>();
         raw_barrier();     // everyone's copies for `step` are in LDS, and everyone is done with step - 1 ...
-        issue(step + kBufs - 1, (step + kBufs - 1) % kBufs);   // ... so its buffer can be refilled
+        issue(next_id, (step + kBufs - 1) % kBufs);            // ... so its buffer can be refilled
+        next_id = block_id(step + kBufs);
         const int kv0 = step * kKT;
         if (kv0 + kKT > total_len) {
             // slots past the sequence's tokens hold stale bytes (possibly NaN): zero those V rows
@@ -295,53 +317,51 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const Prefill
                     for (int b = 0; b < CB; ++b)
                         st[b][hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[b][k], st[b][hf], 0, 0, 0);
                 }
-            // causal mask (only steps that touch the diagonal; a separate code path, so that the
-            // other steps carry no compares), lazy online softmax
-            bf16x8 pop[CB];
-            auto softmax = [&](auto diag_tag) {
-                constexpr bool DIAG = decltype(diag_tag)::value;
+            // Causal mask, only on steps that touch the diagonal (wave-uniform test): masked scores
+            // become a huge negative number, whose weight below is exactly 0.  This is the only
+            // code that differs between the two kinds of step and it touches nothing but the
+            // scores: keeping the accumulators out of duplicated code paths lets them stay in
+            // place in their registers (with the softmax written out once per kind of step they
+            // were copied to fresh registers in every step).
+            if (kv0 + kKT - 1 > wave_first_pos) {
 #pragma unroll
-                for (int b = 0; b < CB; ++b) {
-                    float sc[8];
-                    float mx = kNegBig;
+                for (int b = 0; b < CB; ++b)
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            float x = st[b][hf][i];
-                            if (DIAG && kv0 + hf * 16 + 4 * g + i > my_pos[b]) x = kNegBig;
-                            sc[hf * 4 + i] = x;
-                            mx = fmaxf(mx, x);
-                        }
-                    mx = row_max_across_groups(mx);
-                    mx *= a.scale_log2e;                       // scale > 0: the max commutes with it
-                    if (__builtin_amdgcn_ballot_w64(mx > m_ref[b] + kLazyBits) != 0) {
-                        const float m_new = fmaxf(m_ref[b], mx);
-                        const float alpha = __builtin_amdgcn_exp2f(m_ref[b] - m_new);
-                        l_run[b] *= alpha;
+                        for (int i = 0; i < 4; ++i)
+                            if (kv0 + hf * 16 + 4 * g + i > my_pos[b]) st[b][hf][i] = kNegBig;
+            }
+            // lazy online softmax
+            bf16x8 pop[CB];
 #pragma unroll
-                        for (int n = 0; n < NT; ++n) acc[b][n] *= alpha;
-                        m_ref[b] = m_new;
-                    }
-                    float psum = 0.f;
+            for (int b = 0; b < CB; ++b) {
+                float mx = kNegBig;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[j], a.scale_log2e, -m_ref[b]));
-                        if (DIAG && sc[j] == kNegBig) e = 0.f;
-                        sc[j] = e;
-                        psum += e;
-                    }
-                    l_run[b] += psum;
-                    // P^T operand: k-slot j of lane group g is token 4g+j of half 0 (j < 4) or half 1
-                    const u32x4 pw = {pack_bf16(sc[0], sc[1]), pack_bf16(sc[2], sc[3]), pack_bf16(sc[4], sc[5]),
-                                      pack_bf16(sc[6], sc[7])};
-                    pop[b] = __builtin_bit_cast(bf16x8, pw);
+                for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) mx = fmaxf(mx, st[b][hf][i]);
+                mx = row_max_across_groups(mx) * a.scale_log2e;   // scale > 0: the max commutes with it
+                if (__builtin_amdgcn_ballot_w64(mx > m_ref[b] + kLazyBits) != 0) {
+                    const float m_new = fmaxf(m_ref[b], mx);
+                    const float alpha = __builtin_amdgcn_exp2f(m_ref[b] - m_new);
+                    l_acc[b] *= alpha;
+#pragma unroll
+                    for (int n = 0; n < NT; ++n) acc[b][n] *= alpha;
+                    m_ref[b] = m_new;
                 }
-            };
-            if (kv0 + kKT - 1 > wave_first_pos)   // wave-uniform
-                softmax(std::true_type{});
-            else
-                softmax(std::false_type{});
+                float e[8];
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        e[hf * 4 + i] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[b][hf][i], a.scale_log2e, -m_ref[b]));
+                // P^T operand: k-slot j of lane group g is token 4g+j of half 0 (j < 4) or half 1
+                const u32x4 pw = {pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3]), pack_bf16(e[4], e[5]),
+                                  pack_bf16(e[6], e[7])};
+                pop[b] = __builtin_bit_cast(bf16x8, pw);
+                l_acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pop[b], l_acc[b], 0, 0, 0);
+            }
 #pragma unroll
             for (int n = 0; n < NT; ++n) {
                 // V^T operand: lane (g, j) points at dims 16n + 4(j%4) .. +3 of token 4g + j/4; the
@@ -363,8 +383,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const Prefill
     if (!wave_active) return;
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
-        float l_tot = l_run[b] + __shfl_xor(l_run[b], 16);
-        l_tot += __shfl_xor(l_tot, 32);
+        const float l_tot = l_acc[b][0];
         const int r = my_row0 + 16 * b + c;
         if (r >= q_len) continue;                // surplus row of a ragged tile
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
