@@ -52,8 +52,9 @@ constexpr int kBS = 16;              // tokens per block on this path
 constexpr int kKT = 32;              // tokens per pipeline step (two blocks)
 constexpr int kMaxCachedIds = 1024;  // block ids kept in LDS (16 384 tokens of context)
 #ifndef MUX_PREFILL_BUFS
-#define MUX_PREFILL_BUFS 4
+#define MUX_PREFILL_BUFS 3
 #endif
+constexpr int kWgsPerCu = 3;          // 3 x (3 x 16 KiB + ids) of LDS and 3 x 4 x 170 vector registers fit a compute unit
 constexpr int kBufs = MUX_PREFILL_BUFS;  // LDS buffers: kBufs - 1 steps are in flight while one is consumed
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -3.0e38f;
@@ -406,8 +407,8 @@ void launch_mfma(PrefillArgs a, int max_q_len, hipStream_t st)
     const int group = a.n_q_heads / a.n_kv_heads;
     a.n_passes = (group + HT - 1) / HT;
     const long long units = static_cast<long long>(a.n_seqs) * a.n_kv_heads * a.n_passes;
-    // 2 workgroups fit a CU; with fewer than ~4 rounds of workgroups balance beats L2 reuse
-    a.tile_bundle = units * a.n_row_tiles <= 4 * 2 * 256 ? 1 : a.n_row_tiles;
+    // with fewer than ~4 rounds of workgroups balance beats L2 reuse
+    a.tile_bundle = units * a.n_row_tiles <= 4 * kWgsPerCu * 256 ? 1 : a.n_row_tiles;
     const long long bundles = (a.n_row_tiles + a.tile_bundle - 1) / a.tile_bundle;
     const long long grid = (units + 7) / 8 * 8 * bundles * a.tile_bundle;   // see the blockIdx mapping in the kernel
     constexpr int kLds = kBufs * 2 * kKT * D * 2 + kMaxCachedIds * 4;
@@ -463,9 +464,18 @@ int mux_launch_prefill_attn(const mux_pool *pool, void *out, const void *q, cons
     a.scale_log2e = scale * kLog2e;
     const int group = n_q_heads / n_kv_heads;
     const int ht = group >= 4 ? 4 : (group >= 2 ? 2 : 1);
-    // two column blocks per wave once the chunks are long enough to fill them
+    // Two column blocks per wave (each K / V operand read feeds two matrix instructions) once the
+    // chunks are long enough to fill them AND the launch would still fill the GPU: a launch of
+    // few rows over long contexts (the last stage of a chunked batch) is a few long-running
+    // workgroups, and halving their rows doubles the workgroups that share the work.
     static const int forced_cb = std::getenv("MUX_PREFILL_CB") ? std::atoi(std::getenv("MUX_PREFILL_CB")) : 0;
-    const int cb = forced_cb ? forced_cb : (max_q_len >= 32 * (kWaves / ht) ? 2 : 1);
+    int cb = max_q_len >= 32 * (kWaves / ht) ? 2 : 1;
+    if (cb == 2) {
+        const long long rows2 = 32 * (kWaves / ht);
+        const long long est_wgs = static_cast<long long>(n_kv_heads) * ((group + ht - 1) / ht) * (total_q / rows2 + (n_seqs + 1) / 2);
+        if (est_wgs < kWgsPerCu * 256) cb = 1;
+    }
+    if (forced_cb) cb = forced_cb;
     const long long rows_per_wg = 16 * cb * (kWaves / ht);
     const long long grid = ((max_q_len + rows_per_wg - 1) / rows_per_wg + 1) * (static_cast<long long>(n_seqs) * n_kv_heads * ((group + ht - 1) / ht) + 7);
     if (grid > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
