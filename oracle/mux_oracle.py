@@ -17,6 +17,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mux_oracle.c")
+_SRCS = [_SRC, os.path.join(_HERE, "adbs_oracle.c")]
 _LIB = os.path.join(_HERE, "libmux_oracle.so")
 
 OK, ERR_INVALID, ERR_NOMEM, ERR_QUOTA, ERR_UNSUPPORTED = 0, -1, -2, -3, -5
@@ -25,11 +26,11 @@ BF16, FP32 = 0, 1
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc -O2 and OpenMP; returns the library path."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS)
     if force or stale:
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"]
+            ["gcc", "-O2", "-fopenmp", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp] + _SRCS + ["-lm"]
         )
         os.replace(tmp, _LIB)
     return _LIB
@@ -71,6 +72,17 @@ def lib():
         L.oracle_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32]
         L.oracle_decode_weights.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32]
         L.oracle_num_threads.restype = i32
+        f64 = C.c_double
+        L.adbs_oracle_create.argtypes = [C.POINTER(vp), vp, i32, vp, i32, i32, i32, i32, i32, f64, f64, f64]
+        L.adbs_oracle_destroy.argtypes = [vp]
+        L.adbs_oracle_destroy.restype = None
+        L.adbs_oracle_submit.argtypes = [vp, i32, i64, i32, i32]
+        L.adbs_oracle_step.argtypes = [vp, C.POINTER(i32)]
+        L.adbs_oracle_job.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+        L.adbs_oracle_job_seqs.argtypes = [vp, i32, vp, vp, vp, vp]
+        L.adbs_oracle_table.argtypes = [vp, i32]
+        L.adbs_oracle_table.restype = C.POINTER(i32)
+        L.adbs_oracle_counts.argtypes = [vp, i32, vp]
         _lib = L
     return _lib
 
@@ -257,3 +269,61 @@ def attn_row(q, K, V, scale: float, use_f64: bool = False) -> np.ndarray:
 
 def num_threads() -> int:
     return lib().oracle_num_threads()
+
+
+PREFILL, DECODE, PREEMPT = 1, 2, 3
+FLAG_TABLE, FLAG_FINISHED = 1, 2
+
+
+class OracleScheduler:
+    """The oracle's batch scheduler (Algorithm 3) over an OraclePool.  step() runs one iteration
+    and returns its jobs as dicts: kind, model, ids, slots, lens, flags (numpy arrays)."""
+
+    def __init__(self, pool: OraclePool, heads, max_seqs: int, max_blocks: int, max_prefill_tokens: int,
+                 adapt_period: int = 0, low: float = 0.5, high: float = 0.9, step: float = 0.5):
+        self.pool, self.heads = pool, _i32(heads)
+        self.max_seqs, self.max_blocks = max_seqs, max_blocks
+        self._h = C.c_void_p()
+        rc = lib().adbs_oracle_create(C.byref(self._h), pool._h, self.heads.size, _ptr(self.heads), pool.block_size,
+                                      max_seqs, max_blocks, max_prefill_tokens, adapt_period, low, high, step)
+        if rc != OK:
+            self._h = None
+            raise OracleError(rc, "adbs_oracle_create")
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().adbs_oracle_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def submit(self, model: int, req_id: int, prompt_len: int, output_len: int) -> int:
+        return lib().adbs_oracle_submit(self._h, model, req_id, prompt_len, output_len)
+
+    def step(self):
+        n = C.c_int32()
+        rc = lib().adbs_oracle_step(self._h, C.byref(n))
+        if rc != OK:
+            raise OracleError(rc, "adbs_oracle_step")
+        jobs = []
+        for j in range(n.value):
+            kind, model, cnt = C.c_int32(), C.c_int32(), C.c_int32()
+            lib().adbs_oracle_job(self._h, j, C.byref(kind), C.byref(model), C.byref(cnt))
+            ids = np.zeros(cnt.value, np.int64)
+            slots, lens, flags = (np.zeros(cnt.value, np.int32) for _ in range(3))
+            lib().adbs_oracle_job_seqs(self._h, j, _ptr(ids), _ptr(slots), _ptr(lens), _ptr(flags))
+            jobs.append({"kind": kind.value, "model": model.value, "ids": ids, "slots": slots, "lens": lens, "flags": flags})
+        return jobs
+
+    def table(self, model: int) -> np.ndarray:
+        """The model's host block table [max_seqs][heads][max_blocks] (a copy)."""
+        n = self.max_seqs * int(self.heads[model]) * self.max_blocks
+        p = lib().adbs_oracle_table(self._h, model)
+        return np.ctypeslib.as_array(p, shape=(n,)).reshape(self.max_seqs, int(self.heads[model]), self.max_blocks).copy()
+
+    def counts(self, model: int):
+        """(waiting, running, finished, preempted, quota blocks moved so far)."""
+        c = np.zeros(5, np.int64)
+        lib().adbs_oracle_counts(self._h, model, _ptr(c))
+        return tuple(int(x) for x in c)
