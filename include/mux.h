@@ -219,6 +219,71 @@ MUX_API size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seq
                                    int32_t max_ctx_len, int32_t n_q_heads, int32_t n_kv_heads);
 
 /* Human-readable name of a status code (static storage). */
+/* ---------------------------------------------------------------------------------
+ * Batch scheduler (Section 3.3, Algorithm 3: adaptive batch scheduling).  Host code: it
+ * owns the request queues and the block tables of the colocated models, takes blocks from
+ * the pool (under the models' quotas) and tells the caller which jobs to launch; it
+ * launches nothing itself and never touches device memory.
+ *
+ * One call of mux_sched_step is one iteration of the algorithm's loop:
+ *  1. Prefill.  The first model, round-robin from the model after the one served last,
+ *     that has a waiting request forms one prefill job: its waiting requests in arrival
+ *     order, taken one by one while the job stays within max_prefill_tokens tokens (the
+ *     first request is taken whatever its length), a sequence slot (lowest free) is left,
+ *     and the request's ceil(len / block_size) x heads blocks fit the model's quota and the
+ *     pool (one mux_alloc_blocks call per request; ids head-major in its table row).  The
+ *     prefill yields the request's first output token.  A job with no request is no job.
+ *     The algorithm's rule that a prefill without resources holds back decoding concerns
+ *     compute capacity, which a synchronous caller always has; a prefill refused for lack
+ *     of blocks is skipped for this iteration (decoding is what frees blocks).
+ *  2. Decoding.  Every model with running requests, starting with a model that rotates by
+ *     one per iteration, runs one step for all of them: each request appends the token it
+ *     produced last (context + 1; a context that was a multiple of block_size opens a new
+ *     block per head: one mux_alloc_blocks call of `heads` ids per such request, in
+ *     admission order) and produces the next.  If the step's new blocks do not fit quota or
+ *     pool, the model's most recently admitted request is preempted - blocks freed, back to
+ *     the FRONT of the waiting queue, to be recomputed (its next prefill covers prompt +
+ *     outputs so far - 1 tokens) - until the step fits.
+ *  3. A request ends when it has produced output_len tokens: its blocks are freed in one
+ *     call, in table order.  Every adapt_period iterations (0 = never)
+ *     mux_pool_adapt_quotas(low_util, high_util, step_fraction) runs over all models.
+ *
+ * Jobs of the last step, in execution order: mux_sched_job gives kind / model / number of
+ * sequences; mux_sched_job_seqs copies per sequence (any pointer may be NULL) the request
+ * id, its slot (row of the model's table), its length (prefill: tokens to prefill, from
+ * position 0; decode: context length including the appended token; preempt: tokens it had
+ * cached) and flags.  mux_sched_table: the model's HOST table, int32
+ * [max_seqs][heads][max_blocks], owned by the scheduler, valid until it is destroyed;
+ * the caller mirrors rows flagged MUX_JOB_FLAG_TABLE to the device.  `heads` is the
+ * number of blocks one block_size-token span of a sequence takes (KV heads x
+ * layers).  mux_sched_counts: counts[0..4] = waiting, running, finished, preemptions of
+ * the model, blocks of quota moved so far (all models).
+ * mux_sched_submit: prompt_len, output_len >= 1 and prompt_len + output_len <=
+ * max_blocks x block_size, else MUX_ERR_INVALID.  Not thread-safe: one caller at a time.
+ * ------------------------------------------------------------------------------- */
+typedef struct mux_sched mux_sched_t;
+typedef struct mux_sched_config {
+    int32_t n_models;
+    const int32_t *heads;        /* HOST array of n_models; copied */
+    int32_t max_seqs;            /* sequence slots (table rows) per model */
+    int32_t max_blocks;          /* table columns: blocks per (sequence, head) */
+    int32_t max_prefill_tokens;  /* token budget of one prefill job */
+    int32_t adapt_period;        /* iterations between quota adaptations, 0 = never */
+    double low_util, high_util, step_fraction;
+} mux_sched_config;
+enum { MUX_JOB_PREFILL = 1, MUX_JOB_DECODE = 2, MUX_JOB_PREEMPT = 3 };
+enum { MUX_JOB_FLAG_TABLE = 1, MUX_JOB_FLAG_FINISHED = 2 };
+MUX_API int mux_sched_create(mux_sched_t **out, mux_pool_t *pool, const mux_sched_config *cfg);
+MUX_API int mux_sched_destroy(mux_sched_t *sched);
+MUX_API int mux_sched_submit(mux_sched_t *sched, int32_t model, int64_t request_id, int32_t prompt_len,
+                             int32_t output_len);
+MUX_API int mux_sched_step(mux_sched_t *sched, int32_t *n_jobs);
+MUX_API int mux_sched_job(const mux_sched_t *sched, int32_t job, int32_t *kind, int32_t *model, int32_t *n_seqs);
+MUX_API int mux_sched_job_seqs(const mux_sched_t *sched, int32_t job, int64_t *request_ids, int32_t *slots,
+                               int32_t *lens, int32_t *flags);
+MUX_API const int32_t *mux_sched_table(const mux_sched_t *sched, int32_t model);
+MUX_API int mux_sched_counts(const mux_sched_t *sched, int32_t model, int64_t *counts);
+
 MUX_API const char *mux_status_string(int status);
 
 #ifdef __cplusplus

@@ -25,8 +25,18 @@ EXPORTS = [
     "mux_alloc_blocks", "mux_free_blocks", "mux_kv_append", "mux_decode_attn", "mux_decode_workspace_bytes",
     "mux_prefill_attn", "mux_prefill_workspace_bytes", "mux_status_string", "mux_decode_step",
     "mux_decode_step_workspace_bytes", "mux_pool_set_quota", "mux_pool_get_quota", "mux_pool_peak_used",
-    "mux_pool_init_quotas", "mux_pool_adapt_quotas",
+    "mux_pool_init_quotas", "mux_pool_adapt_quotas", "mux_sched_create", "mux_sched_destroy", "mux_sched_submit",
+    "mux_sched_step", "mux_sched_job", "mux_sched_job_seqs", "mux_sched_table", "mux_sched_counts",
 ]
+
+MUX_JOB_PREFILL, MUX_JOB_DECODE, MUX_JOB_PREEMPT = 1, 2, 3
+MUX_JOB_FLAG_TABLE, MUX_JOB_FLAG_FINISHED = 1, 2
+
+
+class SchedConfig(C.Structure):
+    _fields_ = [("n_models", C.c_int32), ("heads", C.POINTER(C.c_int32)), ("max_seqs", C.c_int32),
+                ("max_blocks", C.c_int32), ("max_prefill_tokens", C.c_int32), ("adapt_period", C.c_int32),
+                ("low_util", C.c_double), ("high_util", C.c_double), ("step_fraction", C.c_double)]
 
 
 class MuxError(RuntimeError):
@@ -57,6 +67,15 @@ def load() -> C.CDLL:
     L.mux_pool_peak_used.argtypes = [vp, i32, C.POINTER(i64)]
     L.mux_pool_init_quotas.argtypes = [vp, i32, vp]
     L.mux_pool_adapt_quotas.argtypes = [vp, i32, C.c_double, C.c_double, C.c_double, C.POINTER(i64)]
+    L.mux_sched_create.argtypes = [C.POINTER(vp), vp, C.POINTER(SchedConfig)]
+    L.mux_sched_destroy.argtypes = [vp]
+    L.mux_sched_submit.argtypes = [vp, i32, i64, i32, i32]
+    L.mux_sched_step.argtypes = [vp, C.POINTER(i32)]
+    L.mux_sched_job.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+    L.mux_sched_job_seqs.argtypes = [vp, i32, vp, vp, vp, vp]
+    L.mux_sched_table.argtypes = [vp, i32]
+    L.mux_sched_table.restype = C.POINTER(i32)
+    L.mux_sched_counts.argtypes = [vp, i32, vp]
     L.mux_pool_num_used.argtypes = [vp, i32]
     L.mux_pool_num_used.restype = i64
     L.mux_pool_block_bytes.argtypes = [vp]
@@ -289,3 +308,58 @@ def mux_prefill_attn(pool: Pool, out: torch.Tensor, q: torch.Tensor, cu_q_lens: 
                                  _dev(block_tables, torch.int32), n_seqs, total_q, max_q_len, max_ctx_len, n_q, n_kv,
                                  max_blocks, scale, _dev(workspace), ws_bytes, _stream(stream))
     _check(rc, "mux_prefill_attn")
+
+
+class Scheduler:
+    """mux_sched_* with the same semantics: step() runs one iteration of the scheduling loop and
+    returns its jobs as dicts (kind, model, ids, slots, lens, flags as numpy arrays)."""
+
+    def __init__(self, pool: Pool, heads, max_seqs: int, max_blocks: int, max_prefill_tokens: int,
+                 adapt_period: int = 0, low: float = 0.5, high: float = 0.9, step: float = 0.5):
+        self.pool = pool
+        self.heads = np.ascontiguousarray(heads, dtype=np.int32)
+        self.max_seqs, self.max_blocks = max_seqs, max_blocks
+        cfg = SchedConfig(self.heads.size, self.heads.ctypes.data_as(C.POINTER(C.c_int32)), max_seqs, max_blocks,
+                          max_prefill_tokens, adapt_period, low, high, step)
+        h = C.c_void_p()
+        rc = load().mux_sched_create(C.byref(h), pool.handle, C.byref(cfg))
+        if rc != MUX_OK:
+            raise MuxError(rc, "mux_sched_create")
+        self.handle = h.value
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load().mux_sched_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.close()
+
+    def submit(self, model: int, request_id: int, prompt_len: int, output_len: int) -> int:
+        return load().mux_sched_submit(self.handle, model, request_id, prompt_len, output_len)
+
+    def step(self):
+        lib, n = load(), C.c_int32()
+        rc = lib.mux_sched_step(self.handle, C.byref(n))
+        if rc != MUX_OK:
+            raise MuxError(rc, "mux_sched_step")
+        jobs = []
+        for j in range(n.value):
+            kind, model, cnt = C.c_int32(), C.c_int32(), C.c_int32()
+            lib.mux_sched_job(self.handle, j, C.byref(kind), C.byref(model), C.byref(cnt))
+            ids = np.zeros(cnt.value, np.int64)
+            slots, lens, flags = (np.zeros(cnt.value, np.int32) for _ in range(3))
+            lib.mux_sched_job_seqs(self.handle, j, ids.ctypes.data, slots.ctypes.data, lens.ctypes.data, flags.ctypes.data)
+            jobs.append({"kind": kind.value, "model": model.value, "ids": ids, "slots": slots, "lens": lens, "flags": flags})
+        return jobs
+
+    def table(self, model: int) -> np.ndarray:
+        """View of the scheduler's host table [max_seqs][heads][max_blocks] (not a copy)."""
+        n = self.max_seqs * int(self.heads[model]) * self.max_blocks
+        p = load().mux_sched_table(self.handle, model)
+        return np.ctypeslib.as_array(p, shape=(n,)).reshape(self.max_seqs, int(self.heads[model]), self.max_blocks)
+
+    def counts(self, model: int):
+        c = np.zeros(5, np.int64)
+        load().mux_sched_counts(self.handle, model, c.ctypes.data)
+        return tuple(int(x) for x in c)

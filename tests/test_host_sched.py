@@ -1,0 +1,105 @@
+"""The library's batch scheduler (Section 3.3, Algorithm 3) against the oracle's, iteration by
+iteration: the same jobs, request ids, slots, lengths, flags, block tables, pool counters and
+quotas.  CPU only; no kernel is launched.
+"""
+import numpy as np
+import pytest
+
+from oracle import mux_oracle as orc
+from paper_2404_02015_amd import binding as mx
+from paper_2404_02015_amd import workloads as wl
+from test_host_library import host_pool
+
+
+def same_jobs(a, b):
+    assert len(a) == len(b), (a, b)
+    for x, y in zip(a, b):
+        assert x["kind"] == y["kind"] and x["model"] == y["model"]
+        for k in ("ids", "slots", "lens", "flags"):
+            assert np.array_equal(x[k], y[k]), (k, x, y)
+
+
+def make(n_blocks, heads, max_seqs, max_blocks, budget, order=None, **kw):
+    lp = host_pool(n_blocks, order=order)
+    op = orc.OraclePool(n_blocks, 16, 128, init_free_order=order)
+    return lp, op, mx.Scheduler(lp, heads, max_seqs, max_blocks, budget, **kw), orc.OracleScheduler(op, heads, max_seqs, max_blocks, budget, **kw)
+
+
+def test_constants_match_the_header():
+    assert (mx.MUX_JOB_PREFILL, mx.MUX_JOB_DECODE, mx.MUX_JOB_PREEMPT) == (orc.PREFILL, orc.DECODE, orc.PREEMPT)
+    assert (mx.MUX_JOB_FLAG_TABLE, mx.MUX_JOB_FLAG_FINISHED) == (orc.FLAG_TABLE, orc.FLAG_FINISHED)
+
+
+def test_hand_trace_and_argument_errors():
+    lp, op, ls, os_ = make(64, [2], 4, 8, 64)
+    assert ls.submit(0, 100, 20, 5) == 0 == os_.submit(0, 100, 20, 5)
+    for _ in range(6):
+        same_jobs(ls.step(), os_.step())
+    assert mx.mux_pool_num_free(lp) == 64 and ls.counts(0) == os_.counts(0) == (0, 0, 1, 0, 0)
+    for args in ((1, 1, 5, 5), (-1, 1, 5, 5), (0, 1, 0, 5), (0, 1, 5, 0), (0, 1, 100, 29)):   # 100 + 29 > 8 * 16
+        assert ls.submit(*args) == mx.MUX_ERR_INVALID and os_.submit(*args) == orc.ERR_INVALID
+    assert ls.submit(0, 1, 100, 28) == 0
+    with pytest.raises(mx.MuxError):
+        mx.Scheduler(lp, [0], 4, 8, 64)
+    with pytest.raises(mx.MuxError):
+        mx.Scheduler(lp, [2], 0, 8, 64)
+    lib = mx.load()
+    assert lib.mux_sched_step(ls.handle, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_sched_job(ls.handle, 5, None, None, None) == mx.MUX_ERR_INVALID
+    assert not lib.mux_sched_table(ls.handle, 3)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_lockstep_under_random_traffic(seed):
+    rng = np.random.default_rng(300 + seed)
+    n_models = int(rng.integers(1, 6))
+    heads = [int(h) for h in rng.choice([1, 2, 8, 32, 40], n_models)]
+    n_blocks = int(rng.integers(2000, 20000))
+    max_seqs, max_blocks = int(rng.integers(2, 24)), 32
+    quota = seed % 2 == 1
+    lp, op, ls, os_ = make(n_blocks, heads, max_seqs, max_blocks, int(rng.integers(64, 1024)),
+                           order=wl.placement_order(rng, n_blocks),
+                           adapt_period=5 if quota else 0, low=0.6, high=0.85, step=0.4)
+    if quota:
+        w = wl.zipf_shares(n_models, 1.3) * np.array(heads)
+        assert mx.mux_pool_init_quotas(lp, w) == 0 == op.init_quotas(w)
+    rid, kinds = 0, set()
+    for it in range(700):
+        if it < 500:
+            for _ in range(int(rng.poisson(0.8))):
+                m = int(rng.integers(n_models))
+                plen, olen = int(rng.integers(1, 300)), int(rng.integers(1, 200))
+                assert ls.submit(m, rid, plen, olen) == os_.submit(m, rid, plen, olen) == 0
+                rid += 1
+        a, b = ls.step(), os_.step()
+        same_jobs(a, b)
+        kinds |= {j["kind"] for j in a}
+        if it % 20 == 0 or it == 699:
+            for m in range(n_models):
+                assert np.array_equal(ls.table(m), os_.table(m))
+                assert ls.counts(m) == os_.counts(m)
+                assert mx.mux_pool_num_used(lp, m) == op.num_used(m)
+                assert mx.mux_pool_get_quota(lp, m) == op.get_quota(m)
+            assert mx.mux_pool_num_free(lp) == op.num_free()
+    assert {mx.MUX_JOB_PREFILL, mx.MUX_JOB_DECODE} <= kinds
+
+
+def test_lockstep_with_preemptions():
+    rng = np.random.default_rng(9)
+    lp, op, ls, os_ = make(300, [4, 2], 8, 32, 512)
+    rid, preempted = 0, 0
+    for it in range(20000):
+        if it < 1000 and rng.random() < 0.2:
+            m = int(rng.integers(2))
+            plen, olen = int(rng.integers(1, 120)), int(rng.integers(1, 250))
+            assert ls.submit(m, rid, plen, olen) == os_.submit(m, rid, plen, olen) == 0
+            rid += 1
+        a, b = ls.step(), os_.step()
+        same_jobs(a, b)
+        preempted += sum(j["ids"].size for j in a if j["kind"] == mx.MUX_JOB_PREEMPT)
+        if it >= 1000 and all(ls.counts(m)[:2] == (0, 0) for m in range(2)):
+            break
+    assert preempted > 0
+    for m in range(2):
+        assert ls.counts(m) == os_.counts(m) and ls.counts(m)[:2] == (0, 0)
+    assert mx.mux_pool_num_free(lp) == 300 == op.num_free()
