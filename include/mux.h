@@ -244,8 +244,13 @@ MUX_API size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seq
  *     pool, the model's most recently admitted request is preempted - blocks freed, back to
  *     the FRONT of the waiting queue, to be recomputed (its next prefill covers prompt +
  *     outputs so far - 1 tokens) - until the step fits.
- *  3. A request ends when it has produced output_len tokens: its blocks are freed in one
- *     call, in table order.  Every adapt_period iterations (0 = never)
+ *  3. A request ends when it has produced output_len tokens.  Its blocks and slot are
+ *     released at the START of the next mux_sched_step (one mux_free_blocks call per
+ *     request, ids in table order, requests in the order they ended): the caller launches
+ *     the job that ends it after this call returns, and that job still reads them.  The
+ *     caller must order the kernels of one step before those of the next (blocks freed at
+ *     a step's start may be handed to another model in that same step).
+ *     Every adapt_period iterations (0 = never)
  *     mux_pool_adapt_quotas(low_util, high_util, step_fraction) runs over all models.
  *
  * Jobs of the last step, in execution order: mux_sched_job gives kind / model / number of

@@ -30,8 +30,10 @@
  *    recomputed: its next prefill covers prompt + outputs so far minus the last) until the step
  *    fits.  Every model with running requests gets one decoding step per iteration; the model
  *    served first rotates by one per iteration.
- *  - A request ends when it has produced output_len tokens; its blocks go back in one call, in
- *    table order (head-major).
+ *  - A request ends when it has produced output_len tokens.  Its blocks and its slot go back at
+ *    the START of the next iteration (one call per request, ids in table order, head-major,
+ *    requests in the order they ended): the job that ends a request still has to read them, and
+ *    whoever launches the jobs does so after the iteration's decisions are taken.
  *  - Every adapt_period iterations the quotas are adapted (oracle_adapt_quotas).
  */
 #include <stdint.h>
@@ -81,7 +83,13 @@ typedef struct {
     int32_t *slots, *lens, *flags;
 } job_t;
 
+typedef struct {
+    int32_t model, slot, ctx;
+} ended_t;
+
 typedef struct adbs_oracle {
+    ended_t *ended; /* requests that ended in the last iteration: blocks still held */
+    int32_t n_ended, cap_ended;
     oracle_pool *pool;
     int32_t n_models, block_size, max_seqs, max_blocks, max_prefill_tokens, adapt_period;
     double low, high, step;
@@ -140,21 +148,39 @@ static int64_t room(adbs_oracle *s, int32_t model)
     return r < 0 ? 0 : r;
 }
 
-/* give back all blocks of a running request (table order: head-major) and its slot */
-static void release(adbs_oracle *s, int32_t model, req_t *r)
+/* give back all blocks of a sequence (table order: head-major) and its slot */
+static void release_slot(adbs_oracle *s, int32_t model, int32_t slot, int32_t ctx)
 {
     model_t *md = &s->m[model];
-    int32_t nb = blocks_for(s, r->ctx);
+    int32_t nb = blocks_for(s, ctx);
     int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * (size_t)(nb * md->heads + 1));
-    int32_t *row = row_of(s, md, r->slot);
+    int32_t *row = row_of(s, md, slot);
     int32_t k = 0;
     for (int32_t h = 0; h < md->heads; ++h)
         for (int32_t b = 0; b < nb; ++b) ids[k++] = row[h * s->max_blocks + b];
     oracle_free_blocks(s->pool, model, k, ids);
     free(ids);
-    md->slot_used[r->slot] = 0;
+    md->slot_used[slot] = 0;
+}
+
+/* a preempted request gives everything back at once: no job of this iteration reads its blocks */
+static void release(adbs_oracle *s, int32_t model, req_t *r)
+{
+    release_slot(s, model, r->slot, r->ctx);
     r->slot = -1;
     r->ctx = 0;
+}
+
+/* a request that ended keeps blocks and slot until the next iteration starts */
+static void retire(adbs_oracle *s, int32_t model, const req_t *r)
+{
+    if (s->n_ended == s->cap_ended) {
+        s->cap_ended = s->cap_ended ? 2 * s->cap_ended : 16;
+        s->ended = (ended_t *)realloc(s->ended, sizeof(ended_t) * (size_t)s->cap_ended);
+    }
+    ended_t e = {model, r->slot, r->ctx};
+    s->ended[s->n_ended++] = e;
+    s->m[model].finished++;
 }
 
 int adbs_oracle_create(adbs_oracle **out, oracle_pool *pool, int32_t n_models, const int32_t *heads,
@@ -206,6 +232,7 @@ void adbs_oracle_destroy(adbs_oracle *s)
         free(s->jobs[j].flags);
     }
     free(s->jobs);
+    free(s->ended);
     free(s->m);
     free(s);
 }
@@ -277,8 +304,7 @@ static void prefill_phase(adbs_oracle *s)
         if (r.gen >= r.output_len) {
             flags |= ADBS_FLAG_FINISHED;
             job_add(job, r.id, slot, len, flags);
-            release(s, model, &r);
-            md->finished++;
+            retire(s, model, &r);
         } else {
             job_add(job, r.id, slot, len, flags);
             md->run[md->n_run++] = r;
@@ -329,8 +355,7 @@ static void decode_phase(adbs_oracle *s)
             r.gen += 1;
             if (r.gen >= r.output_len) {
                 job_add(job, r.id, r.slot, r.ctx, flags | ADBS_FLAG_FINISHED);
-                release(s, model, &r);
-                md->finished++;
+                retire(s, model, &r);
             } else {
                 job_add(job, r.id, r.slot, r.ctx, flags);
                 md->run[kept++] = r;
@@ -345,6 +370,8 @@ int adbs_oracle_step(adbs_oracle *s, int32_t *n_jobs)
 {
     if (!s || !n_jobs) return ADBS_ERR_INVALID;
     s->n_jobs = 0;
+    for (int32_t i = 0; i < s->n_ended; ++i) release_slot(s, s->ended[i].model, s->ended[i].slot, s->ended[i].ctx);
+    s->n_ended = 0;
     prefill_phase(s);
     decode_phase(s);
     s->iteration++;

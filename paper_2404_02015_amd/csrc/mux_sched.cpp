@@ -53,6 +53,8 @@ struct mux_sched {
     int64_t iterations = 0, stamp = 0, quota_moved = 0;
     std::vector<Job> jobs;
     std::vector<int32_t> scratch_ids;
+    struct Ended { int32_t model, slot, cached; };
+    std::vector<Ended> ended;   // ended in the last iteration: blocks and slot held until the next one starts
 
     int32_t *row(Model &m, int32_t slot) { return m.table.data() + static_cast<size_t>(slot) * m.heads * cfg.max_blocks; }
     int32_t blocks_of(int32_t tokens) const { return (tokens + pool->block_size - 1) / pool->block_size; }
@@ -67,18 +69,31 @@ struct mux_sched {
         return std::max<int64_t>(free_now, 0);
     }
 
-    void give_back(int32_t model, Request &r)
+    void free_sequence(int32_t model, int32_t slot, int32_t cached)
     {
         Model &m = models[model];
-        const int32_t nb = blocks_of(r.cached);
+        const int32_t nb = blocks_of(cached);
         scratch_ids.clear();
-        const int32_t *t = row(m, r.slot);
+        const int32_t *t = row(m, slot);
         for (int32_t h = 0; h < m.heads; ++h)
             scratch_ids.insert(scratch_ids.end(), t + h * cfg.max_blocks, t + h * cfg.max_blocks + nb);
         mux_free_blocks(pool, model, static_cast<int64_t>(scratch_ids.size()), scratch_ids.data());
-        m.slot_taken[r.slot] = 0;
+        m.slot_taken[slot] = 0;
+    }
+
+    // preemption: nothing launched for this iteration reads the request's blocks, they go back now
+    void give_back(int32_t model, Request &r)
+    {
+        free_sequence(model, r.slot, r.cached);
         r.slot = -1;
         r.cached = 0;
+    }
+
+    // end of a request: its last job still reads the blocks, so they go back when the next iteration starts
+    void retire(int32_t model, const Request &r)
+    {
+        ended.push_back(Ended{model, r.slot, r.cached});
+        ++models[model].n_finished;
     }
 
     void run_prefill()
@@ -118,8 +133,7 @@ struct mux_sched {
             tokens += len;
             if (r.produced >= r.output_len) {
                 job.add(r.id, r.slot, len, MUX_JOB_FLAG_TABLE | MUX_JOB_FLAG_FINISHED);
-                give_back(pick, r);
-                ++m.n_finished;
+                retire(pick, r);
             } else {
                 job.add(r.id, r.slot, len, MUX_JOB_FLAG_TABLE);
                 m.running.push_back(r);
@@ -168,8 +182,7 @@ struct mux_sched {
             ++r.produced;
             if (r.produced >= r.output_len) {
                 job.add(r.id, r.slot, r.cached, flag | MUX_JOB_FLAG_FINISHED);
-                give_back(model, r);
-                ++m.n_finished;
+                retire(model, r);
             } else {
                 job.add(r.id, r.slot, r.cached, flag);
                 still.push_back(r);
@@ -235,6 +248,8 @@ int mux_sched_step(mux_sched_t *s, int32_t *n_jobs)
 {
     if (!s || !n_jobs) return MUX_ERR_INVALID;
     s->jobs.clear();
+    for (const mux_sched::Ended &e : s->ended) s->free_sequence(e.model, e.slot, e.cached);
+    s->ended.clear();
     s->run_prefill();
     const int32_t n = static_cast<int32_t>(s->models.size());
     for (int32_t k = 0; k < n; ++k) s->run_decode((s->first_decode + k) % n);

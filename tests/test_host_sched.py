@@ -35,6 +35,7 @@ def test_hand_trace_and_argument_errors():
     assert ls.submit(0, 100, 20, 5) == 0 == os_.submit(0, 100, 20, 5)
     for _ in range(6):
         same_jobs(ls.step(), os_.step())
+        assert mx.mux_pool_num_free(lp) == op.num_free()
     assert mx.mux_pool_num_free(lp) == 64 and ls.counts(0) == os_.counts(0) == (0, 0, 1, 0, 0)
     for args in ((1, 1, 5, 5), (-1, 1, 5, 5), (0, 1, 0, 5), (0, 1, 5, 0), (0, 1, 100, 29)):   # 100 + 29 > 8 * 16
         assert ls.submit(*args) == mx.MUX_ERR_INVALID and os_.submit(*args) == orc.ERR_INVALID
@@ -102,4 +103,5 @@ def test_lockstep_with_preemptions():
     assert preempted > 0
     for m in range(2):
         assert ls.counts(m) == os_.counts(m) and ls.counts(m)[:2] == (0, 0)
+    same_jobs(ls.step(), os_.step())
     assert mx.mux_pool_num_free(lp) == 300 == op.num_free()

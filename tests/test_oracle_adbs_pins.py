@@ -28,8 +28,9 @@ def test_single_request_hand_trace():
     assert brief(s.step()) == [(D, 0, [100], [0], [22], [0])]
     assert brief(s.step()) == [(D, 0, [100], [0], [23], [0])]
     assert brief(s.step()) == [(D, 0, [100], [0], [24], [F])]
-    assert p.num_free() == 64 and s.counts(0) == (0, 0, 1, 0, 0)
-    assert s.step() == []
+    # the ended request keeps its blocks until the next iteration starts (its last job reads them)
+    assert p.num_free() == 60 and s.counts(0) == (0, 0, 1, 0, 0)
+    assert s.step() == [] and p.num_free() == 64
     # the blocks came back in table order: the next request gets them in reverse (LIFO)
     assert s.submit(0, 101, 16, 3) == 0
     assert brief(s.step()) == [(P, 0, [101], [0], [16], [T]), (D, 0, [101], [0], [17], [T])]   # 16 % 16 == 0: new block
@@ -37,7 +38,7 @@ def test_single_request_hand_trace():
     # frees pushed 0,1,2,3: the prefill pops 3 (head 0), 2 (head 1); the new block pops 1, 0
     assert t[0, :, 0].tolist() == [3, 2] and t[0, :, 1].tolist() == [1, 0]
     assert brief(s.step()) == [(D, 0, [101], [0], [18], [F])]
-    assert p.num_free() == 64
+    assert s.step() == [] and p.num_free() == 64
 
 
 def test_single_output_request_ends_with_its_prefill():
@@ -45,7 +46,8 @@ def test_single_output_request_ends_with_its_prefill():
     s = orc.OracleScheduler(p, [1], 2, 4, 64)
     s.submit(0, 7, 10, 1)
     assert brief(s.step()) == [(P, 0, [7], [0], [10], [T | F])]
-    assert p.num_free() == 16 and s.counts(0)[:3] == (0, 0, 1)
+    assert p.num_free() == 15 and s.counts(0)[:3] == (0, 0, 1)
+    assert s.step() == [] and p.num_free() == 16
 
 
 def test_round_robin_prefill_and_rotating_decode_start():
@@ -132,17 +134,18 @@ def test_preemption_of_the_youngest_and_recompute_length():
     for rid in (0, 1):
         steps = sum(e[2].count(rid) for e in events if e[1] == D)
         assert steps == 39
+    assert s.step() == []                                          # flushes the blocks of the request that ended last
     assert p.num_free() == 6 and s.counts(0)[2:4] == (2, len(pre))
 
 
-def _check_state(p, s, n_models, heads, B, live):
+def _check_state(p, s, n_models, heads, B, live, ended):
     """Block conservation and table sanity: what the pool says a model holds is what its running
-    requests need; all ids in use are distinct."""
+    requests (and those that ended in this iteration) need; all ids in use are distinct."""
     seen = set()
     for m in range(n_models):
         t = s.table(m)
         need = 0
-        for (mm, rid), (slot, ctx) in live.items():
+        for (mm, rid), (slot, ctx) in list(live.items()) + ended:
             if mm != m:
                 continue
             nb = (ctx + B - 1) // B
@@ -180,6 +183,7 @@ def test_invariants_under_random_traffic(seed, with_quota):
                 submitted[m].append(rid)
                 rid += 1
         jobs = s.step()
+        ended = []
         kinds = [j["kind"] for j in jobs]
         assert kinds.count(P) <= 1 and (P not in kinds or kinds[0] == P)       # at most one prefill job, first
         dec_models = [j["model"] for j in jobs if j["kind"] == D]
@@ -201,18 +205,18 @@ def test_invariants_under_random_traffic(seed, with_quota):
                     assert live.pop(key) == (slot, ln)
                 if fl & F:
                     assert j["kind"] != X
-                    live.pop(key)
+                    ended.append((key, live.pop(key)))
                     assert dec_steps[key] == want_out[key] - 1                   # exactly output_len tokens
                     del want_out[key]
         if with_quota:
             for m in range(n_models):
                 assert p.num_used(m) <= max(p.get_quota(m), p.peak_used(m))
         if it % 50 == 0:
-            _check_state(p, s, n_models, heads, B, live)
+            _check_state(p, s, n_models, heads, B, live, ended)
         if it >= 900 and not want_out:
             break
     assert not want_out and not live, "every request must finish once arrivals stop"
-    assert p.num_free() == n_blocks
+    assert s.step() == [] and p.num_free() == n_blocks
     for m in range(n_models):
         assert first_admit[m] == submitted[m]                                    # first admission is first come first served
         assert s.counts(m)[:2] == (0, 0)
