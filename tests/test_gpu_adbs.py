@@ -1,0 +1,121 @@
+"""The batch scheduler driving the kernels on the GPU (Section 3.3, Algorithm 3 on top of the
+unified KV pool of Section 3.4): every job the library's scheduler hands out is launched through
+the C ABI by the engine, and mirrored - same seeded K/V/Q - into the oracle's own pool through the
+oracle's own scheduler.  Jobs, tables and pool counters must be identical, every attention output
+within the bf16 tolerance of the oracle's.
+"""
+import numpy as np
+import pytest
+import torch
+
+import mux_harness as H
+from oracle import mux_oracle as orc
+from paper_2404_02015_amd import adbs_engine as eng
+from paper_2404_02015_amd import binding as mx
+from paper_2404_02015_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+class SeededSource:
+    """K/V/Q of request r of model m are N(0,1) values rounded to bf16, drawn from a generator
+    seeded with (seed, m, r): a recomputed request gets the same values again."""
+
+    def __init__(self, shapes, d, max_len, seed):
+        self.shapes, self.d, self.max_len, self.seed, self.cache = shapes, d, max_len, seed, {}
+
+    def _get(self, m, r):
+        if (m, r) not in self.cache:
+            s = self.shapes[m]
+            base = (self.seed * 1000 + m) * 100000 + 3 * r
+            self.cache[(m, r)] = tuple(wl.as_bits(wl.randn_values(base + i, (self.max_len, h, self.d))).copy()
+                                       for i, h in enumerate((s.n_kv_heads, s.n_kv_heads, s.n_q_heads)))
+        return self.cache[(m, r)]
+
+    def bits(self, m, r, which, p0, p1):
+        return self._get(m, r)[which][p0:p1]
+
+    def _t(self, a):
+        return torch.from_numpy(a.view(np.int16).copy()).cuda().view(torch.bfloat16)
+
+    def kv(self, m, r, p0, p1):
+        return self._t(self.bits(m, r, 0, p0, p1)), self._t(self.bits(m, r, 1, p0, p1))
+
+    def q(self, m, r, p0, p1):
+        return self._t(self.bits(m, r, 2, p0, p1))
+
+
+def oracle_job_outputs(op, os_, src, shapes, job, scale):
+    m, slots, lens, ids = job["model"], job["slots"], job["lens"], job["ids"]
+    table = os_.table(m)
+    hq = shapes[m].n_q_heads
+    if job["kind"] == orc.PREFILL:
+        k = np.concatenate([src.bits(m, r, 0, 0, n) for r, n in zip(ids, lens)])
+        v = np.concatenate([src.bits(m, r, 1, 0, n) for r, n in zip(ids, lens)])
+        q = np.concatenate([src.bits(m, r, 2, 0, n) for r, n in zip(ids, lens)])
+        op.kv_append(k, v, np.repeat(slots, lens), np.concatenate([np.arange(n) for n in lens]), np.maximum(table, 0))
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        return op.prefill_attn(q, cu, np.zeros(len(lens), np.int32), np.maximum(table[slots], 0), hq, scale)
+    k = np.concatenate([src.bits(m, r, 0, n - 1, n) for r, n in zip(ids, lens)])
+    v = np.concatenate([src.bits(m, r, 1, n - 1, n) for r, n in zip(ids, lens)])
+    q = np.concatenate([src.bits(m, r, 2, n - 1, n) for r, n in zip(ids, lens)])
+    op.kv_append(k, v, slots, lens - 1, np.maximum(table, 0))
+    return op.decode_attn(q, np.maximum(table[slots], 0), lens, hq, scale)
+
+
+@pytest.mark.parametrize("case", ["roomy", "tight-quota", "preempting"])
+def test_scheduler_drives_kernels_like_the_oracle(case):
+    print("[case] adbs %s" % case, flush=True)
+    shapes = [wl.ModelShape("a", 8, 8, 128), wl.ModelShape("b", 16, 4, 128), wl.ModelShape("c", 4, 4, 128)]
+    d, B = 128, 16
+    n_blocks = {"roomy": 4000, "tight-quota": 600, "preempting": 300}[case]
+    max_seqs, max_blocks, budget = 6, 24, 256
+    rng = np.random.default_rng({"roomy": 1, "tight-quota": 2, "preempting": 3}[case])
+    order = wl.placement_order(rng, n_blocks)
+    kv = torch.empty(n_blocks * 2 * B * d * 2, dtype=torch.uint8, device="cuda")
+    kv.view(torch.int16).fill_(0x7FC1)                      # NaN pattern: a read of a never-written slot shows
+    pool = mx.mux_pool_create(kv, n_blocks, B, d, mx.MUX_BF16, order)
+    op = orc.OraclePool(n_blocks, B, d, init_free_order=order)
+    kw = dict(adapt_period=4, low=0.5, high=0.85, step=0.5) if case == "tight-quota" else {}
+    if case == "tight-quota":
+        w = np.array([1.0, 3.0, 1.0]) * np.array([s.n_kv_heads for s in shapes])
+        assert mx.mux_pool_init_quotas(pool, w) == 0 == op.init_quotas(w)
+    src = SeededSource(shapes, d, max_blocks * B, seed=77)
+    engine = eng.Engine(pool, shapes, max_seqs, max_blocks, budget, src, **kw)
+    os_ = orc.OracleScheduler(op, [s.n_kv_heads for s in shapes], max_seqs, max_blocks, budget, **kw)
+    scale = H.default_scale(d)
+    rid, worst, kinds = 0, 0.0, set()
+    for it in range(400):
+        if it < 60:
+            for _ in range(int(rng.poisson(0.7))):
+                m = int(rng.integers(3))
+                plen, olen = int(rng.integers(1, 200)), int(rng.integers(1, 60))
+                engine.submit(m, rid, plen, olen)
+                assert os_.submit(m, rid, plen, olen) == 0
+                rid += 1
+        results = engine.step()
+        want_jobs = os_.step()
+        assert len(results) == len(want_jobs)
+        for (job, out), wj in zip(results, want_jobs):
+            assert job["kind"] == wj["kind"] and job["model"] == wj["model"]
+            for k in ("ids", "slots", "lens", "flags"):
+                assert np.array_equal(job[k], wj[k])
+            kinds.add(job["kind"])
+            if job["kind"] == mx.MUX_JOB_PREEMPT:
+                continue
+            want = oracle_job_outputs(op, os_, src, shapes, wj, scale)
+            worst = max(worst, H.assert_close(out, want, "bf16", "%s job of model %d, iteration %d" % (
+                "prefill" if job["kind"] == mx.MUX_JOB_PREFILL else "decode", job["model"], it)))
+        for m in range(3):
+            assert np.array_equal(engine.sched.table(m), os_.table(m))
+            assert mx.mux_pool_num_used(pool, m) == op.num_used(m)
+        if it >= 60 and engine.idle():
+            break
+    torch.cuda.synchronize()
+    assert engine.idle() and rid > 20
+    engine.step(), os_.step()
+    assert mx.mux_pool_num_free(pool) == n_blocks == op.num_free()
+    assert {mx.MUX_JOB_PREFILL, mx.MUX_JOB_DECODE} <= kinds
+    if case == "preempting":
+        assert mx.MUX_JOB_PREEMPT in kinds
+    print("adbs %s: %d requests, %d iterations, max abs err %.2e" % (case, rid, engine.iterations, worst), flush=True)
