@@ -292,6 +292,74 @@ def cpu_baseline(models, budget_s: float = 12.0):
     }
 
 
+def run_adbs(args) -> int:
+    """Second workload: the batch scheduler (Algorithm 3) serving a Poisson stream of requests for
+    three colocated models, rates 2:8:8 and request lengths 2:1:1 as in the paper's cache-usage
+    ablation (Section 4.4), on a pool that cannot hold everybody's demand.  Every job is launched
+    on the GPU.  Run twice: with quotas in proportion to rate x blocks per token (adapted
+    periodically) and without quotas; reports output tokens/s and how the block usage is shared."""
+    from paper_2404_02015_amd import adbs_engine as eng
+
+    shapes = [wl.LLAMA_13B, wl.LLAMA_7B, wl.LLAMA_7B]
+    rates = np.array([2.0, 8.0, 8.0])
+    length_scale = [2, 1, 1]
+    B, d, n_blocks, max_seqs, max_blocks = 16, 128, 40000, 64, 96
+    iters = max(args.steps, 1) * 8
+    warm = max(args.warmup, 1) * 8
+    per_iter = 1.0 * rates / rates.sum()               # requests per iteration and model
+    out = {}
+    for mode in ("adbs", "no-quota"):
+        kv = torch.empty(n_blocks * 2 * B * d * 2, dtype=torch.uint8, device="cuda")
+        rng = np.random.Generator(np.random.PCG64(20240402))
+        pool = mx.mux_pool_create(kv, n_blocks, B, d, mx.MUX_BF16, wl.placement_order(rng, n_blocks))
+        kw = {}
+        if mode == "adbs":
+            weights = rates * np.array([s.n_kv_heads for s in shapes])
+            assert mx.mux_pool_init_quotas(pool, weights) == 0
+            kw = dict(adapt_period=16, low=0.5, high=0.9, step=0.25)
+        engine = eng.Engine(pool, shapes, max_seqs, max_blocks, 2048, eng.DeviceRandomSource(shapes, d, seed=1),
+                            keep_outputs=False, **kw)
+        use = np.zeros(len(shapes))
+        rid, t0, tok0 = 0, None, 0
+        for it in range(warm + iters):
+            if it == warm:
+                torch.cuda.synchronize()
+                t0, tok0 = time.perf_counter(), sum(m.tokens for m in engine.models)
+            for m in range(len(shapes)):
+                for _ in range(int(rng.poisson(per_iter[m]))):
+                    engine.submit(m, rid, int(rng.integers(64, 385)) * length_scale[m], int(rng.integers(32, 129)) * length_scale[m])
+                    rid += 1
+            engine.step()
+            if it >= warm:
+                use += [mx.mux_pool_num_used(pool, m) for m in range(len(shapes))]
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        counts = [engine.sched.counts(m) for m in range(len(shapes))]
+        out[mode] = {
+            "tokens_per_s": (sum(m.tokens for m in engine.models) - tok0) / dt,
+            "ms_per_iteration": dt / iters * 1e3,
+            "block_usage_share": [round(float(x), 4) for x in use / max(use.sum(), 1)],
+            "mean_blocks_in_use": float(use.sum() / iters),
+            "finished": [c[2] for c in counts], "preemptions": [c[3] for c in counts], "waiting_at_end": [c[0] for c in counts],
+            "quota_blocks_moved": counts[0][4],
+        }
+        del engine, pool, kv
+        torch.cuda.empty_cache()
+    a = out["adbs"]
+    line = {
+        "metric": "ADBS-scheduled serving: output tokens/s, attention path only", "value": a["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": iters, "warmup": warm, "ms_per_step": a["ms_per_iteration"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 storage, f32 arithmetic", "data": "synthetic",
+        "config": {"workload": "batch scheduler (Algorithm 3) over 13B/7B/7B-shaped models, Poisson arrivals 2:8:8, request "
+                               "lengths 2:1:1, %d head-blocks, %d slots per model; every job launched on the GPU by a Python "
+                               "driver (host-bound)" % (n_blocks, max_seqs)},
+        "rate_share": [round(float(x), 4) for x in rates / rates.sum()],
+        "adbs": a, "no_quota": out["no-quota"],
+    }
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -304,6 +372,8 @@ def main() -> int:
     ap.add_argument("--fused", action="store_true", help="use mux_decode_step (append + attention in one launch)")
     ap.add_argument("--chain-decode", action="store_true",
                     help="make each decode kernel wait for the previous model's (adds cross-stream event latency)")
+    ap.add_argument("--adbs", action="store_true",
+                    help="second workload: the batch scheduler serving a request stream (prints its own JSON line)")
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 1 GiB device copies after the timed loop")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -317,6 +387,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     mx.load()
+    if args.adbs:
+        return run_adbs(args)
     total = args.steps + args.warmup
     w, pool, models, prefills = build_workload(args.config, total)
     step_models = [] if args.only == "prefill" else models
