@@ -372,6 +372,10 @@ def main() -> int:
     ap.add_argument("--fused", action="store_true", help="use mux_decode_step (append + attention in one launch)")
     ap.add_argument("--chain-decode", action="store_true",
                     help="make each decode kernel wait for the previous model's (adds cross-stream event latency)")
+    ap.add_argument("--cu-fraction", type=float, default=0.0,
+                    help="run every model's stream on the first F x (compute units) only (CU-masked streams)")
+    ap.add_argument("--cu-split", type=float, default=0.0,
+                    help="decode streams get the first F x (compute units), prefill streams the rest")
     ap.add_argument("--adbs", action="store_true",
                     help="second workload: the batch scheduler serving a request stream (prints its own JSON line)")
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 1 GiB device copies after the timed loop")
@@ -399,6 +403,26 @@ def main() -> int:
     if not step_models and not prefills:
         print("bench.py: configuration %d has nothing to run with --only %s" % (args.config, args.only), file=sys.stderr)
         return 2
+
+    # Optional compute partitioning (the analogue of the paper's MPS shares): CU-masked streams.
+    # Unit i of the mask belongs to XCD i % 8, so "the first n" units are spread evenly over the
+    # XCDs when n is a multiple of 8 (a mask that leaves an XCD without units is refused).
+    partition = None
+    if args.cu_fraction > 0 or args.cu_split > 0:
+        n_cu = mx.mux_device_cu_count()
+        frac = args.cu_fraction if args.cu_fraction > 0 else args.cu_split
+        n_first = min(n_cu, max(8, int(round(frac * n_cu / 8)) * 8))
+        torch.cuda.synchronize()
+        masked = []
+        for m in step_models:
+            masked.append(mx.MaskedStream(range(n_first)))
+            m.stream = masked[-1].stream
+        for pm in prefills:
+            cus = range(n_first) if args.cu_fraction > 0 else range(n_first, n_cu)
+            masked.append(mx.MaskedStream(cus))
+            pm.stream = masked[-1].stream
+        partition = {"compute_units": n_cu, "decode_units": n_first if step_models else 0,
+                     "prefill_units": (n_first if args.cu_fraction > 0 else n_cu - n_first) if prefills else 0}
 
     # Every model has its own stream and nothing orders the streams against each other: the
     # small kernels of one model overlap with the other's decode attention, and the decode
@@ -501,6 +525,8 @@ def main() -> int:
             result["dtype"] = "bf16 MFMA, f32 accumulate"
             result["roofline"] = {"kernel": "prefill_attn_kernel", "bound": "mfma", "achieved": fl / t / 1e12, "peak": 2500.0,
                                   "unit": "TFLOP/s", "frac": fl / t / 2.5e15, "traffic": None}
+    if partition:
+        result["config"]["cu_partition"] = partition
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(models)
     print(json.dumps(result))

@@ -289,6 +289,23 @@ MUX_API int mux_sched_job_seqs(const mux_sched_t *sched, int32_t job, int64_t *r
 MUX_API const int32_t *mux_sched_table(const mux_sched_t *sched, int32_t model);
 MUX_API int mux_sched_counts(const mux_sched_t *sched, int32_t model, int64_t *counts);
 
+/* ---------------------------------------------------------------------------------
+ * Compute partitioning (Section 3.4: the parallel runtime assigns compute to prefill and
+ * decoding jobs at SM granularity, with MPS percentages on the paper's hardware).  Here a
+ * job's share is a HIP stream restricted to a set of compute units: every kernel enqueued
+ * on it - through the calls above or otherwise - runs only on those units.
+ *
+ * mux_device_cu_count: *out = compute units of the current device.
+ * mux_stream_create_masked: cu_mask = HOST array of n_words (1..64) 32-bit words, bit b of
+ *   word w set = compute unit 32 w + b may be used (the runtime's numbering; bits beyond the
+ *   device's units are ignored); at least one bit must be set.  *out_stream = a new
+ *   hipStream_t at default priority, owned by the caller until mux_stream_destroy.
+ * Errors: MUX_ERR_INVALID for bad arguments, MUX_ERR_HIP if the runtime refuses.
+ * ------------------------------------------------------------------------------- */
+MUX_API int mux_device_cu_count(int32_t *out);
+MUX_API int mux_stream_create_masked(void **out_stream, const uint32_t *cu_mask, int32_t n_words);
+MUX_API int mux_stream_destroy(void *stream);
+
 MUX_API const char *mux_status_string(int status);
 
 #ifdef __cplusplus

@@ -27,6 +27,7 @@ EXPORTS = [
     "mux_decode_step_workspace_bytes", "mux_pool_set_quota", "mux_pool_get_quota", "mux_pool_peak_used",
     "mux_pool_init_quotas", "mux_pool_adapt_quotas", "mux_sched_create", "mux_sched_destroy", "mux_sched_submit",
     "mux_sched_step", "mux_sched_job", "mux_sched_job_seqs", "mux_sched_table", "mux_sched_counts",
+    "mux_device_cu_count", "mux_stream_create_masked", "mux_stream_destroy",
 ]
 
 MUX_JOB_PREFILL, MUX_JOB_DECODE, MUX_JOB_PREEMPT = 1, 2, 3
@@ -67,6 +68,9 @@ def load() -> C.CDLL:
     L.mux_pool_peak_used.argtypes = [vp, i32, C.POINTER(i64)]
     L.mux_pool_init_quotas.argtypes = [vp, i32, vp]
     L.mux_pool_adapt_quotas.argtypes = [vp, i32, C.c_double, C.c_double, C.c_double, C.POINTER(i64)]
+    L.mux_device_cu_count.argtypes = [C.POINTER(i32)]
+    L.mux_stream_create_masked.argtypes = [C.POINTER(vp), vp, i32]
+    L.mux_stream_destroy.argtypes = [vp]
     L.mux_sched_create.argtypes = [C.POINTER(vp), vp, C.POINTER(SchedConfig)]
     L.mux_sched_destroy.argtypes = [vp]
     L.mux_sched_submit.argtypes = [vp, i32, i64, i32, i32]
@@ -363,3 +367,29 @@ class Scheduler:
         c = np.zeros(5, np.int64)
         load().mux_sched_counts(self.handle, model, c.ctypes.data)
         return tuple(int(x) for x in c)
+
+
+def mux_device_cu_count() -> int:
+    n = C.c_int32()
+    _check(load().mux_device_cu_count(C.byref(n)), "mux_device_cu_count")
+    return n.value
+
+
+class MaskedStream:
+    """A HIP stream restricted to the compute units in `cus` (mux_stream_create_masked), wrapped
+    as a torch stream (`.stream`) so that it can be passed wherever the binding takes one."""
+
+    def __init__(self, cus, device="cuda"):
+        cus = sorted(set(int(c) for c in cus))
+        words = np.zeros(max(cus) // 32 + 1 if cus else 1, dtype=np.uint32)
+        for c in cus:
+            words[c // 32] |= np.uint32(1 << (c % 32))
+        h = C.c_void_p()
+        _check(load().mux_stream_create_masked(C.byref(h), words.ctypes.data, words.size), "mux_stream_create_masked")
+        self.handle, self.cus = h.value, cus
+        self.stream = torch.cuda.ExternalStream(self.handle, device=device)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load().mux_stream_destroy(self.handle)
+            self.handle = None

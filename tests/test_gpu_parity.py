@@ -402,3 +402,30 @@ def test_fused_step_equals_append_then_decode(dtype, head_dim, block_size, n_q, 
                     for which in (0, 1):
                         want_img[bid, which, pos % block_size] = ls.orc.read_row(bid, pos % block_size, which).view(np.uint16)
     assert np.array_equal(got, want_img)
+
+
+def test_decode_on_a_cu_masked_stream_is_bit_identical():
+    """A stream restricted to a quarter of the compute units (spread over all XCDs) runs the same
+    kernels: outputs equal those of an ordinary stream bit for bit, and the oracle's within tolerance."""
+    print("[case] decode on a CU-masked stream", flush=True)
+    n_cu = mx.mux_device_cu_count()
+    assert n_cu >= 64
+    rng = np.random.default_rng(5)
+    ls = H.Lockstep(6000, 16, 128, "bf16", wl.placement_order(rng, 6000))
+    lens = rng.integers(1, 900, 24).astype(np.int32)
+    st = H.open_job(ls, 0, wl.ModelShape("m", 8, 4, 128), lens.size, int(lens.max()) + 16)
+    H.extend(ls, st, lens, seed=3)
+    q = H.make_q(ls, st, 4)
+    scale = H.default_scale(128)
+    plain = H.decode_gpu(ls, st, q, scale)
+    torch.cuda.synchronize()
+    ms = mx.MaskedStream(range(n_cu // 4))
+    try:
+        with torch.cuda.stream(ms.stream):
+            masked = H.decode_gpu(ls, st, q, scale, stream=ms.stream)
+        ms.stream.synchronize()
+        assert torch.equal(masked.view(torch.int16), plain.view(torch.int16))
+        H.assert_close(masked, H.decode_oracle(ls, st, q, scale), "bf16")
+    finally:
+        torch.cuda.synchronize()
+        ms.close()

@@ -182,3 +182,19 @@ def test_decode_plan_workspace_is_monotone_and_bounded():
         b = lib.mux_decode_workspace_bytes(p.handle, 64, 32, 32, ctx)
         assert b >= prev and b < 64 * 32 * (ctx // 16 + 4) * 130 * 4
         prev = b
+
+
+def test_masked_stream_argument_checks_need_no_gpu():
+    lib = mx.load()
+    import ctypes as C
+    h = C.c_void_p()
+    words = np.zeros(2, dtype=np.uint32)
+    assert lib.mux_stream_create_masked(C.byref(h), words.ctypes.data, 2) == mx.MUX_ERR_INVALID     # no unit enabled
+    words[0] = 0xFF
+    assert lib.mux_stream_create_masked(None, words.ctypes.data, 2) == mx.MUX_ERR_INVALID
+    assert lib.mux_stream_create_masked(C.byref(h), None, 2) == mx.MUX_ERR_INVALID
+    assert lib.mux_stream_create_masked(C.byref(h), words.ctypes.data, 0) == mx.MUX_ERR_INVALID
+    assert lib.mux_stream_create_masked(C.byref(h), words.ctypes.data, 65) == mx.MUX_ERR_INVALID
+    assert lib.mux_stream_destroy(None) == mx.MUX_ERR_INVALID
+    assert lib.mux_device_cu_count(None) == mx.MUX_ERR_INVALID
+    assert h.value is None
