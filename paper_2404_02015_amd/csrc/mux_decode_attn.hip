@@ -233,8 +233,37 @@ __global__ __launch_bounds__(256) void decode_plan_kernel(const DecodeArgs a)
 // device-wide atomics on one address take tens of microseconds to drain and every load issued
 // behind one waits for it.
 struct WorkCursor {
-    int round;     // pieces this workgroup has taken so far
+    int round;        // pieces this workgroup has taken so far
+    const int *rows;  // LDS: row of every rank, when the workgroup ranks the rows itself
 };
+
+// Short launches (one span per row, at most kMaxRankedRows rows) skip the plan kernel: every
+// workgroup ranks the rows by context length itself - one row per thread, its rank is the
+// number of rows that are longer (or as long and earlier) - and leaves "row of rank r" in LDS.
+// That costs a few hundred cycles per workgroup and saves a dependent kernel launch per call.
+constexpr int kMaxRankedRows = kThreads;
+
+__device__ __forceinline__ void rank_rows(const DecodeArgs &a, int tid, int *sm_len, int *sm_row)
+{
+    if (a.plan != nullptr) return;
+    const int n_rows = a.n_seqs * a.n_layers;
+    if (tid < n_rows) {
+        int table_row, len;
+        resolve_row(a, tid, table_row, len);
+        sm_len[tid] = len;
+    }
+    __syncthreads();
+    if (tid < n_rows) {
+        const int mine = sm_len[tid];
+        int rank = 0;
+        for (int j = 0; j < n_rows; ++j) {
+            const int other = sm_len[j];
+            rank += (other > mine || (other == mine && j < tid)) ? 1 : 0;
+        }
+        sm_row[rank] = tid;
+    }
+    // the barrier at the top of take_work makes sm_row visible
+}
 
 __device__ __forceinline__ bool take_work(const DecodeArgs &a, int tid, WorkCursor &cur, bool first, int &row, int &split,
                                           int &kvh, int &pass)
@@ -245,12 +274,18 @@ __device__ __forceinline__ bool take_work(const DecodeArgs &a, int tid, WorkCurs
     int w = k * G + ((k & 1) ? G - 1 - static_cast<int>(blockIdx.x) : static_cast<int>(blockIdx.x));
     cur.round = k + 1;
     const int per_unit = a.n_kv_heads * a.n_passes;
-    const int n_units = __builtin_amdgcn_readfirstlane(a.plan[1]);
-    if (w / per_unit >= n_units) return false;
-    const int2 u = reinterpret_cast<const int2 *>(a.plan + 4)[w / per_unit];
+    if (a.plan == nullptr) {
+        if (w / per_unit >= a.n_seqs * a.n_layers) return false;
+        row = __builtin_amdgcn_readfirstlane(cur.rows[w / per_unit]);
+        split = 0;
+    } else {
+        const int n_units = __builtin_amdgcn_readfirstlane(a.plan[1]);
+        if (w / per_unit >= n_units) return false;
+        const int2 u = reinterpret_cast<const int2 *>(a.plan + 4)[w / per_unit];
+        row = __builtin_amdgcn_readfirstlane(u.x);
+        split = __builtin_amdgcn_readfirstlane(u.y);
+    }
     w %= per_unit;
-    row = __builtin_amdgcn_readfirstlane(u.x);
-    split = __builtin_amdgcn_readfirstlane(u.y);
     pass = w % a.n_passes;
     kvh = w / a.n_passes;
     return true;
@@ -312,7 +347,9 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     const int c0 = (lane % LPR) * EPL;    // first head dimension of this lane
 
     int s, split, kvh, pass;   // s: row of q / out / the table
-    WorkCursor cursor{0};
+    __shared__ int sm_rank_len[kMaxRankedRows], sm_rank_row[kMaxRankedRows];
+    rank_rows(a, tid, sm_rank_len, sm_rank_row);
+    WorkCursor cursor{0, sm_rank_row};
     for (bool first = true; take_work(a, tid, cursor, first, s, split, kvh, pass); first = false) {
     // Block ids of this wave: block blk_lo + wave + kWaves * j sits in lane j.  The load does
     // not wait for the context length (any entry inside the table row may be read; entries
@@ -601,7 +638,9 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
     const int g = lane >> 4, c = lane & 15;
 
     int s, split, kvh, pass;   // s: row of q / out / the table
-    WorkCursor cursor{0};
+    __shared__ int sm_rank_len[kMaxRankedRows], sm_rank_row[kMaxRankedRows];
+    rank_rows(a, tid, sm_rank_len, sm_rank_row);
+    WorkCursor cursor{0, sm_rank_row};
     for (bool first = true; take_work(a, tid, cursor, first, s, split, kvh, pass); first = false) {
     const int blk_lo = split * a.span_blocks;
     int table_row, L;
@@ -964,8 +1003,13 @@ int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, co
     const long long most = n_rows * plan.n_splits * n_kv_heads * plan.n_passes;
     const unsigned g = static_cast<unsigned>(std::min<long long>(most, resident_workgroups(fn)));
     a.grid_wgs = static_cast<int>(g);
-    hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(256), 0, st, a);
-    if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
+    static const int force_plan_kernel = env_int("MUX_DECODE_PLAN_KERNEL", 0);
+    if (plan.n_splits == 1 && n_rows <= kMaxRankedRows && !force_plan_kernel) {
+        a.plan = nullptr;   // the workgroups rank the rows themselves (see rank_rows)
+    } else {
+        hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(256), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
+    }
     hipLaunchKernelGGL(fn, dim3(g), dim3(kThreads), 0, st, a);
     if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
     if (plan.n_splits > 1) {
