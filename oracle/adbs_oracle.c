@@ -9,7 +9,7 @@
  * an endless loop, one prefill job picked round-robin over the LLMs and run if its resources are
  * there; then decoding jobs picked round-robin and run for as long as resources are there; then
  * a periodic adaptation of the quotas.  What it leaves open, and how this file reads it (the
- * GPU library follows the same reading, listed in the design notes):
+ * GPU library is written to the same reading):
  *
  *  - An iteration is synchronous: its jobs run to completion inside it.  The rule that a
  *    prefill job which finds no resources holds back the decoding jobs is about compute

@@ -19,9 +19,8 @@
  *     the paper cites and does not restate; the head-wise paging is a memory
  *     layout, so the result it must reach is the textbook one.
  *
- * Readings where the paper is silent (block layout, free-list policy, scale,
- * grouped-query mapping, causal offset, ...) are listed in the design notes of the
- * repository; each function below states the one it uses.
+ * Where the paper is silent (block layout, free-list policy, scale, grouped-query mapping,
+ * causal offset, ...) each function below states the reading it uses.
  *
  * Arithmetic: K/V/Q are widened to fp32 (bf16 -> fp32 is exact), scores, softmax
  * and the weighted sum are computed in fp32 in index order.  A second build of
