@@ -20,6 +20,7 @@ Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import math
 import os
@@ -292,6 +293,58 @@ def cpu_baseline(models, budget_s: float = 12.0):
     }
 
 
+def measure_ceilings(device: str = "cuda"):
+    """What this GPU sustains with nothing in the way: a plain streaming read of 4 GiB and
+    back-to-back bf16 matrix instructions (the library's probe kernels)."""
+    buf = torch.empty(1 << 32, dtype=torch.uint8, device=device)
+    buf.view(torch.int32).fill_(1)
+    sink = torch.zeros(1, dtype=torch.float32, device=device)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_cu = mx.mux_device_cu_count()
+    mx.mux_probe_stream_read(buf, sink, 16 * n_cu)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(3):
+        mx.mux_probe_stream_read(buf, sink, 16 * n_cu)
+    e1.record()
+    torch.cuda.synchronize()
+    read_gbs = 3 * buf.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del buf
+    n_wg = 4 * n_cu                              # four waves per SIMD: one alone cannot issue at full rate
+    mx.mux_probe_mfma(sink, n_wg, 1000)
+    torch.cuda.synchronize()
+    e0.record()
+    flops = mx.mux_probe_mfma(sink, n_wg, 10000)
+    e1.record()
+    torch.cuda.synchronize()
+    return {"stream_read_GBps": read_gbs, "mfma_bf16_TFLOPps": flops / (e0.elapsed_time(e1) * 1e-3) / 1e12,
+            "note": "measured on this GPU by the library's probe kernels: 4 GiB streaming read (16-byte non-temporal loads) "
+                    "in whole 8 KiB chunks per wave and independent v_mfma_f32_16x16x32_bf16 with four waves per SIMD"}
+
+
+def allocator_ns_per_block():
+    """Host cost of the block manager (the one cost the paper flags on this path, Section 3.4,
+    Implementation): nanoseconds per block id, for decode-sized and prefill-sized calls."""
+    n_blocks = 1 << 20
+    kv = torch.empty(64, dtype=torch.uint8)
+    h = ctypes.c_void_p()
+    lib = mx.load()
+    rc = lib.mux_pool_create(ctypes.byref(h), kv.data_ptr(), n_blocks * 8192, n_blocks, 16, 128, mx.MUX_BF16, None)
+    assert rc == 0
+    out = {}
+    for name, n in (("alloc32_free32", 32), ("alloc1280_free1280", 1280)):
+        ids = np.zeros(n, dtype=np.int32)
+        reps = 20000 if n == 32 else 2000
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            lib.mux_alloc_blocks(h, 0, n, ids.ctypes.data)
+            lib.mux_free_blocks(h, 0, n, ids.ctypes.data)
+        out[name] = (time.perf_counter() - t0) / (2 * reps * n) * 1e9
+    lib.mux_pool_destroy(h)
+    out["note"] = "ns per block id, one alloc + one free call through ctypes (call overhead included)"
+    return out
+
+
 def run_adbs(args) -> int:
     """Second workload: the batch scheduler (Algorithm 3) serving a Poisson stream of requests for
     three colocated models, rates 2:8:8 and request lengths 2:1:1 as in the paper's cache-usage
@@ -378,6 +431,7 @@ def main() -> int:
                     help="decode streams get the first F x (compute units), prefill streams the rest")
     ap.add_argument("--adbs", action="store_true",
                     help="second workload: the batch scheduler serving a request stream (prints its own JSON line)")
+    ap.add_argument("--no-solo", action="store_true", help="skip the per-model solo passes after the timed loop")
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 1 GiB device copies after the timed loop")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -393,7 +447,8 @@ def main() -> int:
     mx.load()
     if args.adbs:
         return run_adbs(args)
-    total = args.steps + args.warmup
+    SOLO_STEPS = 10
+    total = args.steps + args.warmup + SOLO_STEPS
     w, pool, models, prefills = build_workload(args.config, total)
     step_models = [] if args.only == "prefill" else models
     for m in models:
@@ -450,6 +505,18 @@ def main() -> int:
     t_enqueued = time.perf_counter() - t0
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # each decode model alone, for comparison with the colocated run
+    solo = []
+    if len(step_models) > 1 and not args.no_solo:
+        for m in step_models:
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            b1 = 0
+            for _ in range(SOLO_STEPS):
+                b, _ = m.step(record=False)
+                b1 += b
+            torch.cuda.synchronize()
+            solo.append({"model": m.shape.name, "seqs": m.n, "GBps": b1 / max(time.perf_counter() - t1, 1e-9) / 1e9})
     if args.pmc_calibration:
         # a plain copy of known size in the same process, for scaling rocprofv3 --pmc byte counters
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -525,6 +592,10 @@ def main() -> int:
             result["dtype"] = "bf16 MFMA, f32 accumulate"
             result["roofline"] = {"kernel": "prefill_attn_kernel", "bound": "mfma", "achieved": fl / t / 1e12, "peak": 2500.0,
                                   "unit": "TFLOP/s", "frac": fl / t / 2.5e15, "traffic": None}
+    if solo:
+        result["solo_decode"] = solo
+    result["ceilings"] = measure_ceilings()
+    result["allocator_ns_per_block"] = allocator_ns_per_block()
     if partition:
         result["config"]["cu_partition"] = partition
     if not args.no_cpu_baseline:

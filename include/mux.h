@@ -306,6 +306,20 @@ MUX_API int mux_device_cu_count(int32_t *out);
 MUX_API int mux_stream_create_masked(void **out_stream, const uint32_t *cu_mask, int32_t n_words);
 MUX_API int mux_stream_destroy(void *stream);
 
+/* ---------------------------------------------------------------------------------
+ * Ceiling probes for reports (not part of the attention path): what the GPU at hand
+ * sustains for a plain streaming read and for back-to-back matrix instructions.  Both only
+ * enqueue on `stream`; the caller times them.
+ * mux_probe_stream_read: `workgroups` x 4 waves read the whole 8 KiB chunks of `bytes`
+ *   (>= 8192) of DEVICE memory at `buf` (16-byte aligned) once, 16 bytes per lane per load;
+ *   `sink` = 4 bytes of DEVICE memory (never written in practice).
+ * mux_probe_mfma: `workgroups` x 4 waves each issue iters x 16 (8 independent chains)
+ *   v_mfma_f32_16x16x32_bf16; *flops (HOST, may be NULL) = floating-point operations of
+ *   the launch; `sink` = 4 bytes of DEVICE memory.
+ * ------------------------------------------------------------------------------- */
+MUX_API int mux_probe_stream_read(const void *buf, size_t bytes, void *sink, int32_t workgroups, void *stream);
+MUX_API int mux_probe_mfma(void *sink, int32_t workgroups, int32_t iters, double *flops, void *stream);
+
 MUX_API const char *mux_status_string(int status);
 
 #ifdef __cplusplus

@@ -27,7 +27,7 @@ EXPORTS = [
     "mux_decode_step_workspace_bytes", "mux_pool_set_quota", "mux_pool_get_quota", "mux_pool_peak_used",
     "mux_pool_init_quotas", "mux_pool_adapt_quotas", "mux_sched_create", "mux_sched_destroy", "mux_sched_submit",
     "mux_sched_step", "mux_sched_job", "mux_sched_job_seqs", "mux_sched_table", "mux_sched_counts",
-    "mux_device_cu_count", "mux_stream_create_masked", "mux_stream_destroy",
+    "mux_device_cu_count", "mux_stream_create_masked", "mux_stream_destroy", "mux_probe_stream_read", "mux_probe_mfma",
 ]
 
 MUX_JOB_PREFILL, MUX_JOB_DECODE, MUX_JOB_PREEMPT = 1, 2, 3
@@ -68,6 +68,8 @@ def load() -> C.CDLL:
     L.mux_pool_peak_used.argtypes = [vp, i32, C.POINTER(i64)]
     L.mux_pool_init_quotas.argtypes = [vp, i32, vp]
     L.mux_pool_adapt_quotas.argtypes = [vp, i32, C.c_double, C.c_double, C.c_double, C.POINTER(i64)]
+    L.mux_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
+    L.mux_probe_mfma.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
     L.mux_device_cu_count.argtypes = [C.POINTER(i32)]
     L.mux_stream_create_masked.argtypes = [C.POINTER(vp), vp, i32]
     L.mux_stream_destroy.argtypes = [vp]
@@ -393,3 +395,15 @@ class MaskedStream:
         if getattr(self, "handle", None):
             load().mux_stream_destroy(self.handle)
             self.handle = None
+
+
+def mux_probe_stream_read(buf: torch.Tensor, sink: torch.Tensor, workgroups: int, stream=None) -> None:
+    _check(load().mux_probe_stream_read(_dev(buf), buf.numel() * buf.element_size(), _dev(sink), workgroups, _stream(stream)),
+           "mux_probe_stream_read")
+
+
+def mux_probe_mfma(sink: torch.Tensor, workgroups: int, iters: int, stream=None) -> float:
+    """Enqueues the probe; returns the floating-point operations of the launch."""
+    flops = C.c_double()
+    _check(load().mux_probe_mfma(_dev(sink), workgroups, iters, C.byref(flops), _stream(stream)), "mux_probe_mfma")
+    return flops.value

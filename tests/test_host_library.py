@@ -198,3 +198,16 @@ def test_masked_stream_argument_checks_need_no_gpu():
     assert lib.mux_stream_destroy(None) == mx.MUX_ERR_INVALID
     assert lib.mux_device_cu_count(None) == mx.MUX_ERR_INVALID
     assert h.value is None
+
+
+def test_probe_argument_checks_need_no_gpu():
+    lib = mx.load()
+    fake = 4096
+    assert lib.mux_probe_stream_read(None, 1 << 20, fake, 64, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_probe_stream_read(fake, 1 << 20, None, 64, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_probe_stream_read(fake, 100, fake, 64, None) == mx.MUX_ERR_INVALID          # less than one chunk
+    assert lib.mux_probe_stream_read(fake + 4, 1 << 20, fake, 64, None) == mx.MUX_ERR_INVALID  # alignment
+    assert lib.mux_probe_stream_read(fake, 1 << 20, fake, 0, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_probe_mfma(None, 4, 4, None, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_probe_mfma(fake, 0, 4, None, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_probe_mfma(fake, 4, 0, None, None) == mx.MUX_ERR_INVALID
