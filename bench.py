@@ -40,7 +40,7 @@ from paper_2404_02015_amd import workloads as wl  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per decode_attn launch on configuration 2, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (each scaled by a plain 1 GiB copy in the same run): 567 486 KiB x 2.000 fetched + 512 KiB written.
-MEASURED_TRAFFIC_CFG2 = {"bytes": 567486.0 * 1024 * 2.0 + 512.0 * 1024, "source": "profiles/decode_attn_config2_pmc.md"}
+MEASURED_TRAFFIC_CFG2 = {"bytes": 567567.7 * 1024 * 2.0 + 512.0 * 1024, "source": "profiles/decode_attn_config2_pmc.md"}
 
 
 class DecodeModel:
