@@ -429,3 +429,71 @@ def test_decode_on_a_cu_masked_stream_is_bit_identical():
     finally:
         torch.cuda.synchronize()
         ms.close()
+
+
+def test_decode_step_captured_in_a_graph_replays_correctly():
+    """One model's step (mux_kv_append + mux_decode_attn) captured once into a HIP graph and
+    replayed for several consecutive steps, with eager work (table growth, input copies, syncs)
+    between the replays; every replay must match the oracle.  The entry points allocate nothing
+    and enqueue kernels only, so they can be captured."""
+    print("[case] decode step in a HIP graph", flush=True)
+    rng = np.random.default_rng(12)
+    B, d = 16, 128
+    shape = wl.ModelShape("g", 16, 4, d)                      # grouped-query: the matrix-core decode kernel
+    lens = rng.integers(1, 700, 20).astype(np.int32)
+    lens[:3] = [15, 16, 17]                                   # block boundaries are crossed during the replays
+    n = lens.size
+    ls = H.Lockstep(8000, B, d, "bf16", wl.placement_order(rng, 8000))
+    st = H.open_job(ls, 0, shape, n, int(lens.max()) + 64)
+    H.extend(ls, st, lens, seed=5)
+    scale = H.default_scale(d)
+    max_ctx = int(lens.max()) + 16
+    k_new = torch.zeros(n, shape.n_kv_heads, d, dtype=torch.bfloat16, device="cuda")
+    v_new = torch.zeros_like(k_new)
+    q = torch.zeros(n, shape.n_q_heads, d, dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros_like(q)
+    tok_seq = torch.arange(n, dtype=torch.int32, device="cuda")
+    tok_pos = torch.zeros(n, dtype=torch.int32, device="cuda")
+    ctx = torch.zeros(n, dtype=torch.int32, device="cuda")
+    ws = torch.empty(mx.mux_decode_workspace_bytes(ls.lib, n, shape.n_q_heads, shape.n_kv_heads, max_ctx), dtype=torch.uint8,
+                     device="cuda")
+
+    def enqueue():
+        mx.mux_kv_append(ls.lib, k_new, v_new, tok_seq, tok_pos, st.tables_dev)
+        mx.mux_decode_attn(ls.lib, out, q, st.tables_dev, ctx, max_ctx, scale, ws)
+
+    def next_inputs(step):
+        new_lens = st.lens + 1
+        wl.grow_tables(ls.alloc, 0, st.tables, st.lens, new_lens, B, want_changed=False)
+        st.tables_dev.copy_(torch.from_numpy(st.tables))
+        kk, vv = wl.randn_values(700 + step, tuple(k_new.shape)), wl.randn_values(800 + step, tuple(k_new.shape))
+        qq = wl.randn_values(900 + step, tuple(q.shape))
+        k_new.copy_(kk)
+        v_new.copy_(vv)
+        q.copy_(qq)
+        tok_pos.copy_(torch.from_numpy(new_lens - 1))
+        ctx.copy_(torch.from_numpy(new_lens))
+        ls.orc.kv_append(H.to_oracle(kk), H.to_oracle(vv), np.arange(n, dtype=np.int32), new_lens - 1, st.tables)
+        st.lens = new_lens
+        return ls.orc.decode_attn(H.to_oracle(qq), st.tables, new_lens, shape.n_q_heads, scale)
+
+    side = torch.cuda.Stream()
+    want = next_inputs(0)                                     # step 0 runs eagerly (also warms every kernel up)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        enqueue()
+    side.synchronize()
+    H.assert_close(out, want, "bf16", "eager step")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        enqueue()
+    worst = 0.0
+    for step in range(1, 6):
+        want = next_inputs(step)
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        worst = max(worst, H.assert_close(out, want, "bf16", "replay %d" % step))
+    ls.check_counters()
+    print("graph replays: max abs err %.2e" % worst, flush=True)
