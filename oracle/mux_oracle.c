@@ -562,6 +562,16 @@ int oracle_decode_weights(oracle_pool *p, double *weights, const void *q, const 
     return rc;
 }
 
+/* Threads the parallel loops use from now on (n >= 1); for timing the oracle on one core. */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int oracle_num_threads(void)
 {
     int n = 1;

@@ -72,6 +72,8 @@ def lib():
         L.oracle_prefill_attn.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32]
         L.oracle_decode_weights.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32]
         L.oracle_num_threads.restype = i32
+        L.oracle_set_num_threads.argtypes = [i32]
+        L.oracle_set_num_threads.restype = None
         f64 = C.c_double
         L.adbs_oracle_create.argtypes = [C.POINTER(vp), vp, i32, vp, i32, i32, i32, i32, i32, f64, f64, f64]
         L.adbs_oracle_destroy.argtypes = [vp]
@@ -269,6 +271,10 @@ def attn_row(q, K, V, scale: float, use_f64: bool = False) -> np.ndarray:
 
 def num_threads() -> int:
     return lib().oracle_num_threads()
+
+
+def set_num_threads(n: int) -> None:
+    lib().oracle_set_num_threads(int(n))
 
 
 PREFILL, DECODE, PREEMPT = 1, 2, 3
