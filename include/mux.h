@@ -263,8 +263,11 @@ MUX_API size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seq
  * number of blocks one block_size-token span of a sequence takes (KV heads x
  * layers).  mux_sched_counts: counts[0..4] = waiting, running, finished, preemptions of
  * the model, blocks of quota moved so far (all models).
- * mux_sched_submit: prompt_len, output_len >= 1 and prompt_len + output_len <=
- * max_blocks x block_size, else MUX_ERR_INVALID.  Not thread-safe: one caller at a time.
+ * mux_sched_submit: prompt_len, output_len >= 1, prompt_len + output_len <= max_blocks x
+ * block_size, and the blocks of prompt_len + output_len - 1 cached tokens must fit the whole
+ * pool (a request that could never fit would be preempted for ever); else MUX_ERR_INVALID.
+ * A request larger than its model's quota is accepted (quotas move) and waits.
+ * Not thread-safe: one caller at a time.
  * ------------------------------------------------------------------------------- */
 typedef struct mux_sched mux_sched_t;
 typedef struct mux_sched_config {

@@ -35,6 +35,9 @@
  *    requests in the order they ended): the job that ends a request still has to read them, and
  *    whoever launches the jobs does so after the iteration's decisions are taken.
  *  - Every adapt_period iterations the quotas are adapted (oracle_adapt_quotas).
+ *  - A request is refused at submission if its prompt_len + output_len - 1 tokens of cache need
+ *    more table columns than a row has or more blocks than the whole pool holds.  (One that
+ *    exceeds its model's QUOTA is accepted: quotas move.)
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -53,6 +56,7 @@ typedef struct oracle_pool oracle_pool;
 int oracle_alloc_blocks(oracle_pool *p, int32_t model_id, int64_t n, int32_t *out_ids);
 int oracle_free_blocks(oracle_pool *p, int32_t model_id, int64_t n, const int32_t *ids);
 int64_t oracle_pool_num_free(const oracle_pool *p);
+int64_t oracle_pool_num_blocks(const oracle_pool *p);
 int64_t oracle_pool_num_used(const oracle_pool *p, int32_t model_id);
 int64_t oracle_get_quota(const oracle_pool *p, int32_t model_id);
 int oracle_adapt_quotas(oracle_pool *p, int32_t n_models, double low, double high, double step, int64_t *moved);
@@ -256,6 +260,9 @@ int adbs_oracle_submit(adbs_oracle *s, int32_t model, int64_t id, int32_t prompt
 {
     if (!s || model < 0 || model >= s->n_models || prompt_len <= 0 || output_len <= 0) return ADBS_ERR_INVALID;
     if ((int64_t)prompt_len + output_len > (int64_t)s->max_blocks * s->block_size) return ADBS_ERR_INVALID;
+    /* a request whose cache could not even fit an empty pool would be preempted for ever */
+    if ((int64_t)blocks_for(s, prompt_len + output_len - 1) * s->m[model].heads > oracle_pool_num_blocks(s->pool))
+        return ADBS_ERR_INVALID;
     req_t r = {id, prompt_len, output_len, 0, 0, -1, 0};
     push_wait(&s->m[model], r, 0);
     return ADBS_OK;

@@ -118,6 +118,7 @@ void oracle_pool_destroy(oracle_pool *p)
 }
 
 int64_t oracle_pool_num_free(const oracle_pool *p) { return p ? p->n_free : ORACLE_ERR_INVALID; }
+int64_t oracle_pool_num_blocks(const oracle_pool *p) { return p ? p->num_blocks : ORACLE_ERR_INVALID; }
 
 int64_t oracle_pool_num_used(const oracle_pool *p, int32_t model_id)
 {

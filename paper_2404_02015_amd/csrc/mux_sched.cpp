@@ -236,6 +236,9 @@ int mux_sched_submit(mux_sched_t *s, int32_t model, int64_t request_id, int32_t 
         return MUX_ERR_INVALID;
     if (static_cast<int64_t>(prompt_len) + output_len > static_cast<int64_t>(s->cfg.max_blocks) * s->pool->block_size)
         return MUX_ERR_INVALID;
+    // the most it will ever cache must fit an empty pool, or it would be preempted for ever
+    if (static_cast<int64_t>(s->blocks_of(prompt_len + output_len - 1)) * s->models[model].heads > s->pool->num_blocks)
+        return MUX_ERR_INVALID;
     Request r;
     r.id = request_id;
     r.prompt_len = prompt_len;

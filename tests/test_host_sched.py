@@ -40,6 +40,10 @@ def test_hand_trace_and_argument_errors():
     for args in ((1, 1, 5, 5), (-1, 1, 5, 5), (0, 1, 0, 5), (0, 1, 5, 0), (0, 1, 100, 29)):   # 100 + 29 > 8 * 16
         assert ls.submit(*args) == mx.MUX_ERR_INVALID and os_.submit(*args) == orc.ERR_INVALID
     assert ls.submit(0, 1, 100, 28) == 0
+    # a request that could never fit the pool is refused: 16 blocks of 2 heads each, 20 tokens need 2 x 2
+    lp2, op2, ls2, os2 = make(3, [2], 4, 8, 64)
+    assert ls2.submit(0, 1, 10, 8) == mx.MUX_ERR_INVALID and os2.submit(0, 1, 10, 8) == orc.ERR_INVALID   # 17 tokens: 4 blocks
+    assert ls2.submit(0, 2, 10, 7) == 0 == os2.submit(0, 2, 10, 7)                                        # 16 tokens: 2 blocks
     with pytest.raises(mx.MuxError):
         mx.Scheduler(lp, [0], 4, 8, 64)
     with pytest.raises(mx.MuxError):
