@@ -90,12 +90,19 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b)
 __device__ __forceinline__ float row_max_across_groups(float x)
 {
     typedef unsigned u32pair __attribute__((ext_vector_type(2)));
+    // plain v_max_f32: fmaxf on values that come out of a bit cast is preceded by one canonicalising
+    // max per operand (the inputs are never NaN here); the trailing wait states cover the hazard
+    // between a vector write and the lane swap that reads it, which the compiler cannot see
+    auto vmax = [](unsigned p, unsigned q) {
+        unsigned r;
+        asm("v_max_f32 %0, %1, %2\n\ts_nop 1" : "=v"(r) : "v"(p), "v"(q));
+        return r;
+    };
     const unsigned u = __float_as_uint(x);
     const u32pair h = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    const float y = fmaxf(__uint_as_float(h[0]), __uint_as_float(h[1]));
-    const unsigned v = __float_as_uint(y);
+    const unsigned v = vmax(h[0], h[1]);
     const u32pair r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    return __uint_as_float(vmax(r[0], r[1]));
 }
 
 // Transposing LDS read: within each group of 16 lanes, lane i receives element (i % 4) of the
@@ -283,12 +290,14 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
     wait_vmem<0>();   // q rows and table entries have arrived: from here on only tile copies are in flight
     for (int t = 0; t < kBufs - 1; ++t) issue(block_id(t), t);
     int next_id = block_id(kBufs - 1);   // fetched one iteration ahead of its use
-    for (int step = 0; step < n_steps; ++step) {
-        const int buf = step % kBufs;
+    // The loop is unrolled over the kBufs buffers so that every LDS address of a step is a
+    // loop-invariant per-lane register plus a compile-time offset.
+    auto run_step = [&](int step, auto buf_tag) {
+        constexpr int buf = decltype(buf_tag)::value;
         // this wave's copies for `step` have landed once only the younger steps' copies are in flight
         wait_vmem<(kBufs - 2) * LPS>();
         raw_barrier();     // everyone's copies for `step` are in LDS, and everyone is done with step - 1 ...
-        issue(next_id, (step + kBufs - 1) % kBufs);            // ... so its buffer can be refilled
+        issue(next_id, (buf + kBufs - 1) % kBufs);             // ... so its buffer can be refilled
         next_id = block_id(step + kBufs);
         const int kv0 = step * kKT;
         if (kv0 + kKT > total_len) {
@@ -378,6 +387,12 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
                     acc[b][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop[b], acc[b][n], 0, 0, 0);
             }
         }
+    };
+    static_assert(kBufs == 3, "the unrolling below names the buffers one by one");
+    for (int step = 0; step < n_steps; step += kBufs) {
+        run_step(step, std::integral_constant<int, 0>{});
+        if (step + 1 < n_steps) run_step(step + 1, std::integral_constant<int, 1>{});
+        if (step + 2 < n_steps) run_step(step + 2, std::integral_constant<int, 2>{});
     }
 
     wait_vmem<0>();   // the clamped copies issued past the last step must land before the LDS is given back
