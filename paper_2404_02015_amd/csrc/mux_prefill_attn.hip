@@ -113,6 +113,18 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const char *p)
     const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
     return __builtin_bit_cast(u32x2, r);
 }
+// The same two reads from an LDS byte address held as a number (see the pinned offsets in the kernel).
+__device__ __forceinline__ u32x2 lds_read_tr16_at(unsigned addr)
+{
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_s16x4 *>(static_cast<size_t>(addr)));
+    return __builtin_bit_cast(u32x2, r);
+}
+__device__ __forceinline__ u32x4 lds_read16_at(unsigned addr)
+{
+    typedef __attribute__((address_space(3))) const u32x4 lds_u32x4;
+    return *reinterpret_cast<lds_u32x4 *>(static_cast<size_t>(addr));
+}
 
 // The K/V tiles travel global -> LDS asynchronously and several of them are meant to stay in
 // flight across workgroup barriers.  The compiler cannot know which LDS buffer an in-flight copy
@@ -167,6 +179,8 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
     // dynamic LDS (the launcher sizes it): kBufs tile buffers, then the block-id cache
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int *sm_ids = reinterpret_cast<int *>(smem + kBufs * (KBUF + VBUF));
+    // the LDS byte address of smem, as a number
+    const unsigned smem_lds = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) char *)smem));
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -268,7 +282,6 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
         koff[p] = (tok % kBS) * ROWB + (pos ^ kswz(tok)) * 16;
         voff[p] = kBS * ROWB + (tok % kBS) * ROWB + (pos ^ vswz(tok)) * 16;
     }
-    const unsigned smem_lds = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) char *)smem));
     auto block_id = [&](int step_raw) {                  // id of this wave's block in a step (same in all lanes)
         const int blk = min(step_raw, n_steps - 1) * 2 + my_blk;
         if (blk < n_ids) return sm_ids[blk];
@@ -290,6 +303,23 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
     wait_vmem<0>();   // q rows and table entries have arrived: from here on only tile copies are in flight
     for (int t = 0; t < kBufs - 1; ++t) issue(block_id(t), t);
     int next_id = block_id(kBufs - 1);   // fetched one iteration ahead of its use
+    // Per-lane LDS addresses of the operand reads inside tile 0 (they never change): K piece of
+    // slab k in row c (the second 16-token half sits 16 rows further), V piece pair of slab n in
+    // row 4g + c/4.  Each is pinned to a register of its own; left alone the compiler keeps a few
+    // partial sums instead and re-adds them before every read.
+    unsigned k_off[KC], v_off[NT];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        k_off[k] = smem_lds + c * ROWB + (((4 * k + g) ^ kswz(c)) * 16);
+        asm volatile("" : "+v"(k_off[k]));
+    }
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int vr = 4 * g + (c >> 2);                        // row inside a half; halves are 16 rows apart,
+        const int vpiece = (2 * n + ((c & 3) >> 1)) ^ vswz(vr);  // which leaves the swizzle unchanged
+        v_off[n] = smem_lds + vr * ROWB + vpiece * 16 + (c & 1) * 8;
+        asm volatile("" : "+v"(v_off[n]));
+    }
     // The loop is unrolled over the kBufs buffers so that every LDS address of a step is a
     // loop-invariant per-lane register plus a compile-time offset.
     auto run_step = [&](int step, auto buf_tag) {
@@ -320,9 +350,7 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
             for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
                 for (int k = 0; k < KC; ++k) {
-                    const int kr = hf * 16 + c;
-                    const bf16x8 kop = __builtin_bit_cast(
-                        bf16x8, *reinterpret_cast<const u32x4 *>(kb + kr * ROWB + (((4 * k + g) ^ kswz(kr)) * 16)));
+                    const bf16x8 kop = __builtin_bit_cast(bf16x8, lds_read16_at(k_off[k] + buf * (KBUF + VBUF) + hf * 16 * ROWB));
 #pragma unroll
                     for (int b = 0; b < CB; ++b)
                         st[b][hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qreg[b][k], st[b][hf], 0, 0, 0);
@@ -376,11 +404,9 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
             for (int n = 0; n < NT; ++n) {
                 // V^T operand: lane (g, j) points at dims 16n + 4(j%4) .. +3 of token 4g + j/4; the
                 // transposing read returns dim 16n + c of tokens 4g .. 4g+3 to lane (g, c)
-                const int vr = 4 * g + (c >> 2);                        // row inside a half; halves are 16 rows apart,
-                const int vpiece = (2 * n + ((c & 3) >> 1)) ^ vswz(vr);  // which leaves the swizzle unchanged
-                const char *vsrc = vb + vr * ROWB + vpiece * 16 + (c & 1) * 8;
-                const u32x2 lo = lds_read_tr16(vsrc);                 // half 0
-                const u32x2 hi = lds_read_tr16(vsrc + 16 * ROWB);     // half 1
+                const unsigned vsrc = v_off[n] + buf * (KBUF + VBUF) + KBUF;
+                const u32x2 lo = lds_read_tr16_at(vsrc);                 // half 0
+                const u32x2 hi = lds_read_tr16_at(vsrc + 16 * ROWB);     // half 1
                 const bf16x8 vop = __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], hi[0], hi[1]});
 #pragma unroll
                 for (int b = 0; b < CB; ++b)
