@@ -293,6 +293,27 @@ def test_chunked_prefill_equals_oracle_and_unchunked(chunk):
     H.assert_close(got, want, "bf16")
 
 
+def test_prefill_chunk_behind_a_context_longer_than_the_id_cache():
+    """The MFMA prefill kernel keeps the block ids of the first 1 024 blocks (16 384 tokens) of a
+    sequence in LDS and reads the table for the rest; a late chunk of a 17 000-token prompt next to a
+    short prompt exercises both paths in one launch."""
+    print("[case] prefill chunk at context 17 000", flush=True)
+    lens = np.array([17000, 300], dtype=np.int32)
+    q_lens = np.array([150, 100], dtype=np.int32)
+    n_q, n_kv, d, B = 4, 2, 128, 16
+    need = int(((lens + B - 1) // B).sum()) * n_kv
+    rng = np.random.Generator(np.random.PCG64(8))
+    ls = H.Lockstep(need + 32, B, d, "bf16", wl.placement_order(rng, need + 32))
+    job = H.open_job(ls, 0, wl.ModelShape("t", n_q, n_kv, d), 2, int(lens.max()) + B)
+    H.extend(ls, job, lens, seed=77)
+    q = wl.randn_values(78, (int(q_lens.sum()), n_q, d)).cuda()
+    q_start = lens - q_lens
+    got = H.prefill_gpu(ls, job, q, q_lens, q_start, H.default_scale(d))
+    want = H.prefill_oracle(ls, job, q, q_lens, q_start, H.default_scale(d))
+    err = H.assert_close(got, want, "bf16")
+    print("max abs err %.2e" % err, flush=True)
+
+
 def test_prefill_rows_equal_decode_rows_on_gpu():
     """A prefill row at position p and a decode step with context p+1 and the same query see the
     same keys; the two kernels agree within the bf16 tolerance of each against the oracle."""
