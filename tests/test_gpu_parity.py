@@ -144,6 +144,20 @@ def test_decode_matches_oracle_across_shapes(dtype, head_dim, block_size, n_q, n
     print("max abs err %.2e" % err)
 
 
+@pytest.mark.parametrize("n_q,n_kv", [(4, 4), (8, 1)])
+def test_decode_batches_too_large_to_rank_in_the_kernel(n_q, n_kv):
+    """More than 256 sequences of one span each: the work list comes from the plan kernel rather
+    than from the attention kernel's own ranking.  Includes empty and one-token contexts."""
+    _say("decode with 700 sequences, Hq=%d Hkv=%d" % (n_q, n_kv))
+    rng = np.random.default_rng(n_q)
+    lens = rng.integers(0, 260, 700)
+    lens[:4] = [0, 1, 16, 17]
+    ls, job, q, got, want = _decode_case("bf16", 128, 16, n_q, n_kv, [int(x) for x in lens], seed=40 + n_q)
+    err = H.assert_close(got, want, "bf16")
+    assert not got[0].float().abs().max().item()
+    print("max abs err %.2e" % err)
+
+
 def test_decode_rows_sum_to_one_on_gpu():
     """V == 1 everywhere => O == 1 (softmax weights sum to one), checked on the GPU path."""
     rng = np.random.Generator(np.random.PCG64(3))
