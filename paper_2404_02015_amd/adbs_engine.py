@@ -37,6 +37,12 @@ class DeviceRandomSource:
     def q(self, model, request_id, pos0, pos1):
         return self._draw(pos1 - pos0, self.shapes[model].n_q_heads)
 
+    def job_values(self, model, request_ids, pos0, pos1):
+        """K, V and Q of a whole job in three draws (rows in request order)."""
+        n = int(np.sum(np.asarray(pos1) - np.asarray(pos0)))
+        s = self.shapes[model]
+        return self._draw(n, s.n_kv_heads), self._draw(n, s.n_kv_heads), self._draw(n, s.n_q_heads)
+
 
 class _ModelState:
     def __init__(self, pool, shape, max_seqs, max_blocks, device):
@@ -76,6 +82,19 @@ class Engine:
     def _dev(self, a, dtype):
         return torch.from_numpy(np.ascontiguousarray(a)).to(self.device, dtype=dtype, non_blocking=False)
 
+    def _job_values(self, model, ids, pos0, pos1):
+        """K/V rows and queries of positions pos0[i] .. pos1[i]-1 of every request of a job,
+        concatenated in request order."""
+        if hasattr(self.values, "job_values"):
+            return self.values.job_values(model, ids, pos0, pos1)
+        ks, vs, qs = [], [], []
+        for rid, p0, p1 in zip(ids.tolist(), pos0.tolist(), pos1.tolist()):
+            k, v = self.values.kv(model, rid, p0, p1)
+            ks.append(k)
+            vs.append(v)
+            qs.append(self.values.q(model, rid, p0, p1))
+        return torch.cat(ks), torch.cat(vs), torch.cat(qs)
+
     def _mirror_rows(self, st: _ModelState, model: int, slots: np.ndarray) -> None:
         if slots.size == 0:
             return
@@ -87,19 +106,15 @@ class Engine:
         st = self.models[model]
         slots, lens, ids = job["slots"], job["lens"], job["ids"]
         self._mirror_rows(st, model, slots)
-        ks, vs, qs = [], [], []
-        for rid, ln in zip(ids.tolist(), lens.tolist()):
-            k, v = self.values.kv(model, rid, 0, ln)
-            ks.append(k)
-            vs.append(v)
-            qs.append(self.values.q(model, rid, 0, ln))
-        k, v, q = torch.cat(ks), torch.cat(vs), torch.cat(qs)
-        tok_seq = self._dev(np.repeat(slots, lens), torch.int32)
-        tok_pos = self._dev(np.concatenate([np.arange(n) for n in lens]), torch.int32)
+        k, v, q = self._job_values(model, ids, np.zeros_like(lens), lens)
+        n, total = len(lens), int(lens.sum())
+        # one host-to-device copy for all the small integer arrays of the job
+        packed = self._dev(np.concatenate([np.repeat(slots, lens), np.concatenate([np.arange(x) for x in lens]),
+                                           [0], np.cumsum(lens), np.zeros(n, np.int64), slots]), torch.int32)
+        tok_seq, tok_pos = packed[:total], packed[total:2 * total]
+        cu, q_start, slots_dev = packed[2 * total:2 * total + n + 1], packed[2 * total + n + 1:2 * total + 2 * n + 1], packed[2 * total + 2 * n + 1:]
         mx.mux_kv_append(self.pool, k, v, tok_seq, tok_pos, st.tables, stream=st.stream)
-        cu = self._dev(np.concatenate([[0], np.cumsum(lens)]), torch.int32)
-        q_start = torch.zeros(len(lens), dtype=torch.int32, device=self.device)
-        tables_job = st.tables.index_select(0, self._dev(slots, torch.int64))
+        tables_job = st.tables.index_select(0, slots_dev)
         out = torch.empty_like(q)
         mx.mux_prefill_attn(self.pool, out, q, cu, q_start, tables_job, int(lens.max()), int(lens.max()), self.scale,
                             stream=st.stream)
@@ -110,19 +125,16 @@ class Engine:
         st = self.models[model]
         slots, lens, ids, flags = job["slots"], job["lens"], job["ids"], job["flags"]
         self._mirror_rows(st, model, slots[(flags & mx.MUX_JOB_FLAG_TABLE) != 0])
-        ks, vs, qs = [], [], []
-        for rid, ln in zip(ids.tolist(), lens.tolist()):
-            k, v = self.values.kv(model, rid, ln - 1, ln)
-            ks.append(k)
-            vs.append(v)
-            qs.append(self.values.q(model, rid, ln - 1, ln))
-        slots_dev = self._dev(slots, torch.int64)
-        mx.mux_kv_append(self.pool, torch.cat(ks), torch.cat(vs), self._dev(slots, torch.int32), self._dev(lens - 1, torch.int32),
-                         st.tables, stream=st.stream)
+        k, v, q = self._job_values(model, ids, lens - 1, lens)
+        n = len(lens)
         ctx = np.zeros(self.max_seqs, dtype=np.int32)     # slots outside the job attend to nothing
         ctx[slots] = lens
-        st.ctx.copy_(self._dev(ctx, torch.int32))
-        st.q_all.index_copy_(0, slots_dev, torch.cat(qs))
+        packed = self._dev(np.concatenate([slots, lens - 1, ctx]), torch.int32)   # one copy for the job's integer arrays
+        slots32, pos = packed[:n], packed[n:2 * n]
+        slots_dev = slots32.long()
+        mx.mux_kv_append(self.pool, k, v, slots32, pos, st.tables, stream=st.stream)
+        st.ctx.copy_(packed[2 * n:])
+        st.q_all.index_copy_(0, slots_dev, q)
         mx.mux_decode_attn(self.pool, st.out_all, st.q_all, st.tables, st.ctx, int(lens.max()), self.scale, st.workspace,
                            stream=st.stream)
         st.tokens += len(lens)
