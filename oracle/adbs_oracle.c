@@ -429,3 +429,44 @@ int adbs_oracle_counts(const adbs_oracle *s, int32_t model, int64_t *counts)
     counts[4] = s->quota_moved;
     return ADBS_OK;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Throughput estimator (Section 3.3, Eq. 3; Appendix A.2): a stable batch of   */
+/* b^m requests of LLM m takes the prefill latencies of ALL colocated LLMs (they */
+/* run one after another) plus m's decoding latency times its average           */
+/* generation length (decoding phases overlap); the estimate is the batch over   */
+/* that time, capped by the offered rate W_b.  An LLM with an empty batch runs   */
+/* no prefill.  Returns -1 for arguments outside the formula's domain.           */
+/* ------------------------------------------------------------------------- */
+double adbs_oracle_tpt(int32_t n_models, const double *batch, const double *t_prefill, const double *t_decode,
+                       const double *gen_len, int32_t m, double rate_cap)
+{
+    if (n_models <= 0 || !batch || !t_prefill || !t_decode || !gen_len || m < 0 || m >= n_models) return -1.0;
+    if (!(rate_cap >= 0.0)) return -1.0;
+    double denom = 0.0;
+    for (int32_t i = 0; i < n_models; ++i) {
+        if (!(batch[i] >= 0.0) || !(t_prefill[i] >= 0.0) || !(t_decode[i] >= 0.0) || !(gen_len[i] >= 0.0)) return -1.0;
+        if (batch[i] > 0.0) denom += t_prefill[i];
+    }
+    denom += t_decode[m] * gen_len[m];
+    if (denom <= 0.0) return batch[m] > 0.0 ? rate_cap : 0.0;
+    double tpt = batch[m] / denom;
+    return tpt < rate_cap ? tpt : rate_cap;
+}
+
+/* "Binary search to find the batch size that can satisfy the traffic": by definition the      */
+/* smallest batch size whose estimate reaches the rate.  Latencies are the caller's fitted     */
+/* lines t_p(b) = p0 + p1 b, t_d(b) = d0 + d1 b.  Written as the plain scan over b = 1, 2, ... */
+/* Returns 0 if no b <= max_batch does, -1 for bad arguments.                                   */
+int64_t adbs_oracle_batch_size(double rate, int64_t max_batch, double p0, double p1, double d0, double d1,
+                               double gen_len, double other_prefill)
+{
+    if (!(rate >= 0.0) || max_batch < 1 || !(p0 >= 0.0) || !(p1 >= 0.0) || !(d0 >= 0.0) || !(d1 >= 0.0) ||
+        !(gen_len >= 0.0) || !(other_prefill >= 0.0))
+        return -1;
+    for (int64_t b = 1; b <= max_batch; ++b) {
+        double t = other_prefill + (p0 + p1 * (double)b) + (d0 + d1 * (double)b) * gen_len;
+        if (t <= 0.0 || (double)b / t >= rate) return b;
+    }
+    return 0;
+}

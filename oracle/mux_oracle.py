@@ -85,6 +85,10 @@ def lib():
         L.adbs_oracle_table.argtypes = [vp, i32]
         L.adbs_oracle_table.restype = C.POINTER(i32)
         L.adbs_oracle_counts.argtypes = [vp, i32, vp]
+        L.adbs_oracle_tpt.argtypes = [i32, vp, vp, vp, vp, i32, f64]
+        L.adbs_oracle_tpt.restype = f64
+        L.adbs_oracle_batch_size.argtypes = [f64, i64] + [f64] * 6
+        L.adbs_oracle_batch_size.restype = i64
         _lib = L
     return _lib
 
@@ -333,3 +337,13 @@ class OracleScheduler:
         c = np.zeros(5, np.int64)
         lib().adbs_oracle_counts(self._h, model, _ptr(c))
         return tuple(int(x) for x in c)
+
+
+def estimate_tpt(batch, t_prefill, t_decode, gen_len, m: int, rate_cap: float) -> float:
+    """Eq. 3 (oracle); -1 for arguments outside its domain."""
+    arrs = [np.ascontiguousarray(a, dtype=np.float64) for a in (batch, t_prefill, t_decode, gen_len)]
+    return lib().adbs_oracle_tpt(arrs[0].size, *[_ptr(a) for a in arrs], m, rate_cap)
+
+
+def find_batch_size(rate, max_batch, p0, p1, d0, d1, gen_len, other_prefill) -> int:
+    return lib().adbs_oracle_batch_size(rate, max_batch, p0, p1, d0, d1, gen_len, other_prefill)
