@@ -310,6 +310,30 @@ MUX_API int mux_stream_create_masked(void **out_stream, const uint32_t *cu_mask,
 MUX_API int mux_stream_destroy(void *stream);
 
 /* ---------------------------------------------------------------------------------
+ * Throughput estimator (Section 3.3, Eq. 3; Appendix A.2).  In a stable serving state the
+ * prefill phases of the colocated LLMs run one after another and the decoding phases
+ * overlap, so a batch of b^m requests of LLM m takes the sum of all LLMs' prefill
+ * latencies plus its own decoding latency times its average generation length:
+ *     tpt(m) = min( b^m / ( sum_i t_p^i + t_d^m * l_o^m ), W_b ).
+ * mux_estimate_tpt: HOST arrays of n_models doubles: batch sizes b^i, prefill latency of
+ *   each LLM's batch t_p^i (seconds), decoding latency per step t_d^i (seconds), average
+ *   generation lengths l_o^i; m = the LLM asked about; rate_cap = W_b, the request rate the
+ *   workload offers (requests/s).  LLMs with batch 0 contribute no prefill.  Returns
+ *   requests/s, or NaN for bad arguments (null, negative or NaN entries, m out of range).
+ * mux_find_batch_size: the paper finds, by binary search, the batch size that satisfies the
+ *   traffic.  With profiled latencies fitted as t_p(b) = p0 + p1 b and t_d(b) = d0 + d1 b
+ *   (seconds), generation length gen_len and the other LLMs' prefill time other_prefill,
+ *   b / (other_prefill + t_p(b) + t_d(b) gen_len) (evaluated in fp64, in this order) never
+ *   decreases with b; returns the
+ *   smallest b in [1, max_batch] whose value reaches `rate`, 0 if even max_batch does not,
+ *   MUX_ERR_INVALID for negative or NaN arguments or max_batch < 1.
+ * ------------------------------------------------------------------------------- */
+MUX_API double mux_estimate_tpt(int32_t n_models, const double *batch, const double *t_prefill, const double *t_decode,
+                                const double *gen_len, int32_t m, double rate_cap);
+MUX_API int64_t mux_find_batch_size(double rate, int64_t max_batch, double p0, double p1, double d0, double d1,
+                                    double gen_len, double other_prefill);
+
+/* ---------------------------------------------------------------------------------
  * Ceiling probes for reports (not part of the attention path): what the GPU at hand
  * sustains for a plain streaming read and for back-to-back matrix instructions.  Both only
  * enqueue on `stream`; the caller times them.

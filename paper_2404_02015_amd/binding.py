@@ -28,6 +28,7 @@ EXPORTS = [
     "mux_pool_init_quotas", "mux_pool_adapt_quotas", "mux_sched_create", "mux_sched_destroy", "mux_sched_submit",
     "mux_sched_step", "mux_sched_job", "mux_sched_job_seqs", "mux_sched_table", "mux_sched_counts",
     "mux_device_cu_count", "mux_stream_create_masked", "mux_stream_destroy", "mux_probe_stream_read", "mux_probe_mfma",
+    "mux_estimate_tpt", "mux_find_batch_size",
 ]
 
 MUX_JOB_PREFILL, MUX_JOB_DECODE, MUX_JOB_PREEMPT = 1, 2, 3
@@ -68,6 +69,10 @@ def load() -> C.CDLL:
     L.mux_pool_peak_used.argtypes = [vp, i32, C.POINTER(i64)]
     L.mux_pool_init_quotas.argtypes = [vp, i32, vp]
     L.mux_pool_adapt_quotas.argtypes = [vp, i32, C.c_double, C.c_double, C.c_double, C.POINTER(i64)]
+    L.mux_estimate_tpt.argtypes = [i32, vp, vp, vp, vp, i32, C.c_double]
+    L.mux_estimate_tpt.restype = C.c_double
+    L.mux_find_batch_size.argtypes = [C.c_double, i64] + [C.c_double] * 6
+    L.mux_find_batch_size.restype = i64
     L.mux_probe_stream_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
     L.mux_probe_mfma.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
     L.mux_device_cu_count.argtypes = [C.POINTER(i32)]
@@ -407,3 +412,16 @@ def mux_probe_mfma(sink: torch.Tensor, workgroups: int, iters: int, stream=None)
     flops = C.c_double()
     _check(load().mux_probe_mfma(_dev(sink), workgroups, iters, C.byref(flops), _stream(stream)), "mux_probe_mfma")
     return flops.value
+
+
+def mux_estimate_tpt(batch, t_prefill, t_decode, gen_len, m: int, rate_cap: float) -> float:
+    arrs = [np.ascontiguousarray(a, dtype=np.float64) for a in (batch, t_prefill, t_decode, gen_len)]
+    n = arrs[0].size
+    if any(a.size != n for a in arrs):
+        raise MuxError(MUX_ERR_INVALID, "mux_estimate_tpt")
+    return load().mux_estimate_tpt(n, *[a.ctypes.data for a in arrs], m, rate_cap)
+
+
+def mux_find_batch_size(rate: float, max_batch: int, p0: float, p1: float, d0: float, d1: float, gen_len: float,
+                        other_prefill: float) -> int:
+    return load().mux_find_batch_size(rate, max_batch, p0, p1, d0, d1, gen_len, other_prefill)

@@ -17,7 +17,7 @@ CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libmux.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
 
-SOURCES = ["mux_api.cpp", "mux_sched.cpp", "mux_stream.cpp", "mux_probes.hip", "mux_kv_append.hip", "mux_decode_attn.hip", "mux_prefill_attn.hip"]
+SOURCES = ["mux_api.cpp", "mux_sched.cpp", "mux_stream.cpp", "mux_estimator.cpp", "mux_probes.hip", "mux_kv_append.hip", "mux_decode_attn.hip", "mux_prefill_attn.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -43,7 +43,7 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = OUT + ".tmp.%d" % os.getpid()
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
