@@ -28,7 +28,10 @@
  *    next.  If the step's blocks do not fit the quota or the pool, the model's most recently
  *    admitted request is preempted (blocks freed, back to the FRONT of the waiting queue, to be
  *    recomputed: its next prefill covers prompt + outputs so far minus the last) until the step
- *    fits.  Every model with running requests gets one decoding step per iteration; the model
+ *    fits.  A request preempted in the very iteration that admitted it is struck from that
+ *    iteration's prefill job instead of being listed as preempted: whoever launches the jobs
+ *    must not write its K/V, because the blocks it gave back may already belong to another
+ *    model's decoding job of the same iteration (it still counts as a preemption).  Every model with running requests gets one decoding step per iteration; the model
  *    served first rotates by one per iteration.
  *  - A request ends when it has produced output_len tokens.  Its blocks and its slot go back at
  *    the START of the next iteration (one call per request, ids in table order, head-major,
@@ -100,6 +103,7 @@ typedef struct adbs_oracle {
     model_t *m;
     int32_t prefill_ptr, decode_ptr;
     int64_t iteration, stamp, quota_moved;
+    int64_t first_stamp; /* admission stamp at the start of the current iteration */
     job_t *jobs;
     int32_t n_jobs, cap_jobs;
 } adbs_oracle;
@@ -319,6 +323,42 @@ static void prefill_phase(adbs_oracle *s)
     }
 }
 
+/* the request was admitted in this iteration: take it out of the iteration's prefill job */
+static void strike_from_prefill(adbs_oracle *s, int32_t model, const req_t *r)
+{
+    for (int32_t j = 0; j < s->n_jobs; ++j) {
+        job_t *jb = &s->jobs[j];
+        if (jb->kind != ADBS_PREFILL || jb->model != model) continue;
+        for (int32_t i = 0; i < jb->n; ++i)
+            if (jb->ids[i] == r->id && jb->slots[i] == r->slot) {
+                for (int32_t k = i + 1; k < jb->n; ++k) {
+                    jb->ids[k - 1] = jb->ids[k];
+                    jb->slots[k - 1] = jb->slots[k];
+                    jb->lens[k - 1] = jb->lens[k];
+                    jb->flags[k - 1] = jb->flags[k];
+                }
+                jb->n--;
+                return;
+            }
+    }
+}
+
+/* a job that lost all its requests is no job: close the gaps, keeping the order */
+static void drop_empty_jobs(adbs_oracle *s)
+{
+    int32_t kept = 0;
+    for (int32_t j = 0; j < s->n_jobs; ++j) {
+        if (s->jobs[j].n == 0) continue;
+        if (kept != j) {
+            job_t t = s->jobs[kept];
+            s->jobs[kept] = s->jobs[j];
+            s->jobs[j] = t; /* the arrays of the empty one stay owned by the list */
+        }
+        kept++;
+    }
+    s->n_jobs = kept;
+}
+
 static void decode_phase(adbs_oracle *s)
 {
     for (int32_t k = 0; k < s->n_models; ++k) {
@@ -336,8 +376,12 @@ static void decode_phase(adbs_oracle *s)
             for (int32_t i = 1; i < md->n_run; ++i)
                 if (md->run[i].order > md->run[y].order) y = i;
             req_t r = md->run[y];
-            if (!pre) pre = new_job(s, ADBS_PREEMPT, model);
-            job_add(pre, r.id, r.slot, r.ctx, 0);
+            if (r.order >= s->first_stamp) {
+                strike_from_prefill(s, model, &r);
+            } else {
+                if (!pre) pre = new_job(s, ADBS_PREEMPT, model);
+                job_add(pre, r.id, r.slot, r.ctx, 0);
+            }
             release(s, model, &r);
             memmove(md->run + y, md->run + y + 1, sizeof(req_t) * (size_t)(md->n_run - y - 1));
             md->n_run--;
@@ -379,8 +423,10 @@ int adbs_oracle_step(adbs_oracle *s, int32_t *n_jobs)
     s->n_jobs = 0;
     for (int32_t i = 0; i < s->n_ended; ++i) release_slot(s, s->ended[i].model, s->ended[i].slot, s->ended[i].ctx);
     s->n_ended = 0;
+    s->first_stamp = s->stamp;
     prefill_phase(s);
     decode_phase(s);
+    drop_empty_jobs(s);
     s->iteration++;
     if (s->adapt_period > 0 && s->iteration % s->adapt_period == 0) {
         int64_t moved = 0;

@@ -138,6 +138,36 @@ def test_preemption_of_the_youngest_and_recompute_length():
     assert p.num_free() == 6 and s.counts(0)[2:4] == (2, len(pre))
 
 
+def test_request_preempted_in_the_iteration_that_admitted_it_never_launches():
+    # 3 blocks of 4 tokens, 1 head.  Request 0 (prompt 4) holds 2 blocks after its first iteration.
+    # Request 1 (prompt 4) is admitted into the last free block, and in the same iteration its
+    # decoding step needs a block that is not there: it is the youngest, goes back to the queue,
+    # and - its block being free again for anybody - must not appear in any job of that iteration.
+    p = orc.OraclePool(3, 4, 128)
+    s = orc.OracleScheduler(p, [1], max_seqs=2, max_blocks=8, max_prefill_tokens=64)
+    assert s.submit(0, 0, 4, 9) == 0
+    assert brief(s.step()) == [(P, 0, [0], [0], [4], [T]), (D, 0, [0], [0], [5], [T])]
+    assert s.submit(0, 1, 4, 9) == 0
+    assert brief(s.step()) == [(D, 0, [0], [0], [6], [0])]
+    assert s.counts(0)[:4] == (1, 1, 0, 1) and p.num_used(0) == 2 and p.num_free() == 1
+    assert brief(s.step()) == [(D, 0, [0], [0], [7], [0])]
+    assert s.counts(0)[:4] == (1, 1, 0, 2)
+    assert brief(s.step()) == [(D, 0, [0], [0], [8], [0])]
+    # context 8 opens a block for request 0: request 1 is admitted first, struck again, and the block goes to request 0
+    assert brief(s.step()) == [(D, 0, [0], [0], [9], [T])]
+    assert p.num_free() == 0 and s.counts(0)[:4] == (1, 1, 0, 4)
+    events = []
+    for _ in range(40):
+        events += brief(s.step())
+        if s.counts(0)[2] == 2:
+            break
+    assert s.step() == [] and p.num_free() == 3
+    # request 1 was prefilled exactly once (after request 0 ended) and no preempt job was ever listed
+    assert [e for e in events if e[0] == P] == [(P, 0, [1], [0], [4], [T])]
+    assert not [e for e in events if e[0] == X]
+    assert sum(e[2].count(1) for e in events if e[0] == D) == 8
+
+
 def _check_state(p, s, n_models, heads, B, live, ended):
     """Block conservation and table sanity: what the pool says a model holds is what its running
     requests (and those that ended in this iteration) need; all ids in use are distinct."""
