@@ -243,7 +243,10 @@ MUX_API size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seq
  *     admission order) and produces the next.  If the step's new blocks do not fit quota or
  *     pool, the model's most recently admitted request is preempted - blocks freed, back to
  *     the FRONT of the waiting queue, to be recomputed (its next prefill covers prompt +
- *     outputs so far - 1 tokens) - until the step fits.
+ *     outputs so far - 1 tokens) - until the step fits.  A request preempted in the iteration
+ *     that admitted it is taken out of that iteration's prefill job instead of being listed in
+ *     a preempt job (its blocks may already belong to another model's decoding job of the same
+ *     iteration, so its K/V must not be written); it counts as a preemption.
  *  3. A request ends when it has produced output_len tokens.  Its blocks and slot are
  *     released at the START of the next mux_sched_step (one mux_free_blocks call per
  *     request, ids in table order, requests in the order they ended): the caller launches
@@ -291,6 +294,49 @@ MUX_API int mux_sched_job_seqs(const mux_sched_t *sched, int32_t job, int64_t *r
                                int32_t *lens, int32_t *flags);
 MUX_API const int32_t *mux_sched_table(const mux_sched_t *sched, int32_t model);
 MUX_API int mux_sched_counts(const mux_sched_t *sched, int32_t model, int64_t *counts);
+
+/* ---------------------------------------------------------------------------------
+ * Job runner (Section 3.3, Algorithm 3 `execute`; Section 3.4: the engines fill K/V into the
+ * blocks the manager assigned and run attention over them).  It launches the jobs of a
+ * scheduler on the GPU: per job ONE host-to-device copy of the job's integer arrays (staged
+ * in pinned memory the runner owns), a small kernel that installs the block ids the scheduler
+ * just handed out into the runner's device copy of the model's table, then the append and the
+ * attention on the model's stream.  Unlike the calls above the runner OWNS device memory
+ * (table copies, staging areas, kernel workspaces: allocated in mux_runner_create on the
+ * current device, freed in mux_runner_destroy); launches allocate nothing.
+ *
+ * mux_runner_create: `sched` must have been created over `pool`; every model is one layer,
+ *   its KV heads = the scheduler's `heads`.  n_q_heads: HOST array per model, a multiple of
+ *   the model's KV heads.  streams: HOST array of hipStream_t per model (NULL = all on the
+ *   default stream); models may share a stream.
+ * mux_runner_step: mux_sched_step, plus the ordering the scheduler asks for: if the iteration
+ *   gave blocks back to the pool, everything launched so far on any model's stream is
+ *   ordered (events, no host wait) before what is launched next on every stream.
+ * mux_runner_launch: enqueues job `job` of the last step; returns without waiting.
+ *   Prefill job of n requests with T tokens in total: k_new, v_new DEVICE [T][kv heads][d],
+ *   q, out DEVICE [T][q heads][d], rows packed request by request in the job's order
+ *   (positions 0 .. len-1 of each).  Decode job: k_new, v_new DEVICE [max_seqs][kv heads][d],
+ *   q, out DEVICE [max_seqs][q heads][d], row = the sequence's SLOT (the row of the
+ *   scheduler's table; rows of slots outside the job are neither read nor appended, their
+ *   out rows up to the job's highest slot are zeroed).  Preempt jobs launch nothing.  The
+ *   buffers must stay untouched until the work has finished on the model's stream.
+ *   Jobs of one step are launched in job order, each at most once.
+ * mux_runner_synchronize: waits for every model's stream.
+ * mux_runner_read_table: waits for the model's stream and copies the runner's device copy of
+ *   the model's table to host_out (HOST int32 [max_seqs][heads][max_blocks]; entries the
+ *   scheduler never handed out are 0).  For checks; not part of the serving loop.
+ * Errors: MUX_ERR_INVALID (arguments), MUX_ERR_HIP (runtime), MUX_ERR_NOMEM (host memory).
+ * Not thread-safe: one caller at a time, the same as the scheduler it drives.
+ * ------------------------------------------------------------------------------- */
+typedef struct mux_runner mux_runner_t;
+MUX_API int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, const int32_t *n_q_heads,
+                              void *const *streams);
+MUX_API int mux_runner_destroy(mux_runner_t *runner);
+MUX_API int mux_runner_step(mux_runner_t *runner, int32_t *n_jobs);
+MUX_API int mux_runner_launch(mux_runner_t *runner, int32_t job, void *out, const void *q, const void *k_new,
+                              const void *v_new, float scale);
+MUX_API int mux_runner_synchronize(mux_runner_t *runner);
+MUX_API int mux_runner_read_table(mux_runner_t *runner, int32_t model, int32_t *host_out);
 
 /* ---------------------------------------------------------------------------------
  * Compute partitioning (Section 3.4: the parallel runtime assigns compute to prefill and

@@ -1,11 +1,15 @@
-"""Driver that runs the jobs of the batch scheduler (MuxServe, Section 3.3, Algorithm 3) on the
-GPU: it mirrors the scheduler's block tables to the device and launches mux_kv_append,
-mux_prefill_attn and mux_decode_attn for every job, one HIP stream per model.  The K/V rows and
-queries come from a caller-given source (a real engine would compute them with its QKV
-projections); everything that decides or computes is in the library.
+"""Drivers that run the jobs of the batch scheduler (MuxServe, Section 3.3, Algorithm 3) on the
+GPU, one HIP stream per model.  The K/V rows and queries come from a caller-given source (a real
+engine would compute them with its QKV projections); everything that decides or computes is in
+the library.
 
-Used by the tests (with a seeded CPU source mirrored into the oracle) and by bench.py (with a
-device random source).
+Engine       mirrors the scheduler's block tables to the device itself and calls mux_kv_append,
+             mux_prefill_attn and mux_decode_attn for every job (a handful of small copies and
+             launches per job from Python).
+NativeEngine hands every job to the library's runner (mux_runner_launch): one staged copy, the
+             table update and the kernels are issued from C++.
+
+Used by the tests (with a seeded CPU source mirrored into the oracle) and by bench.py.
 """
 from __future__ import annotations
 
@@ -42,6 +46,20 @@ class DeviceRandomSource:
         n = int(np.sum(np.asarray(pos1) - np.asarray(pos0)))
         s = self.shapes[model]
         return self._draw(n, s.n_kv_heads), self._draw(n, s.n_kv_heads), self._draw(n, s.n_q_heads)
+
+
+def _job_values(values, model, ids, pos0, pos1):
+    """K/V rows and queries of positions pos0[i] .. pos1[i]-1 of every request of a job,
+    concatenated in request order."""
+    if hasattr(values, "job_values"):
+        return values.job_values(model, ids, pos0, pos1)
+    ks, vs, qs = [], [], []
+    for rid, p0, p1 in zip(ids.tolist(), pos0.tolist(), pos1.tolist()):
+        k, v = values.kv(model, rid, p0, p1)
+        ks.append(k)
+        vs.append(v)
+        qs.append(values.q(model, rid, p0, p1))
+    return torch.cat(ks), torch.cat(vs), torch.cat(qs)
 
 
 class _ModelState:
@@ -82,19 +100,6 @@ class Engine:
     def _dev(self, a, dtype):
         return torch.from_numpy(np.ascontiguousarray(a)).to(self.device, dtype=dtype, non_blocking=False)
 
-    def _job_values(self, model, ids, pos0, pos1):
-        """K/V rows and queries of positions pos0[i] .. pos1[i]-1 of every request of a job,
-        concatenated in request order."""
-        if hasattr(self.values, "job_values"):
-            return self.values.job_values(model, ids, pos0, pos1)
-        ks, vs, qs = [], [], []
-        for rid, p0, p1 in zip(ids.tolist(), pos0.tolist(), pos1.tolist()):
-            k, v = self.values.kv(model, rid, p0, p1)
-            ks.append(k)
-            vs.append(v)
-            qs.append(self.values.q(model, rid, p0, p1))
-        return torch.cat(ks), torch.cat(vs), torch.cat(qs)
-
     def _mirror_rows(self, st: _ModelState, model: int, slots: np.ndarray) -> None:
         if slots.size == 0:
             return
@@ -106,7 +111,7 @@ class Engine:
         st = self.models[model]
         slots, lens, ids = job["slots"], job["lens"], job["ids"]
         self._mirror_rows(st, model, slots)
-        k, v, q = self._job_values(model, ids, np.zeros_like(lens), lens)
+        k, v, q = _job_values(self.values, model, ids, np.zeros_like(lens), lens)
         n, total = len(lens), int(lens.sum())
         # one host-to-device copy for all the small integer arrays of the job
         packed = self._dev(np.concatenate([np.repeat(slots, lens), np.concatenate([np.arange(x) for x in lens]),
@@ -125,7 +130,7 @@ class Engine:
         st = self.models[model]
         slots, lens, ids, flags = job["slots"], job["lens"], job["ids"], job["flags"]
         self._mirror_rows(st, model, slots[(flags & mx.MUX_JOB_FLAG_TABLE) != 0])
-        k, v, q = self._job_values(model, ids, lens - 1, lens)
+        k, v, q = _job_values(self.values, model, ids, lens - 1, lens)
         n = len(lens)
         ctx = np.zeros(self.max_seqs, dtype=np.int32)     # slots outside the job attend to nothing
         ctx[slots] = lens
@@ -161,6 +166,104 @@ class Engine:
                     results.append((job, None))
         for st in self.models:
             st.done.record(st.stream)
+            if self.keep_outputs:
+                st.stream.synchronize()   # the caller reads the outputs from another stream
+        self.iterations += 1
+        return results
+
+    def idle(self) -> bool:
+        return all(self.sched.counts(m)[:2] == (0, 0) for m in range(len(self.models)))
+
+
+class _NativeModel:
+    def __init__(self, pool, shape, max_seqs, max_tokens, device, stream):
+        d = pool.head_dim
+        kw = dict(dtype=torch.bfloat16, device=device)
+        self.shape, self.stream = shape, stream
+        # decode buffers: row = the sequence's slot; prefill buffers: the job's tokens, packed
+        self.k_dec, self.v_dec = (torch.randn(max_seqs, shape.n_kv_heads, d, **kw) for _ in range(2))
+        self.q_dec, self.out_dec = (torch.randn(max_seqs, shape.n_q_heads, d, **kw) for _ in range(2))
+        self.k_pre, self.v_pre = (torch.randn(max_tokens, shape.n_kv_heads, d, **kw) for _ in range(2))
+        self.q_pre, self.out_pre = (torch.randn(max_tokens, shape.n_q_heads, d, **kw) for _ in range(2))
+        self.tokens = 0
+
+
+class NativeEngine:
+    """Engine's interface on top of mux_runner_*.  values = a source as for Engine, or None: the
+    buffers keep the random values they were created with (timing runs; step() then returns the
+    number of jobs and reads nothing back)."""
+
+    def __init__(self, pool: mx.Pool, shapes: Sequence, max_seqs: int, max_blocks: int, max_prefill_tokens: int, values=None,
+                 device="cuda", keep_outputs: bool = True, shared_stream: bool = False, **sched_kw):
+        self.pool, self.shapes, self.values, self.device = pool, list(shapes), values, device
+        self.keep_outputs = keep_outputs and values is not None
+        self.sched = mx.Scheduler(pool, [s.n_kv_heads for s in shapes], max_seqs, max_blocks, max_prefill_tokens, **sched_kw)
+        one = torch.cuda.Stream(device=device) if shared_stream else None
+        streams = [one or torch.cuda.Stream(device=device) for _ in shapes]
+        self.runner = mx.Runner(self.sched, [s.n_q_heads for s in shapes], streams)
+        max_tokens = max(max_prefill_tokens, max_blocks * pool.block_size)
+        self.models = [_NativeModel(pool, s, max_seqs, max_tokens, device, st) for s, st in zip(shapes, streams)]
+        torch.cuda.synchronize()
+        self.scale = 1.0 / math.sqrt(pool.head_dim)
+        self.iterations = 0
+
+    def submit(self, model: int, request_id: int, prompt_len: int, output_len: int) -> None:
+        rc = self.sched.submit(model, request_id, prompt_len, output_len)
+        if rc != mx.MUX_OK:
+            raise mx.MuxError(rc, "mux_sched_submit")
+
+    def _fill(self, st, job):
+        """Copies the job's K/V/Q rows from the source into the buffers the runner reads."""
+        model, lens, ids = job["model"], job["lens"], job["ids"]
+        if job["kind"] == mx.MUX_JOB_PREFILL:
+            k, v, q = _job_values(self.values, model, ids, np.zeros_like(lens), lens)
+            n = int(lens.sum())
+            st.k_pre[:n], st.v_pre[:n], st.q_pre[:n] = k, v, q
+        else:
+            k, v, q = _job_values(self.values, model, ids, lens - 1, lens)
+            slots = torch.from_numpy(job["slots"].astype(np.int64)).to(self.device)
+            st.k_dec.index_copy_(0, slots, k)
+            st.v_dec.index_copy_(0, slots, v)
+            st.q_dec.index_copy_(0, slots, q)
+
+    def step(self):
+        n = self.runner.step()
+        if self.values is None:
+            for j in range(n):
+                kind, model, cnt = self.sched.job(j)
+                st = self.models[model]
+                if kind == mx.MUX_JOB_PREFILL:
+                    self.runner.launch(j, st.out_pre, st.q_pre, st.k_pre, st.v_pre, self.scale)
+                elif kind == mx.MUX_JOB_DECODE:
+                    self.runner.launch(j, st.out_dec, st.q_dec, st.k_dec, st.v_dec, self.scale)
+                else:
+                    continue
+                st.tokens += cnt
+            self.iterations += 1
+            return n
+        results = []
+        for j, job in enumerate(self.sched.jobs(n)):
+            st = self.models[job["model"]]
+            if job["kind"] == mx.MUX_JOB_PREEMPT:
+                results.append((job, None))
+                continue
+            prefill = job["kind"] == mx.MUX_JOB_PREFILL
+            with torch.cuda.stream(st.stream):
+                self._fill(st, job)
+                if prefill:
+                    self.runner.launch(j, st.out_pre, st.q_pre, st.k_pre, st.v_pre, self.scale)
+                else:
+                    self.runner.launch(j, st.out_dec, st.q_dec, st.k_dec, st.v_dec, self.scale)
+                out = None
+                if self.keep_outputs:
+                    if prefill:
+                        out = st.out_pre[:int(job["lens"].sum())].clone()
+                    else:
+                        out = st.out_dec.index_select(0, torch.from_numpy(job["slots"].astype(np.int64)).to(self.device))
+            st.tokens += len(job["lens"])
+            results.append((job, out))
+        if self.keep_outputs:
+            self.runner.synchronize()
         self.iterations += 1
         return results
 

@@ -28,7 +28,8 @@ EXPORTS = [
     "mux_pool_init_quotas", "mux_pool_adapt_quotas", "mux_sched_create", "mux_sched_destroy", "mux_sched_submit",
     "mux_sched_step", "mux_sched_job", "mux_sched_job_seqs", "mux_sched_table", "mux_sched_counts",
     "mux_device_cu_count", "mux_stream_create_masked", "mux_stream_destroy", "mux_probe_stream_read", "mux_probe_mfma",
-    "mux_estimate_tpt", "mux_find_batch_size",
+    "mux_estimate_tpt", "mux_find_batch_size", "mux_runner_create", "mux_runner_destroy", "mux_runner_step",
+    "mux_runner_launch", "mux_runner_synchronize", "mux_runner_read_table",
 ]
 
 MUX_JOB_PREFILL, MUX_JOB_DECODE, MUX_JOB_PREEMPT = 1, 2, 3
@@ -87,6 +88,12 @@ def load() -> C.CDLL:
     L.mux_sched_table.argtypes = [vp, i32]
     L.mux_sched_table.restype = C.POINTER(i32)
     L.mux_sched_counts.argtypes = [vp, i32, vp]
+    L.mux_runner_create.argtypes = [C.POINTER(vp), vp, vp, vp, vp]
+    L.mux_runner_destroy.argtypes = [vp]
+    L.mux_runner_step.argtypes = [vp, C.POINTER(i32)]
+    L.mux_runner_launch.argtypes = [vp, i32, vp, vp, vp, vp, f32]
+    L.mux_runner_synchronize.argtypes = [vp]
+    L.mux_runner_read_table.argtypes = [vp, i32, vp]
     L.mux_pool_num_used.argtypes = [vp, i32]
     L.mux_pool_num_used.restype = i64
     L.mux_pool_block_bytes.argtypes = [vp]
@@ -350,12 +357,20 @@ class Scheduler:
         return load().mux_sched_submit(self.handle, model, request_id, prompt_len, output_len)
 
     def step(self):
-        lib, n = load(), C.c_int32()
-        rc = lib.mux_sched_step(self.handle, C.byref(n))
-        if rc != MUX_OK:
-            raise MuxError(rc, "mux_sched_step")
-        jobs = []
-        for j in range(n.value):
+        n = C.c_int32()
+        _check(load().mux_sched_step(self.handle, C.byref(n)), "mux_sched_step")
+        return self.jobs(n.value)
+
+    def job(self, j: int):
+        """(kind, model, number of sequences) of job j of the last step."""
+        kind, model, cnt = C.c_int32(), C.c_int32(), C.c_int32()
+        _check(load().mux_sched_job(self.handle, j, C.byref(kind), C.byref(model), C.byref(cnt)), "mux_sched_job")
+        return kind.value, model.value, cnt.value
+
+    def jobs(self, n: int):
+        """The first n jobs of the last step as dicts."""
+        lib, jobs = load(), []
+        for j in range(n):
             kind, model, cnt = C.c_int32(), C.c_int32(), C.c_int32()
             lib.mux_sched_job(self.handle, j, C.byref(kind), C.byref(model), C.byref(cnt))
             ids = np.zeros(cnt.value, np.int64)
@@ -374,6 +389,51 @@ class Scheduler:
         c = np.zeros(5, np.int64)
         load().mux_sched_counts(self.handle, model, c.ctypes.data)
         return tuple(int(x) for x in c)
+
+
+class Runner:
+    """mux_runner_*: launches the scheduler's jobs on the GPU (one stream per model, or None for
+    the current stream for all).  The tensors passed to launch() must stay alive and untouched
+    until the work has finished on the model's stream."""
+
+    def __init__(self, sched: Scheduler, n_q_heads, streams=None):
+        self.sched = sched
+        self.n_q_heads = np.ascontiguousarray(n_q_heads, dtype=np.int32)
+        if self.n_q_heads.size != sched.heads.size:
+            raise ValueError("one query-head count per model")
+        self.streams = list(streams) if streams is not None else [torch.cuda.current_stream()] * sched.heads.size
+        handles = (C.c_void_p * len(self.streams))(*[s.cuda_stream or None for s in self.streams])
+        h = C.c_void_p()
+        _check(load().mux_runner_create(C.byref(h), sched.pool.handle, sched.handle, self.n_q_heads.ctypes.data, handles),
+               "mux_runner_create")
+        self.handle = h.value
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load().mux_runner_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.close()
+
+    def step(self) -> int:
+        """One scheduler iteration (plus stream ordering when blocks changed hands); number of jobs."""
+        n = C.c_int32()
+        _check(load().mux_runner_step(self.handle, C.byref(n)), "mux_runner_step")
+        return n.value
+
+    def launch(self, job: int, out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, scale: float) -> None:
+        _check(load().mux_runner_launch(self.handle, job, _dev(out), _dev(q), _dev(k_new), _dev(v_new), scale), "mux_runner_launch")
+
+    def synchronize(self) -> None:
+        _check(load().mux_runner_synchronize(self.handle), "mux_runner_synchronize")
+
+    def read_table(self, model: int) -> np.ndarray:
+        """Host copy of the runner's device table of a model, [max_seqs][heads][max_blocks]."""
+        heads = int(self.sched.heads[model])
+        host = np.empty((self.sched.max_seqs, heads, self.sched.max_blocks), np.int32)
+        _check(load().mux_runner_read_table(self.handle, model, host.ctypes.data), "mux_runner_read_table")
+        return host
 
 
 def mux_device_cu_count() -> int:

@@ -61,3 +61,11 @@ int mux_launch_prefill_attn(const mux_pool *pool, void *out, const void *q, cons
                             int32_t max_q_len, int32_t max_ctx_len, int32_t n_q_heads, int32_t n_kv_heads,
                             int32_t max_blocks, float scale, void *workspace, void *stream);
 bool mux_prefill_uses_mfma(const mux_pool *pool);
+
+// Scheduler internals the job runner needs (defined in mux_sched.cpp).
+struct mux_sched;
+struct mux_runner;
+mux_pool *mux_sched_pool(const mux_sched *s);
+void mux_sched_geometry(const mux_sched *s, int32_t *n_models, int32_t *max_seqs, int32_t *max_blocks, int32_t *max_prefill_tokens);
+int32_t mux_sched_heads(const mux_sched *s, int32_t model);
+bool mux_sched_released_blocks(const mux_sched *s);   // the last mux_sched_step gave blocks back to the pool

@@ -1,0 +1,346 @@
+// Job runner: launches the jobs of the batch scheduler (MuxServe, Section 3.3, Algorithm 3) on
+// the GPU - the part of the paper's serving loop between "the scheduler picked a job" and "the
+// attention of that job ran over the unified KV cache" (Section 3.4).  For every job it stages
+// the job's small integer arrays in pinned memory, sends them with ONE host-to-device copy,
+// installs the block ids the scheduler just handed out into the device copy of the model's
+// table, and enqueues append + attention on the model's stream.  Nothing here computes
+// attention: the kernels are those behind mux_kv_append, mux_prefill_attn and mux_decode_step.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "mux_internal.h"
+
+namespace {
+
+constexpr int kRing = 4;          // staging areas per model: a job's area is rewritten 4 jobs later
+constexpr int kEntryInts = 5;     // slot, job row (-1: none), first column, columns, offset of the ids
+
+// One workgroup per entry: the ids of one sequence, head-major [heads][n_cols], go to columns
+// col0 .. col0+n_cols-1 of its row in the model's table and, for a prefill, of the job's table.
+__global__ void install_blocks_kernel(const int32_t *__restrict__ entries, const int32_t *__restrict__ ids,
+                                      int32_t *__restrict__ slot_tables, int32_t *__restrict__ job_tables, int heads,
+                                      int max_blocks)
+{
+    const int32_t *e = entries + static_cast<size_t>(blockIdx.x) * kEntryInts;
+    const int slot = e[0], job_row = e[1], col0 = e[2], n_cols = e[3], at = e[4];
+    for (int i = threadIdx.x; i < heads * n_cols; i += blockDim.x) {
+        const int h = i / n_cols, j = i - h * n_cols;
+        const int32_t id = ids[at + i];
+        slot_tables[(static_cast<size_t>(slot) * heads + h) * max_blocks + col0 + j] = id;
+        if (job_row >= 0) job_tables[(static_cast<size_t>(job_row) * heads + h) * max_blocks + col0 + j] = id;
+    }
+}
+
+struct ModelRun {
+    int32_t hq = 0, hkv = 0;
+    hipStream_t stream = nullptr;
+    int32_t *tables = nullptr;       // DEVICE [max_seqs][hkv][max_blocks], row = the scheduler's slot
+    int32_t *job_tables = nullptr;   // DEVICE, same shape, row = position in the current prefill job
+    void *decode_ws = nullptr, *prefill_ws = nullptr;
+    size_t decode_ws_bytes = 0, prefill_ws_bytes = 0;
+    int32_t *stage_dev = nullptr;    // DEVICE kRing areas
+    int32_t *stage_host = nullptr;   // pinned HOST kRing areas
+    hipEvent_t copied[kRing] = {};   // the area's host-to-device copy has finished
+    bool in_flight[kRing] = {};
+    int next_area = 0;
+    hipEvent_t done = nullptr;       // everything launched for this model so far
+    bool launched = false;           // since `done` was last recorded
+};
+
+}  // namespace
+
+struct mux_runner {
+    mux_pool *pool = nullptr;
+    mux_sched *sched = nullptr;
+    int32_t max_seqs = 0, max_blocks = 0, max_tokens = 0;
+    size_t area_ints = 0;
+    std::vector<ModelRun> models;
+    bool one_stream = true;
+    std::vector<int64_t> ids64;
+    std::vector<int32_t> slots, lens, flags;
+};
+
+namespace {
+
+bool ok(hipError_t e)
+{
+    if (e == hipSuccess) return true;
+    (void)hipGetLastError();
+    return false;
+}
+
+void release(mux_runner *r)
+{
+    for (ModelRun &m : r->models) {
+        (void)hipStreamSynchronize(m.stream);
+        if (m.tables) (void)hipFree(m.tables);
+        if (m.job_tables) (void)hipFree(m.job_tables);
+        if (m.decode_ws) (void)hipFree(m.decode_ws);
+        if (m.prefill_ws) (void)hipFree(m.prefill_ws);
+        if (m.stage_dev) (void)hipFree(m.stage_dev);
+        if (m.stage_host) (void)hipHostFree(m.stage_host);
+        for (hipEvent_t &e : m.copied)
+            if (e) (void)hipEventDestroy(e);
+        if (m.done) (void)hipEventDestroy(m.done);
+    }
+    delete r;
+}
+
+// Every kernel launched so far, on any model's stream, comes before whatever is launched next.
+int order_streams(mux_runner *r)
+{
+    if (r->one_stream) return MUX_OK;
+    for (ModelRun &m : r->models)
+        if (m.launched) {
+            if (!ok(hipEventRecord(m.done, m.stream))) return MUX_ERR_HIP;
+            for (ModelRun &other : r->models)
+                if (other.stream != m.stream && !ok(hipStreamWaitEvent(other.stream, m.done, 0))) return MUX_ERR_HIP;
+            m.launched = false;
+        }
+    return MUX_OK;
+}
+
+// Claims the model's next staging area; waits (rarely: kRing jobs later) for its last copy.
+int claim_area(ModelRun &m, size_t area_ints, int32_t **host, int32_t **dev, int *area)
+{
+    const int a = m.next_area;
+    m.next_area = (a + 1) % kRing;
+    if (m.in_flight[a] && !ok(hipEventSynchronize(m.copied[a]))) return MUX_ERR_HIP;
+    m.in_flight[a] = false;
+    *host = m.stage_host + static_cast<size_t>(a) * area_ints;
+    *dev = m.stage_dev + static_cast<size_t>(a) * area_ints;
+    *area = a;
+    return MUX_OK;
+}
+
+int send_area(ModelRun &m, int area, const int32_t *host, int32_t *dev, size_t n_ints)
+{
+    if (!ok(hipMemcpyAsync(dev, host, n_ints * sizeof(int32_t), hipMemcpyHostToDevice, m.stream))) return MUX_ERR_HIP;
+    if (!ok(hipEventRecord(m.copied[area], m.stream))) return MUX_ERR_HIP;
+    m.in_flight[area] = true;
+    return MUX_OK;
+}
+
+int install(ModelRun &m, const int32_t *entries_dev, const int32_t *ids_dev, int n_entries, bool prefill, int max_blocks)
+{
+    if (n_entries == 0) return MUX_OK;
+    hipLaunchKernelGGL(install_blocks_kernel, dim3(static_cast<unsigned>(n_entries)), dim3(256), 0, m.stream, entries_dev, ids_dev,
+                       m.tables, prefill ? m.job_tables : nullptr, m.hkv, max_blocks);
+    return ok(hipGetLastError()) ? MUX_OK : MUX_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, const int32_t *n_q_heads, void *const *streams)
+{
+    if (!out || !pool || !sched || !n_q_heads || mux_sched_pool(sched) != pool) return MUX_ERR_INVALID;
+    int32_t n_models = 0, max_seqs = 0, max_blocks = 0, budget = 0;
+    mux_sched_geometry(sched, &n_models, &max_seqs, &max_blocks, &budget);
+    for (int32_t i = 0; i < n_models; ++i) {
+        const int32_t hkv = mux_sched_heads(sched, i);
+        if (n_q_heads[i] <= 0 || n_q_heads[i] % hkv != 0) return MUX_ERR_INVALID;
+    }
+    const int64_t max_ctx = static_cast<int64_t>(max_blocks) * pool->block_size;
+    if (max_ctx > 0x7fffffff) return MUX_ERR_UNSUPPORTED;
+    mux_runner *r = new (std::nothrow) mux_runner();
+    if (!r) return MUX_ERR_NOMEM;
+    r->pool = pool;
+    r->sched = sched;
+    r->max_seqs = max_seqs;
+    r->max_blocks = max_blocks;
+    // a prefill job holds at most `budget` tokens, or one request of any admissible length
+    r->max_tokens = static_cast<int32_t>(std::max<int64_t>(budget, max_ctx));
+    int32_t max_heads = 0;
+    for (int32_t i = 0; i < n_models; ++i) max_heads = std::max(max_heads, mux_sched_heads(sched, i));
+    const size_t prefill_ints = 2 * static_cast<size_t>(r->max_tokens) + (2 + kEntryInts) * static_cast<size_t>(max_seqs) + 1 +
+                                (static_cast<size_t>(r->max_tokens) / pool->block_size + max_seqs) * max_heads;
+    const size_t decode_ints = static_cast<size_t>(max_seqs) * (1 + kEntryInts + max_heads);
+    r->area_ints = (std::max(prefill_ints, decode_ints) + 3) / 4 * 4;   // areas stay 16-byte aligned
+    try {
+        r->models.resize(static_cast<size_t>(n_models));
+        r->ids64.resize(static_cast<size_t>(max_seqs));
+        r->slots.resize(static_cast<size_t>(max_seqs));
+        r->lens.resize(static_cast<size_t>(max_seqs));
+        r->flags.resize(static_cast<size_t>(max_seqs));
+    } catch (const std::bad_alloc &) {
+        delete r;
+        return MUX_ERR_NOMEM;
+    }
+    for (int32_t i = 0; i < n_models; ++i) {
+        r->models[i].stream = streams ? static_cast<hipStream_t>(streams[i]) : nullptr;
+        if (r->models[i].stream != r->models[0].stream) r->one_stream = false;
+    }
+    for (int32_t i = 0; i < n_models; ++i) {
+        ModelRun &m = r->models[i];
+        m.hq = n_q_heads[i];
+        m.hkv = mux_sched_heads(sched, i);
+        const size_t table_bytes = static_cast<size_t>(max_seqs) * m.hkv * max_blocks * sizeof(int32_t);
+        // the split of long contexts depends on both the number of rows and the longest context:
+        // size the workspace for the worst launch this scheduler can produce
+        for (int32_t rows = 1; rows <= max_seqs; ++rows)
+            for (int32_t nb = 1; nb <= max_blocks; ++nb)
+                m.decode_ws_bytes = std::max(m.decode_ws_bytes,
+                                             mux_decode_step_workspace_bytes(pool, 1, rows, m.hq, m.hkv, nb * pool->block_size));
+        m.prefill_ws_bytes = mux_prefill_workspace_bytes(pool, max_seqs, r->max_tokens, static_cast<int32_t>(max_ctx), m.hq, m.hkv);
+        bool good = m.decode_ws_bytes != 0;
+        good = good && ok(hipMalloc(&m.tables, table_bytes)) && ok(hipMalloc(&m.job_tables, table_bytes));
+        good = good && ok(hipMemset(m.tables, 0, table_bytes)) && ok(hipMemset(m.job_tables, 0, table_bytes));
+        good = good && ok(hipMalloc(&m.decode_ws, m.decode_ws_bytes));
+        good = good && (m.prefill_ws_bytes == 0 || ok(hipMalloc(&m.prefill_ws, m.prefill_ws_bytes)));
+        good = good && ok(hipMalloc(&m.stage_dev, kRing * r->area_ints * sizeof(int32_t)));
+        good = good && ok(hipHostMalloc(&m.stage_host, kRing * r->area_ints * sizeof(int32_t), hipHostMallocDefault));
+        for (hipEvent_t &e : m.copied) good = good && ok(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        good = good && ok(hipEventCreateWithFlags(&m.done, hipEventDisableTiming));
+        if (!good) {
+            release(r);
+            return MUX_ERR_HIP;
+        }
+    }
+    if (!ok(hipDeviceSynchronize())) {   // the tables are cleared before any stream uses them
+        release(r);
+        return MUX_ERR_HIP;
+    }
+    *out = r;
+    return MUX_OK;
+}
+
+int mux_runner_destroy(mux_runner_t *r)
+{
+    if (!r) return MUX_ERR_INVALID;
+    release(r);
+    return MUX_OK;
+}
+
+int mux_runner_step(mux_runner_t *r, int32_t *n_jobs)
+{
+    if (!r || !n_jobs) return MUX_ERR_INVALID;
+    const int rc = mux_sched_step(r->sched, n_jobs);
+    if (rc != MUX_OK) return rc;
+    // blocks that went back to the pool in this iteration may already belong to another model:
+    // what read them (launched earlier, on that model's stream) must finish before this
+    // iteration's kernels start on any stream
+    if (mux_sched_released_blocks(r->sched)) return order_streams(r);
+    return MUX_OK;
+}
+
+int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, const void *k_new, const void *v_new, float scale)
+{
+    if (!r) return MUX_ERR_INVALID;
+    int32_t kind = 0, model = 0, n = 0;
+    int rc = mux_sched_job(r->sched, job, &kind, &model, &n);
+    if (rc != MUX_OK) return rc;
+    if (kind == MUX_JOB_PREEMPT || n == 0) return MUX_OK;
+    if (!out || !q || !k_new || !v_new) return MUX_ERR_INVALID;
+    if (n > r->max_seqs) return MUX_ERR_INVALID;
+    rc = mux_sched_job_seqs(r->sched, job, nullptr, r->slots.data(), r->lens.data(), r->flags.data());
+    if (rc != MUX_OK) return rc;
+    ModelRun &m = r->models[model];
+    const int32_t *table = mux_sched_table(r->sched, model);
+    const int32_t B = r->pool->block_size, heads = m.hkv, cols = r->max_blocks;
+    int32_t *host = nullptr, *dev = nullptr;
+    int area = 0;
+    rc = claim_area(m, r->area_ints, &host, &dev, &area);
+    if (rc != MUX_OK) return rc;
+
+    if (kind == MUX_JOB_PREFILL) {
+        int64_t total = 0, id_ints = 0;
+        int32_t longest = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            total += r->lens[i];
+            id_ints += static_cast<int64_t>((r->lens[i] + B - 1) / B) * heads;
+            longest = std::max(longest, r->lens[i]);
+        }
+        const size_t need = 2 * static_cast<size_t>(total) + 2 * static_cast<size_t>(n) + 1 + static_cast<size_t>(kEntryInts) * n +
+                            static_cast<size_t>(id_ints);
+        if (total > r->max_tokens || need > r->area_ints) return MUX_ERR_INVALID;
+        // area: token -> job row | token -> position | chunk starts (n + 1) | tokens cached before (n zeros) | entries | ids
+        int32_t *tok_seq = host, *tok_pos = host + total, *cu = host + 2 * total, *q_start = cu + n + 1;
+        int32_t *entries = q_start + n, *ids = entries + kEntryInts * n;
+        int32_t t = 0, at = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            const int32_t len = r->lens[i], nb = (len + B - 1) / B, slot = r->slots[i];
+            if (slot < 0 || slot >= r->max_seqs || nb > cols) return MUX_ERR_INVALID;
+            cu[i] = t;
+            q_start[i] = 0;
+            for (int32_t p = 0; p < len; ++p, ++t) {
+                tok_seq[t] = i;
+                tok_pos[t] = p;
+            }
+            int32_t *e = entries + kEntryInts * i;
+            e[0] = slot, e[1] = i, e[2] = 0, e[3] = nb, e[4] = at;
+            const int32_t *row = table + static_cast<size_t>(slot) * heads * cols;
+            for (int32_t h = 0; h < heads; ++h, at += nb) std::memcpy(ids + at, row + static_cast<size_t>(h) * cols, sizeof(int32_t) * nb);
+        }
+        cu[n] = t;
+        rc = send_area(m, area, host, dev, need);
+        if (rc != MUX_OK) return rc;
+        const int32_t *d_seq = dev, *d_pos = dev + total, *d_cu = dev + 2 * total, *d_start = d_cu + n + 1;
+        const int32_t *d_entries = d_start + n, *d_ids = d_entries + kEntryInts * n;
+        rc = install(m, d_entries, d_ids, n, true, cols);
+        if (rc != MUX_OK) return rc;
+        m.launched = true;
+        rc = mux_kv_append(r->pool, k_new, v_new, d_seq, d_pos, m.job_tables, static_cast<int32_t>(total), n, heads, cols, m.stream);
+        if (rc != MUX_OK) return rc;
+        return mux_prefill_attn(r->pool, out, q, d_cu, d_start, m.job_tables, n, static_cast<int32_t>(total), longest, longest, m.hq,
+                                heads, cols, scale, m.prefill_ws, m.prefill_ws_bytes, m.stream);
+    }
+
+    if (kind != MUX_JOB_DECODE) return MUX_ERR_INVALID;
+    // area: context length per slot (0 = not in this step), up to the highest slot | entries | ids
+    int32_t rows = 0, longest = 0, n_entries = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (r->slots[i] < 0 || r->slots[i] >= r->max_seqs) return MUX_ERR_INVALID;
+        rows = std::max(rows, r->slots[i] + 1);
+        longest = std::max(longest, r->lens[i]);
+        n_entries += (r->flags[i] & MUX_JOB_FLAG_TABLE) ? 1 : 0;
+    }
+    const size_t need = static_cast<size_t>(rows) + static_cast<size_t>(n_entries) * (kEntryInts + heads);
+    if (need > r->area_ints) return MUX_ERR_INVALID;
+    int32_t *ctx = host, *entries = host + rows, *ids = entries + kEntryInts * n_entries;
+    std::fill(ctx, ctx + rows, 0);
+    int32_t e_at = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t slot = r->slots[i], len = r->lens[i];
+        ctx[slot] = len;
+        if (!(r->flags[i] & MUX_JOB_FLAG_TABLE)) continue;
+        const int32_t col = (len - 1) / B;   // the block the appended token opened
+        if (len <= 0 || col >= cols) return MUX_ERR_INVALID;
+        int32_t *e = entries + kEntryInts * e_at;
+        e[0] = slot, e[1] = -1, e[2] = col, e[3] = 1, e[4] = e_at * heads;
+        const int32_t *row = table + static_cast<size_t>(slot) * heads * cols;
+        for (int32_t h = 0; h < heads; ++h) ids[e_at * heads + h] = row[static_cast<size_t>(h) * cols + col];
+        ++e_at;
+    }
+    rc = send_area(m, area, host, dev, need);
+    if (rc != MUX_OK) return rc;
+    rc = install(m, dev + rows, dev + rows + kEntryInts * n_entries, n_entries, false, cols);
+    if (rc != MUX_OK) return rc;
+    m.launched = true;
+    return mux_decode_step(r->pool, out, q, k_new, v_new, m.tables, dev, 1, rows, m.hq, heads, cols, longest, scale, m.decode_ws,
+                           m.decode_ws_bytes, m.stream);
+}
+
+int mux_runner_synchronize(mux_runner_t *r)
+{
+    if (!r) return MUX_ERR_INVALID;
+    for (ModelRun &m : r->models)
+        if (!ok(hipStreamSynchronize(m.stream))) return MUX_ERR_HIP;
+    return MUX_OK;
+}
+
+int mux_runner_read_table(mux_runner_t *r, int32_t model, int32_t *host_out)
+{
+    if (!r || model < 0 || model >= static_cast<int32_t>(r->models.size()) || !host_out) return MUX_ERR_INVALID;
+    ModelRun &m = r->models[model];
+    const size_t bytes = static_cast<size_t>(r->max_seqs) * m.hkv * r->max_blocks * sizeof(int32_t);
+    if (!ok(hipStreamSynchronize(m.stream)) || !ok(hipMemcpy(host_out, m.tables, bytes, hipMemcpyDeviceToHost))) return MUX_ERR_HIP;
+    return MUX_OK;
+}
+
+}  // extern "C"

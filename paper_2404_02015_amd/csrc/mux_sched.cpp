@@ -51,10 +51,12 @@ struct mux_sched {
     std::vector<Model> models;
     int32_t next_prefill = 0, first_decode = 0;
     int64_t iterations = 0, stamp = 0, quota_moved = 0;
+    int64_t first_stamp = 0;    // admission stamp at the start of the current iteration
     std::vector<Job> jobs;
     std::vector<int32_t> scratch_ids;
     struct Ended { int32_t model, slot, cached; };
     std::vector<Ended> ended;   // ended in the last iteration: blocks and slot held until the next one starts
+    bool released = false;      // the last iteration gave blocks back to the pool
 
     int32_t *row(Model &m, int32_t slot) { return m.table.data() + static_cast<size_t>(slot) * m.heads * cfg.max_blocks; }
     int32_t blocks_of(int32_t tokens) const { return (tokens + pool->block_size - 1) / pool->block_size; }
@@ -79,6 +81,7 @@ struct mux_sched {
             scratch_ids.insert(scratch_ids.end(), t + h * cfg.max_blocks, t + h * cfg.max_blocks + nb);
         mux_free_blocks(pool, model, static_cast<int64_t>(scratch_ids.size()), scratch_ids.data());
         m.slot_taken[slot] = 0;
+        released = true;
     }
 
     // preemption: nothing launched for this iteration reads the request's blocks, they go back now
@@ -142,6 +145,23 @@ struct mux_sched {
         if (!job.ids.empty()) jobs.push_back(std::move(job));
     }
 
+    // The blocks of a request preempted in the iteration that admitted it may be handed to another
+    // model before the iteration's jobs are launched, so its entry leaves the prefill job.
+    void cancel_prefill(int32_t model, const Request &r)
+    {
+        for (Job &job : jobs) {
+            if (job.kind != MUX_JOB_PREFILL || job.model != model) continue;
+            for (size_t i = 0; i < job.ids.size(); ++i)
+                if (job.ids[i] == r.id && job.slots[i] == r.slot) {
+                    job.ids.erase(job.ids.begin() + static_cast<std::ptrdiff_t>(i));
+                    job.slots.erase(job.slots.begin() + static_cast<std::ptrdiff_t>(i));
+                    job.lens.erase(job.lens.begin() + static_cast<std::ptrdiff_t>(i));
+                    job.flags.erase(job.flags.begin() + static_cast<std::ptrdiff_t>(i));
+                    return;
+                }
+        }
+    }
+
     void run_decode(int32_t model)
     {
         Model &m = models[model];
@@ -157,7 +177,10 @@ struct mux_sched {
                                              [](const Request &a, const Request &b) { return a.admitted < b.admitted; });
             Request r = *youngest;
             m.running.erase(youngest);
-            evicted.add(r.id, r.slot, r.cached, 0);
+            if (r.admitted >= first_stamp)
+                cancel_prefill(model, r);   // admitted in this very iteration: its prefill must not launch
+            else
+                evicted.add(r.id, r.slot, r.cached, 0);
             give_back(model, r);
             ++m.n_preempted;
             m.waiting.push_front(r);
@@ -251,12 +274,15 @@ int mux_sched_step(mux_sched_t *s, int32_t *n_jobs)
 {
     if (!s || !n_jobs) return MUX_ERR_INVALID;
     s->jobs.clear();
+    s->released = false;
     for (const mux_sched::Ended &e : s->ended) s->free_sequence(e.model, e.slot, e.cached);
     s->ended.clear();
+    s->first_stamp = s->stamp;
     s->run_prefill();
     const int32_t n = static_cast<int32_t>(s->models.size());
     for (int32_t k = 0; k < n; ++k) s->run_decode((s->first_decode + k) % n);
     s->first_decode = (s->first_decode + 1) % n;
+    s->jobs.erase(std::remove_if(s->jobs.begin(), s->jobs.end(), [](const Job &j) { return j.ids.empty(); }), s->jobs.end());
     ++s->iterations;
     if (s->cfg.adapt_period > 0 && s->iterations % s->cfg.adapt_period == 0) {
         int64_t moved = 0;
@@ -306,3 +332,15 @@ int mux_sched_counts(const mux_sched_t *s, int32_t model, int64_t *counts)
 }
 
 }  // extern "C"
+
+// Accessors for the job runner (same library, not part of the ABI).
+mux_pool *mux_sched_pool(const mux_sched *s) { return s->pool; }
+void mux_sched_geometry(const mux_sched *s, int32_t *n_models, int32_t *max_seqs, int32_t *max_blocks, int32_t *max_prefill_tokens)
+{
+    *n_models = static_cast<int32_t>(s->models.size());
+    *max_seqs = s->cfg.max_seqs;
+    *max_blocks = s->cfg.max_blocks;
+    *max_prefill_tokens = s->cfg.max_prefill_tokens;
+}
+int32_t mux_sched_heads(const mux_sched *s, int32_t model) { return s->models[model].heads; }
+bool mux_sched_released_blocks(const mux_sched *s) { return s->released; }

@@ -63,9 +63,10 @@ def oracle_job_outputs(op, os_, src, shapes, job, scale):
     return op.decode_attn(q, np.maximum(table[slots], 0), lens, hq, scale)
 
 
+@pytest.mark.parametrize("driver", ["python", "runner", "runner-one-stream"])
 @pytest.mark.parametrize("case", ["roomy", "tight-quota", "preempting"])
-def test_scheduler_drives_kernels_like_the_oracle(case):
-    print("[case] adbs %s" % case, flush=True)
+def test_scheduler_drives_kernels_like_the_oracle(case, driver):
+    print("[case] adbs %s, driver %s" % (case, driver), flush=True)
     shapes = [wl.ModelShape("a", 8, 8, 128), wl.ModelShape("b", 16, 4, 128), wl.ModelShape("c", 4, 4, 128)]
     d, B = 128, 16
     n_blocks = {"roomy": 4000, "tight-quota": 600, "preempting": 300}[case]
@@ -81,7 +82,10 @@ def test_scheduler_drives_kernels_like_the_oracle(case):
         w = np.array([1.0, 3.0, 1.0]) * np.array([s.n_kv_heads for s in shapes])
         assert mx.mux_pool_init_quotas(pool, w) == 0 == op.init_quotas(w)
     src = SeededSource(shapes, d, max_blocks * B, seed=77)
-    engine = eng.Engine(pool, shapes, max_seqs, max_blocks, budget, src, **kw)
+    if driver == "python":
+        engine = eng.Engine(pool, shapes, max_seqs, max_blocks, budget, src, **kw)
+    else:
+        engine = eng.NativeEngine(pool, shapes, max_seqs, max_blocks, budget, src, shared_stream=driver == "runner-one-stream", **kw)
     os_ = orc.OracleScheduler(op, [s.n_kv_heads for s in shapes], max_seqs, max_blocks, budget, **kw)
     scale = H.default_scale(d)
     rid, worst, kinds = 0, 0.0, set()
@@ -109,6 +113,15 @@ def test_scheduler_drives_kernels_like_the_oracle(case):
         for m in range(3):
             assert np.array_equal(engine.sched.table(m), os_.table(m))
             assert mx.mux_pool_num_used(pool, m) == op.num_used(m)
+        if driver != "python":
+            # the runner's device tables hold the blocks of every sequence that just decoded
+            for wj in want_jobs:
+                if wj["kind"] != orc.DECODE:
+                    continue
+                got_t, want_t = engine.runner.read_table(wj["model"]), os_.table(wj["model"])
+                for slot, n in zip(wj["slots"], wj["lens"]):
+                    nb = (n + B - 1) // B
+                    assert np.array_equal(got_t[slot, :, :nb], want_t[slot, :, :nb])
         if it >= 60 and engine.idle():
             break
     torch.cuda.synchronize()
