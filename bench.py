@@ -383,14 +383,18 @@ def run_adbs(args) -> int:
             weights = rates * np.array([s.n_kv_heads for s in shapes])
             assert mx.mux_pool_init_quotas(pool, weights) == 0
             kw = dict(adapt_period=16, low=0.5, high=0.9, step=0.25)
-        engine = eng.Engine(pool, shapes, max_seqs, max_blocks, 2048, eng.DeviceRandomSource(shapes, d, seed=1),
-                            keep_outputs=False, **kw)
+        if args.adbs_driver == "python":
+            engine = eng.Engine(pool, shapes, max_seqs, max_blocks, 2048, eng.DeviceRandomSource(shapes, d, seed=1),
+                                keep_outputs=False, **kw)
+        else:
+            engine = eng.NativeEngine(pool, shapes, max_seqs, max_blocks, 2048, None,
+                                      shared_stream=args.adbs_driver == "runner-one-stream", **kw)
         use = np.zeros(len(shapes))
         rid, t0, tok0 = 0, None, 0
         for it in range(warm + iters):
             if it == warm:
                 torch.cuda.synchronize()
-                t0, tok0 = time.perf_counter(), sum(m.tokens for m in engine.models)
+                t0, tok0 = time.perf_counter(), engine.tokens()
             for m in range(len(shapes)):
                 for _ in range(int(rng.poisson(per_iter[m]))):
                     engine.submit(m, rid, int(rng.integers(64, 385)) * length_scale[m], int(rng.integers(32, 129)) * length_scale[m])
@@ -402,7 +406,7 @@ def run_adbs(args) -> int:
         dt = time.perf_counter() - t0
         counts = [engine.sched.counts(m) for m in range(len(shapes))]
         out[mode] = {
-            "tokens_per_s": (sum(m.tokens for m in engine.models) - tok0) / dt,
+            "tokens_per_s": (engine.tokens() - tok0) / dt,
             "ms_per_iteration": dt / iters * 1e3,
             "block_usage_share": [round(float(x), 4) for x in use / max(use.sum(), 1)],
             "mean_blocks_in_use": float(use.sum() / iters),
@@ -417,8 +421,8 @@ def run_adbs(args) -> int:
         "n_gpus": 1, "steps": iters, "warmup": warm, "ms_per_step": a["ms_per_iteration"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16 storage, f32 arithmetic", "data": "synthetic",
         "config": {"workload": "batch scheduler (Algorithm 3) over 13B/7B/7B-shaped models, Poisson arrivals 2:8:8, request "
-                               "lengths 2:1:1, %d head-blocks, %d slots per model; every job launched on the GPU by a Python "
-                               "driver (host-bound)" % (n_blocks, max_seqs)},
+                               "lengths 2:1:1, %d head-blocks, %d slots per model; every job launched on the GPU, driver: %s"
+                               % (n_blocks, max_seqs, args.adbs_driver)},
         "rate_share": [round(float(x), 4) for x in rates / rates.sum()],
         "adbs": a, "no_quota": out["no-quota"],
     }
@@ -444,6 +448,9 @@ def main() -> int:
                     help="decode streams get the first F x (compute units), prefill streams the rest")
     ap.add_argument("--adbs", action="store_true",
                     help="second workload: the batch scheduler serving a request stream (prints its own JSON line)")
+    ap.add_argument("--adbs-driver", choices=["runner", "runner-one-stream", "python"], default="runner",
+                    help="who launches the scheduler's jobs: the library's runner (one stream per model, or one for all) "
+                         "or the Python driver")
     ap.add_argument("--no-solo", action="store_true", help="skip the per-model solo passes after the timed loop")
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 1 GiB device copies after the timed loop")
     args = ap.parse_args()

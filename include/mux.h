@@ -309,9 +309,10 @@ MUX_API int mux_sched_counts(const mux_sched_t *sched, int32_t model, int64_t *c
  *   its KV heads = the scheduler's `heads`.  n_q_heads: HOST array per model, a multiple of
  *   the model's KV heads.  streams: HOST array of hipStream_t per model (NULL = all on the
  *   default stream); models may share a stream.
- * mux_runner_step: mux_sched_step, plus the ordering the scheduler asks for: if the iteration
- *   gave blocks back to the pool, everything launched so far on any model's stream is
- *   ordered (events, no host wait) before what is launched next on every stream.
+ * mux_runner_step: mux_sched_step, plus the ordering the scheduler asks for: for every model
+ *   whose blocks went back to the pool in this iteration, what was launched so far on that
+ *   model's stream (the last readers of those blocks) is ordered, by an event and without a
+ *   host wait, before what is launched next on the other models' streams.
  * mux_runner_launch: enqueues job `job` of the last step; returns without waiting.
  *   Prefill job of n requests with T tokens in total: k_new, v_new DEVICE [T][kv heads][d],
  *   q, out DEVICE [T][q heads][d], rows packed request by request in the job's order
@@ -321,6 +322,15 @@ MUX_API int mux_sched_counts(const mux_sched_t *sched, int32_t model, int64_t *c
  *   out rows up to the job's highest slot are zeroed).  Preempt jobs launch nothing.  The
  *   buffers must stay untouched until the work has finished on the model's stream.
  *   Jobs of one step are launched in job order, each at most once.
+ * mux_runner_set_buffers / mux_runner_run_step: for engines that keep their Q/K/V/output in
+ *   fixed buffers (shapes as for mux_runner_launch: the prefill set sized for the largest
+ *   prefill job - max(max_prefill_tokens, max_blocks x block_size) tokens -, the decode set
+ *   for max_seqs rows).  mux_runner_run_step = mux_runner_step followed by mux_runner_launch
+ *   of every job with its model's registered buffers and scale: one call per iteration.
+ *   A job of a model without registered buffers -> MUX_ERR_INVALID (jobs before it were
+ *   launched).
+ * mux_runner_counts: counts[0..1] = prefill and decode jobs launched so far, and the sequences in
+ *   them (every sequence of such a job yields one output token).
  * mux_runner_synchronize: waits for every model's stream.
  * mux_runner_read_table: waits for the model's stream and copies the runner's device copy of
  *   the model's table to host_out (HOST int32 [max_seqs][heads][max_blocks]; entries the
@@ -335,6 +345,11 @@ MUX_API int mux_runner_destroy(mux_runner_t *runner);
 MUX_API int mux_runner_step(mux_runner_t *runner, int32_t *n_jobs);
 MUX_API int mux_runner_launch(mux_runner_t *runner, int32_t job, void *out, const void *q, const void *k_new,
                               const void *v_new, float scale);
+MUX_API int mux_runner_set_buffers(mux_runner_t *runner, int32_t model, void *prefill_out, const void *prefill_q,
+                                   const void *prefill_k, const void *prefill_v, void *decode_out, const void *decode_q,
+                                   const void *decode_k, const void *decode_v, float scale);
+MUX_API int mux_runner_run_step(mux_runner_t *runner, int32_t *n_jobs);
+MUX_API int mux_runner_counts(const mux_runner_t *runner, int64_t *counts);
 MUX_API int mux_runner_synchronize(mux_runner_t *runner);
 MUX_API int mux_runner_read_table(mux_runner_t *runner, int32_t model, int32_t *host_out);
 

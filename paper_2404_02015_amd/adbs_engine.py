@@ -174,6 +174,10 @@ class Engine:
     def idle(self) -> bool:
         return all(self.sched.counts(m)[:2] == (0, 0) for m in range(len(self.models)))
 
+    def tokens(self) -> int:
+        """Output tokens produced so far."""
+        return sum(st.tokens for st in self.models)
+
 
 class _NativeModel:
     def __init__(self, pool, shape, max_seqs, max_tokens, device, stream):
@@ -185,7 +189,6 @@ class _NativeModel:
         self.q_dec, self.out_dec = (torch.randn(max_seqs, shape.n_q_heads, d, **kw) for _ in range(2))
         self.k_pre, self.v_pre = (torch.randn(max_tokens, shape.n_kv_heads, d, **kw) for _ in range(2))
         self.q_pre, self.out_pre = (torch.randn(max_tokens, shape.n_q_heads, d, **kw) for _ in range(2))
-        self.tokens = 0
 
 
 class NativeEngine:
@@ -206,6 +209,14 @@ class NativeEngine:
         torch.cuda.synchronize()
         self.scale = 1.0 / math.sqrt(pool.head_dim)
         self.iterations = 0
+        if values is None:
+            for i, st in enumerate(self.models):
+                self.runner.set_buffers(i, (st.out_pre, st.q_pre, st.k_pre, st.v_pre), (st.out_dec, st.q_dec, st.k_dec, st.v_dec),
+                                        self.scale)
+
+    def tokens(self) -> int:
+        """Output tokens produced so far: every request of a prefill or decode job yields one."""
+        return self.runner.counts()[1]
 
     def submit(self, model: int, request_id: int, prompt_len: int, output_len: int) -> None:
         rc = self.sched.submit(model, request_id, prompt_len, output_len)
@@ -227,20 +238,11 @@ class NativeEngine:
             st.q_dec.index_copy_(0, slots, q)
 
     def step(self):
-        n = self.runner.step()
         if self.values is None:
-            for j in range(n):
-                kind, model, cnt = self.sched.job(j)
-                st = self.models[model]
-                if kind == mx.MUX_JOB_PREFILL:
-                    self.runner.launch(j, st.out_pre, st.q_pre, st.k_pre, st.v_pre, self.scale)
-                elif kind == mx.MUX_JOB_DECODE:
-                    self.runner.launch(j, st.out_dec, st.q_dec, st.k_dec, st.v_dec, self.scale)
-                else:
-                    continue
-                st.tokens += cnt
+            n = self.runner.run_step()
             self.iterations += 1
             return n
+        n = self.runner.step()
         results = []
         for j, job in enumerate(self.sched.jobs(n)):
             st = self.models[job["model"]]
@@ -260,7 +262,6 @@ class NativeEngine:
                         out = st.out_pre[:int(job["lens"].sum())].clone()
                     else:
                         out = st.out_dec.index_select(0, torch.from_numpy(job["slots"].astype(np.int64)).to(self.device))
-            st.tokens += len(job["lens"])
             results.append((job, out))
         if self.keep_outputs:
             self.runner.synchronize()

@@ -926,6 +926,17 @@ mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_
     } else {
         const long long items = static_cast<long long>(n_seqs) * n_kv_heads * plan.n_passes;
         long long want_splits = (2048 + items - 1) / items;
+        // Splitting adds the work-list and merge kernels to the chain (~15 us, the time ~100 MB of
+        // K/V take).  For a short launch that is more than the split can win back: without it
+        // the loss is at most the imbalance of whole rows over the resident workgroups (a GPU
+        // half full of workgroups already streams at ~90 % of its bandwidth).
+        static const bool split_short = env_int("MUX_DECODE_SPLIT_SHORT", 0) != 0;
+        const double bound_bytes = static_cast<double>(items) * ctx_blocks * pool->block_bytes;   // every row at max_ctx_len
+        const double slots = uses_group_kernel(pool, group) ? 512.0 : 1024.0;
+        const double rounds = items / slots;
+        const double imbalance = rounds >= 1.0 ? static_cast<double>((items + static_cast<long long>(slots) - 1) / static_cast<long long>(slots)) / rounds
+                                               : std::max(1.0, 0.5 / rounds);
+        if (!split_short && bound_bytes <= 768e6 && bound_bytes * (imbalance - 1.0) <= 100e6) want_splits = 1;
         if (want_splits > ctx_blocks) want_splits = ctx_blocks;
         if (want_splits < 1) want_splits = 1;
         span = (ctx_blocks + want_splits - 1) / want_splits;

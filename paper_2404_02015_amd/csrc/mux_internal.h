@@ -68,4 +68,4 @@ struct mux_runner;
 mux_pool *mux_sched_pool(const mux_sched *s);
 void mux_sched_geometry(const mux_sched *s, int32_t *n_models, int32_t *max_seqs, int32_t *max_blocks, int32_t *max_prefill_tokens);
 int32_t mux_sched_heads(const mux_sched *s, int32_t model);
-bool mux_sched_released_blocks(const mux_sched *s);   // the last mux_sched_step gave blocks back to the pool
+bool mux_sched_released_blocks(const mux_sched *s, int32_t model);   // the last mux_sched_step gave blocks of this model back to the pool

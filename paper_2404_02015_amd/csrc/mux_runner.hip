@@ -1,13 +1,15 @@
 // Job runner: launches the jobs of the batch scheduler (MuxServe, Section 3.3, Algorithm 3) on
 // the GPU - the part of the paper's serving loop between "the scheduler picked a job" and "the
 // attention of that job ran over the unified KV cache" (Section 3.4).  For every job it stages
-// the job's small integer arrays in pinned memory, sends them with ONE host-to-device copy,
-// installs the block ids the scheduler just handed out into the device copy of the model's
-// table, and enqueues append + attention on the model's stream.  Nothing here computes
+// the job's small integer arrays - as kernel arguments when they fit (the usual decode job),
+// else in pinned memory sent with ONE host-to-device copy -, installs the block ids the
+// scheduler just handed out into the device copy of the model's table, and enqueues append +
+// attention on the model's stream.  Nothing here computes
 // attention: the kernels are those behind mux_kv_append, mux_prefill_attn and mux_decode_step.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -35,11 +37,30 @@ __global__ void install_blocks_kernel(const int32_t *__restrict__ entries, const
     }
 }
 
+// The same for a decode job whose arrays are small enough to travel as kernel arguments (no
+// copy, no staging): context lengths of the job's rows, then entries, then ids.  One workgroup.
+constexpr int kInlineInts = 960;   // 3 840 bytes: with the other arguments under the 4 KiB argument limit
+struct InlineArrays {
+    int32_t v[kInlineInts];
+};
+__global__ void install_inline_kernel(InlineArrays a, int rows, int n_entries, int32_t *__restrict__ ctx_out,
+                                      int32_t *__restrict__ slot_tables, int heads, int max_blocks)
+{
+    for (int i = threadIdx.x; i < rows; i += blockDim.x) ctx_out[i] = a.v[i];
+    const int ids0 = rows + n_entries * kEntryInts;
+    for (int i = threadIdx.x; i < n_entries * heads; i += blockDim.x) {
+        const int e = i / heads, h = i - e * heads;
+        const int slot = a.v[rows + e * kEntryInts], col = a.v[rows + e * kEntryInts + 2];
+        slot_tables[(static_cast<size_t>(slot) * heads + h) * max_blocks + col] = a.v[ids0 + i];
+    }
+}
+
 struct ModelRun {
     int32_t hq = 0, hkv = 0;
     hipStream_t stream = nullptr;
     int32_t *tables = nullptr;       // DEVICE [max_seqs][hkv][max_blocks], row = the scheduler's slot
     int32_t *job_tables = nullptr;   // DEVICE, same shape, row = position in the current prefill job
+    int32_t *ctx = nullptr;          // DEVICE [max_seqs]: context lengths of the current decode job, by slot
     void *decode_ws = nullptr, *prefill_ws = nullptr;
     size_t decode_ws_bytes = 0, prefill_ws_bytes = 0;
     int32_t *stage_dev = nullptr;    // DEVICE kRing areas
@@ -48,6 +69,10 @@ struct ModelRun {
     bool in_flight[kRing] = {};
     int next_area = 0;
     hipEvent_t done = nullptr;       // everything launched for this model so far
+    // buffers registered with mux_runner_set_buffers: [0] prefill, [1] decode
+    void *reg_out[2] = {};
+    const void *reg_q[2] = {}, *reg_k[2] = {}, *reg_v[2] = {};
+    float reg_scale = 0.f;
     bool launched = false;           // since `done` was last recorded
 };
 
@@ -60,6 +85,8 @@ struct mux_runner {
     size_t area_ints = 0;
     std::vector<ModelRun> models;
     bool one_stream = true;
+    int64_t jobs_launched = 0, seqs_launched = 0;
+    bool stage_always = false;   // MUX_RUNNER_STAGE_ALWAYS=1 when the runner was created: never pass arrays as arguments
     std::vector<int64_t> ids64;
     std::vector<int32_t> slots, lens, flags;
 };
@@ -79,6 +106,7 @@ void release(mux_runner *r)
         (void)hipStreamSynchronize(m.stream);
         if (m.tables) (void)hipFree(m.tables);
         if (m.job_tables) (void)hipFree(m.job_tables);
+        if (m.ctx) (void)hipFree(m.ctx);
         if (m.decode_ws) (void)hipFree(m.decode_ws);
         if (m.prefill_ws) (void)hipFree(m.prefill_ws);
         if (m.stage_dev) (void)hipFree(m.stage_dev);
@@ -90,17 +118,16 @@ void release(mux_runner *r)
     delete r;
 }
 
-// Every kernel launched so far, on any model's stream, comes before whatever is launched next.
-int order_streams(mux_runner *r)
+// Blocks a model gave back may be handed to any other model from now on: what that model has
+// launched so far (the last readers of those blocks) comes before whatever is launched next on
+// the other models' streams.  Its own stream is ordered anyway.
+int order_after(mux_runner *r, ModelRun &m)
 {
-    if (r->one_stream) return MUX_OK;
-    for (ModelRun &m : r->models)
-        if (m.launched) {
-            if (!ok(hipEventRecord(m.done, m.stream))) return MUX_ERR_HIP;
-            for (ModelRun &other : r->models)
-                if (other.stream != m.stream && !ok(hipStreamWaitEvent(other.stream, m.done, 0))) return MUX_ERR_HIP;
-            m.launched = false;
-        }
+    if (r->one_stream || !m.launched) return MUX_OK;
+    if (!ok(hipEventRecord(m.done, m.stream))) return MUX_ERR_HIP;
+    for (ModelRun &other : r->models)
+        if (other.stream != m.stream && !ok(hipStreamWaitEvent(other.stream, m.done, 0))) return MUX_ERR_HIP;
+    m.launched = false;
     return MUX_OK;
 }
 
@@ -152,6 +179,8 @@ int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, 
     if (!r) return MUX_ERR_NOMEM;
     r->pool = pool;
     r->sched = sched;
+    const char *stage = std::getenv("MUX_RUNNER_STAGE_ALWAYS");
+    r->stage_always = stage && stage[0] == '1';
     r->max_seqs = max_seqs;
     r->max_blocks = max_blocks;
     // a prefill job holds at most `budget` tokens, or one request of any admissible length
@@ -191,6 +220,7 @@ int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, 
         bool good = m.decode_ws_bytes != 0;
         good = good && ok(hipMalloc(&m.tables, table_bytes)) && ok(hipMalloc(&m.job_tables, table_bytes));
         good = good && ok(hipMemset(m.tables, 0, table_bytes)) && ok(hipMemset(m.job_tables, 0, table_bytes));
+        good = good && ok(hipMalloc(&m.ctx, static_cast<size_t>(max_seqs) * sizeof(int32_t)));
         good = good && ok(hipMalloc(&m.decode_ws, m.decode_ws_bytes));
         good = good && (m.prefill_ws_bytes == 0 || ok(hipMalloc(&m.prefill_ws, m.prefill_ws_bytes)));
         good = good && ok(hipMalloc(&m.stage_dev, kRing * r->area_ints * sizeof(int32_t)));
@@ -222,10 +252,11 @@ int mux_runner_step(mux_runner_t *r, int32_t *n_jobs)
     if (!r || !n_jobs) return MUX_ERR_INVALID;
     const int rc = mux_sched_step(r->sched, n_jobs);
     if (rc != MUX_OK) return rc;
-    // blocks that went back to the pool in this iteration may already belong to another model:
-    // what read them (launched earlier, on that model's stream) must finish before this
-    // iteration's kernels start on any stream
-    if (mux_sched_released_blocks(r->sched)) return order_streams(r);
+    for (size_t i = 0; i < r->models.size(); ++i)
+        if (mux_sched_released_blocks(r->sched, static_cast<int32_t>(i))) {
+            const int rc2 = order_after(r, r->models[i]);
+            if (rc2 != MUX_OK) return rc2;
+        }
     return MUX_OK;
 }
 
@@ -238,17 +269,19 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
     if (kind == MUX_JOB_PREEMPT || n == 0) return MUX_OK;
     if (!out || !q || !k_new || !v_new) return MUX_ERR_INVALID;
     if (n > r->max_seqs) return MUX_ERR_INVALID;
+    ++r->jobs_launched;
+    r->seqs_launched += n;
     rc = mux_sched_job_seqs(r->sched, job, nullptr, r->slots.data(), r->lens.data(), r->flags.data());
     if (rc != MUX_OK) return rc;
     ModelRun &m = r->models[model];
     const int32_t *table = mux_sched_table(r->sched, model);
     const int32_t B = r->pool->block_size, heads = m.hkv, cols = r->max_blocks;
-    int32_t *host = nullptr, *dev = nullptr;
-    int area = 0;
-    rc = claim_area(m, r->area_ints, &host, &dev, &area);
-    if (rc != MUX_OK) return rc;
 
     if (kind == MUX_JOB_PREFILL) {
+        int32_t *host = nullptr, *dev = nullptr;
+        int area = 0;
+        rc = claim_area(m, r->area_ints, &host, &dev, &area);
+        if (rc != MUX_OK) return rc;
         int64_t total = 0, id_ints = 0;
         int32_t longest = 0;
         for (int32_t i = 0; i < n; ++i) {
@@ -292,7 +325,7 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
     }
 
     if (kind != MUX_JOB_DECODE) return MUX_ERR_INVALID;
-    // area: context length per slot (0 = not in this step), up to the highest slot | entries | ids
+    // arrays: context length per slot (0 = not in this step), up to the highest slot | entries | ids
     int32_t rows = 0, longest = 0, n_entries = 0;
     for (int32_t i = 0; i < n; ++i) {
         if (r->slots[i] < 0 || r->slots[i] >= r->max_seqs) return MUX_ERR_INVALID;
@@ -302,6 +335,14 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
     }
     const size_t need = static_cast<size_t>(rows) + static_cast<size_t>(n_entries) * (kEntryInts + heads);
     if (need > r->area_ints) return MUX_ERR_INVALID;
+    const bool as_arguments = !r->stage_always && need <= static_cast<size_t>(kInlineInts);
+    InlineArrays inl;
+    int32_t *host = inl.v, *dev = nullptr;
+    int area = 0;
+    if (!as_arguments) {
+        rc = claim_area(m, r->area_ints, &host, &dev, &area);
+        if (rc != MUX_OK) return rc;
+    }
     int32_t *ctx = host, *entries = host + rows, *ids = entries + kEntryInts * n_entries;
     std::fill(ctx, ctx + rows, 0);
     int32_t e_at = 0;
@@ -317,13 +358,61 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
         for (int32_t h = 0; h < heads; ++h) ids[e_at * heads + h] = row[static_cast<size_t>(h) * cols + col];
         ++e_at;
     }
-    rc = send_area(m, area, host, dev, need);
-    if (rc != MUX_OK) return rc;
-    rc = install(m, dev + rows, dev + rows + kEntryInts * n_entries, n_entries, false, cols);
-    if (rc != MUX_OK) return rc;
+    const int32_t *ctx_dev = nullptr;
+    if (as_arguments) {
+        hipLaunchKernelGGL(install_inline_kernel, dim3(1), dim3(256), 0, m.stream, inl, rows, n_entries, m.ctx, m.tables, heads, cols);
+        if (!ok(hipGetLastError())) return MUX_ERR_HIP;
+        ctx_dev = m.ctx;
+    } else {
+        rc = send_area(m, area, host, dev, need);
+        if (rc != MUX_OK) return rc;
+        rc = install(m, dev + rows, dev + rows + kEntryInts * n_entries, n_entries, false, cols);
+        if (rc != MUX_OK) return rc;
+        ctx_dev = dev;
+    }
     m.launched = true;
-    return mux_decode_step(r->pool, out, q, k_new, v_new, m.tables, dev, 1, rows, m.hq, heads, cols, longest, scale, m.decode_ws,
+    return mux_decode_step(r->pool, out, q, k_new, v_new, m.tables, ctx_dev, 1, rows, m.hq, heads, cols, longest, scale, m.decode_ws,
                            m.decode_ws_bytes, m.stream);
+}
+
+int mux_runner_set_buffers(mux_runner_t *r, int32_t model, void *prefill_out, const void *prefill_q, const void *prefill_k,
+                           const void *prefill_v, void *decode_out, const void *decode_q, const void *decode_k,
+                           const void *decode_v, float scale)
+{
+    if (!r || model < 0 || model >= static_cast<int32_t>(r->models.size())) return MUX_ERR_INVALID;
+    if (!prefill_out || !prefill_q || !prefill_k || !prefill_v || !decode_out || !decode_q || !decode_k || !decode_v)
+        return MUX_ERR_INVALID;
+    ModelRun &m = r->models[model];
+    m.reg_out[0] = prefill_out, m.reg_q[0] = prefill_q, m.reg_k[0] = prefill_k, m.reg_v[0] = prefill_v;
+    m.reg_out[1] = decode_out, m.reg_q[1] = decode_q, m.reg_k[1] = decode_k, m.reg_v[1] = decode_v;
+    m.reg_scale = scale;
+    return MUX_OK;
+}
+
+int mux_runner_run_step(mux_runner_t *r, int32_t *n_jobs)
+{
+    int rc = mux_runner_step(r, n_jobs);
+    if (rc != MUX_OK) return rc;
+    for (int32_t j = 0; j < *n_jobs; ++j) {
+        int32_t kind = 0, model = 0, n = 0;
+        rc = mux_sched_job(r->sched, j, &kind, &model, &n);
+        if (rc != MUX_OK) return rc;
+        if (kind == MUX_JOB_PREEMPT) continue;
+        const ModelRun &m = r->models[model];
+        const int which = kind == MUX_JOB_DECODE ? 1 : 0;
+        if (!m.reg_out[which]) return MUX_ERR_INVALID;   // no buffers registered for this model
+        rc = mux_runner_launch(r, j, m.reg_out[which], m.reg_q[which], m.reg_k[which], m.reg_v[which], m.reg_scale);
+        if (rc != MUX_OK) return rc;
+    }
+    return MUX_OK;
+}
+
+int mux_runner_counts(const mux_runner_t *r, int64_t *counts)
+{
+    if (!r || !counts) return MUX_ERR_INVALID;
+    counts[0] = r->jobs_launched;
+    counts[1] = r->seqs_launched;
+    return MUX_OK;
 }
 
 int mux_runner_synchronize(mux_runner_t *r)

@@ -56,7 +56,7 @@ struct mux_sched {
     std::vector<int32_t> scratch_ids;
     struct Ended { int32_t model, slot, cached; };
     std::vector<Ended> ended;   // ended in the last iteration: blocks and slot held until the next one starts
-    bool released = false;      // the last iteration gave blocks back to the pool
+    std::vector<char> released; // per model: the last iteration gave blocks of this model back to the pool
 
     int32_t *row(Model &m, int32_t slot) { return m.table.data() + static_cast<size_t>(slot) * m.heads * cfg.max_blocks; }
     int32_t blocks_of(int32_t tokens) const { return (tokens + pool->block_size - 1) / pool->block_size; }
@@ -81,7 +81,7 @@ struct mux_sched {
             scratch_ids.insert(scratch_ids.end(), t + h * cfg.max_blocks, t + h * cfg.max_blocks + nb);
         mux_free_blocks(pool, model, static_cast<int64_t>(scratch_ids.size()), scratch_ids.data());
         m.slot_taken[slot] = 0;
-        released = true;
+        released[model] = 1;
     }
 
     // preemption: nothing launched for this iteration reads the request's blocks, they go back now
@@ -232,6 +232,7 @@ int mux_sched_create(mux_sched_t **out, mux_pool_t *pool, const mux_sched_config
         s->cfg = *cfg;
         s->cfg.heads = nullptr;   // copied into the models below; the caller's array is not kept
         s->models.resize(static_cast<size_t>(cfg->n_models));
+        s->released.assign(static_cast<size_t>(cfg->n_models), 0);
         for (int32_t i = 0; i < cfg->n_models; ++i) {
             Model &m = s->models[i];
             m.heads = cfg->heads[i];
@@ -274,7 +275,7 @@ int mux_sched_step(mux_sched_t *s, int32_t *n_jobs)
 {
     if (!s || !n_jobs) return MUX_ERR_INVALID;
     s->jobs.clear();
-    s->released = false;
+    std::fill(s->released.begin(), s->released.end(), 0);
     for (const mux_sched::Ended &e : s->ended) s->free_sequence(e.model, e.slot, e.cached);
     s->ended.clear();
     s->first_stamp = s->stamp;
@@ -343,4 +344,4 @@ void mux_sched_geometry(const mux_sched *s, int32_t *n_models, int32_t *max_seqs
     *max_prefill_tokens = s->cfg.max_prefill_tokens;
 }
 int32_t mux_sched_heads(const mux_sched *s, int32_t model) { return s->models[model].heads; }
-bool mux_sched_released_blocks(const mux_sched *s) { return s->released; }
+bool mux_sched_released_blocks(const mux_sched *s, int32_t model) { return s->released[model] != 0; }

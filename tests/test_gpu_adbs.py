@@ -63,9 +63,9 @@ def oracle_job_outputs(op, os_, src, shapes, job, scale):
     return op.decode_attn(q, np.maximum(table[slots], 0), lens, hq, scale)
 
 
-@pytest.mark.parametrize("driver", ["python", "runner", "runner-one-stream"])
+@pytest.mark.parametrize("driver", ["python", "runner", "runner-one-stream", "runner-staged"])
 @pytest.mark.parametrize("case", ["roomy", "tight-quota", "preempting"])
-def test_scheduler_drives_kernels_like_the_oracle(case, driver):
+def test_scheduler_drives_kernels_like_the_oracle(case, driver, monkeypatch):
     print("[case] adbs %s, driver %s" % (case, driver), flush=True)
     shapes = [wl.ModelShape("a", 8, 8, 128), wl.ModelShape("b", 16, 4, 128), wl.ModelShape("c", 4, 4, 128)]
     d, B = 128, 16
@@ -85,6 +85,8 @@ def test_scheduler_drives_kernels_like_the_oracle(case, driver):
     if driver == "python":
         engine = eng.Engine(pool, shapes, max_seqs, max_blocks, budget, src, **kw)
     else:
+        # decode jobs send their arrays as kernel arguments when they fit; "staged" forces the pinned-memory copy instead
+        monkeypatch.setenv("MUX_RUNNER_STAGE_ALWAYS", "1" if driver == "runner-staged" else "0")
         engine = eng.NativeEngine(pool, shapes, max_seqs, max_blocks, budget, src, shared_stream=driver == "runner-one-stream", **kw)
     os_ = orc.OracleScheduler(op, [s.n_kv_heads for s in shapes], max_seqs, max_blocks, budget, **kw)
     scale = H.default_scale(d)
@@ -132,3 +134,52 @@ def test_scheduler_drives_kernels_like_the_oracle(case, driver):
     if case == "preempting":
         assert mx.MUX_JOB_PREEMPT in kinds
     print("adbs %s: %d requests, %d iterations, max abs err %.2e" % (case, rid, engine.iterations, worst), flush=True)
+
+
+def test_run_step_with_registered_buffers_equals_step_plus_launch():
+    """mux_runner_run_step (one call per iteration, buffers registered once) does what mux_runner_step +
+    mux_runner_launch per job do: same jobs, same bytes in the pool, same outputs, bit for bit."""
+    print("[case] runner run_step against step + launch", flush=True)
+    shapes = [wl.ModelShape("a", 8, 8, 128), wl.ModelShape("b", 16, 4, 128)]
+    d, B, n_blocks, max_seqs, max_blocks, budget = 128, 16, 500, 6, 24, 256
+    order = wl.placement_order(np.random.default_rng(5), n_blocks)
+    sides = []
+    for _ in range(2):
+        kv = torch.zeros(n_blocks * 2 * B * d * 2, dtype=torch.uint8, device="cuda")
+        pool = mx.mux_pool_create(kv, n_blocks, B, d, mx.MUX_BF16, order)
+        torch.manual_seed(11)                                           # both sides get the same buffer contents
+        engine = eng.NativeEngine(pool, shapes, max_seqs, max_blocks, budget, None)
+        sides.append((kv, pool, engine))
+    (kv_a, _, a), (kv_b, _, b) = sides
+    for st_a, st_b in zip(a.models, b.models):
+        for name in ("k_dec", "v_dec", "q_dec", "k_pre", "v_pre", "q_pre"):
+            assert torch.equal(getattr(st_a, name), getattr(st_b, name))
+    rng = np.random.default_rng(6)
+    rid = 0
+    for it in range(400):
+        if it < 40:
+            for _ in range(int(rng.poisson(0.7))):
+                m, plen, olen = int(rng.integers(2)), int(rng.integers(1, 200)), int(rng.integers(1, 60))
+                a.submit(m, rid, plen, olen)
+                b.submit(m, rid, plen, olen)
+                rid += 1
+        n_a = a.step()                                                  # registered buffers, one call
+        n_b = b.runner.step()
+        assert n_a == n_b
+        for j in range(n_b):
+            kind, model, _ = b.sched.job(j)
+            st = b.models[model]
+            if kind == mx.MUX_JOB_PREFILL:
+                b.runner.launch(j, st.out_pre, st.q_pre, st.k_pre, st.v_pre, b.scale)
+            elif kind == mx.MUX_JOB_DECODE:
+                b.runner.launch(j, st.out_dec, st.q_dec, st.k_dec, st.v_dec, b.scale)
+        a.runner.synchronize()
+        b.runner.synchronize()
+        for st_a, st_b in zip(a.models, b.models):
+            assert torch.equal(st_a.out_dec.view(torch.int16), st_b.out_dec.view(torch.int16))
+            assert torch.equal(st_a.out_pre.view(torch.int16), st_b.out_pre.view(torch.int16))
+        if it >= 40 and a.idle():
+            break
+    assert a.idle() and b.idle() and rid > 10
+    assert torch.equal(kv_a, kv_b)
+    assert a.runner.counts() == b.runner.counts() and a.tokens() > rid
