@@ -211,3 +211,53 @@ def test_probe_argument_checks_need_no_gpu():
     assert lib.mux_probe_mfma(None, 4, 4, None, None) == mx.MUX_ERR_INVALID
     assert lib.mux_probe_mfma(fake, 0, 4, None, None) == mx.MUX_ERR_INVALID
     assert lib.mux_probe_mfma(fake, 4, 0, None, None) == mx.MUX_ERR_INVALID
+
+
+def test_block_manager_is_safe_from_several_host_threads():
+    """The header allows pool calls from several host threads (one per colocated model): eight
+    threads allocate and free concurrently on one pool (ctypes drops the interpreter lock during
+    the calls).  No id may ever be held twice, counters must add up, foreign frees must fail."""
+    import threading
+
+    n_blocks, n_threads, ops = 4096, 8, 3000
+    p = host_pool(n_blocks)
+    lib = mx.load()
+    held = [[] for _ in range(n_threads)]          # per thread: arrays of ids it holds
+    errors = []
+    start = threading.Barrier(n_threads)
+
+    def worker(t):
+        rng = np.random.default_rng(1000 + t)
+        ids = np.zeros(64, np.int32)
+        start.wait()
+        for _ in range(ops):
+            if held[t] and rng.random() < 0.5:
+                mine = held[t].pop(int(rng.integers(len(held[t]))))
+                if lib.mux_free_blocks(p.handle, t, mine.size, mine.ctypes.data) != 0:
+                    errors.append("thread %d: freeing its own ids failed" % t)
+            else:
+                n = int(rng.integers(1, 65))
+                rc = lib.mux_alloc_blocks(p.handle, t, n, ids.ctypes.data)
+                if rc == 0:
+                    held[t].append(ids[:n].copy())
+                elif rc != mx.MUX_ERR_NOMEM:
+                    errors.append("thread %d: alloc returned %d" % (t, rc))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(n_threads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors[:3]
+    all_ids = np.concatenate([a for h in held for a in h]) if any(held) else np.zeros(0, np.int32)
+    assert all_ids.size == np.unique(all_ids).size and (all_ids >= 0).all() and (all_ids < n_blocks).all()
+    for t in range(n_threads):
+        assert mx.mux_pool_num_used(p, t) == sum(a.size for a in held[t])
+    assert mx.mux_pool_num_free(p) == n_blocks - all_ids.size
+    # an id held by thread 0's model cannot be freed on behalf of model 1
+    if held[0]:
+        assert lib.mux_free_blocks(p.handle, 1, 1, held[0][0][:1].ctypes.data) == mx.MUX_ERR_INVALID
+    for t in range(n_threads):
+        for a in held[t]:
+            assert lib.mux_free_blocks(p.handle, t, a.size, a.ctypes.data) == 0
+    assert mx.mux_pool_num_free(p) == n_blocks
