@@ -926,17 +926,21 @@ mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_
     } else {
         const long long items = static_cast<long long>(n_seqs) * n_kv_heads * plan.n_passes;
         long long want_splits = (2048 + items - 1) / items;
-        // Splitting adds the work-list and merge kernels to the chain (~15 us, the time ~100 MB of
-        // K/V take).  For a short launch that is more than the split can win back: without it
-        // the loss is at most the imbalance of whole rows over the resident workgroups (a GPU
-        // half full of workgroups already streams at ~90 % of its bandwidth).
-        static const bool split_short = env_int("MUX_DECODE_SPLIT_SHORT", 0) != 0;
-        const double bound_bytes = static_cast<double>(items) * ctx_blocks * pool->block_bytes;   // every row at max_ctx_len
-        const double slots = uses_group_kernel(pool, group) ? 512.0 : 1024.0;
-        const double rounds = items / slots;
-        const double imbalance = rounds >= 1.0 ? static_cast<double>((items + static_cast<long long>(slots) - 1) / static_cast<long long>(slots)) / rounds
-                                               : std::max(1.0, 0.5 / rounds);
-        if (!split_short && bound_bytes <= 768e6 && bound_bytes * (imbalance - 1.0) <= 100e6) want_splits = 1;
+        // Splitting adds the work-list and merge kernels to the chain (~20 us end to end) and only pays
+        // when whole rows cannot keep the GPU busy: a lone workgroup streams ~50 GB/s, so a
+        // few hundred of them already saturate the memory system, and the longest-first
+        // assignment balances whole rows well.  Estimate both ways from what the host knows
+        // (every row at max_ctx_len; a typical batch holds ~0.56 of that) and keep the rows
+        // whole unless the split wins.  MUX_DECODE_SPLIT_SHORT=1 switches the estimate off.
+        static const bool always_split = env_int("MUX_DECODE_SPLIT_SHORT", 0) != 0;
+        if (want_splits > 1 && ctx_blocks <= max_span && !always_split) {
+            const double row_us = static_cast<double>(ctx_blocks) * pool->block_bytes / 50e3;
+            const double total_us = 0.56 * static_cast<double>(items) * ctx_blocks * pool->block_bytes / 6.5e6;
+            const long long slots = uses_group_kernel(pool, group) ? 512 : 1024;
+            const long long whole = (items + slots - 1) / slots;
+            const double uneven = items >= slots ? static_cast<double>(whole) * slots / items : 1.0;   // equal rows, worst case
+            if (std::max(row_us * whole, total_us * uneven) <= total_us + 20.0) want_splits = 1;
+        }
         if (want_splits > ctx_blocks) want_splits = ctx_blocks;
         if (want_splits < 1) want_splits = 1;
         span = (ctx_blocks + want_splits - 1) / want_splits;
