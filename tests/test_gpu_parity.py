@@ -158,6 +158,20 @@ def test_decode_batches_too_large_to_rank_in_the_kernel(n_q, n_kv):
     print("max abs err %.2e" % err)
 
 
+@pytest.mark.parametrize("n_q,n_kv", [(2, 2), (8, 1), (4, 1)])
+def test_decode_few_long_rows_are_split_into_spans(n_q, n_kv):
+    """A handful of long rows cannot fill the GPU as whole rows: the host plan splits them into spans
+    (partial results in the workspace, merged by the combine kernel).  Short and empty rows ride along."""
+    _say("decode, few long rows, Hq=%d Hkv=%d" % (n_q, n_kv))
+    lens = [4000, 3000, 17, 0, 2500]
+    ls, job, q, got, want = _decode_case("bf16", 128, 16, n_q, n_kv, lens, seed=60 + n_q)
+    plan_only = 16 + len(lens) * 8 + 16
+    assert mx.mux_decode_workspace_bytes(ls.lib, len(lens), n_q, n_kv, 4000) > plan_only    # the plan did split
+    err = H.assert_close(got, want, "bf16")
+    assert not got[3].float().abs().max().item()
+    print("max abs err %.2e" % err)
+
+
 def test_decode_rows_sum_to_one_on_gpu():
     """V == 1 everywhere => O == 1 (softmax weights sum to one), checked on the GPU path."""
     rng = np.random.Generator(np.random.PCG64(3))
