@@ -405,10 +405,12 @@ def run_adbs(args) -> int:
     shapes = [wl.LLAMA_13B, wl.LLAMA_7B, wl.LLAMA_7B]
     rates = np.array([2.0, 8.0, 8.0])
     length_scale = [2, 1, 1]
-    B, d, n_blocks, max_seqs, max_blocks = 16, 128, 40000, 64, 96
+    S = max(int(args.adbs_scale), 1)                   # pool, slots, arrivals and prefill budget grow together
+    B, d, n_blocks, max_seqs, max_blocks = 16, 128, 40000 * S, min(64 * S, 1024), 96
+    budget = 2048 * S
     iters = max(args.steps, 1) * 8
-    warm = max(args.warmup, 1) * 8
-    per_iter = 1.0 * rates / rates.sum()               # requests per iteration and model
+    warm = max(args.warmup, 1) * 8 * (2 if S > 1 else 1)
+    per_iter = S * rates / rates.sum()                 # requests per iteration and model
     out = {}
     for mode in ("adbs", "no-quota"):
         kv = torch.empty(n_blocks * 2 * B * d * 2, dtype=torch.uint8, device="cuda")
@@ -420,10 +422,10 @@ def run_adbs(args) -> int:
             assert mx.mux_pool_init_quotas(pool, weights) == 0
             kw = dict(adapt_period=16, low=0.5, high=0.9, step=0.25)
         if args.adbs_driver == "python":
-            engine = eng.Engine(pool, shapes, max_seqs, max_blocks, 2048, eng.DeviceRandomSource(shapes, d, seed=1),
+            engine = eng.Engine(pool, shapes, max_seqs, max_blocks, budget, eng.DeviceRandomSource(shapes, d, seed=1),
                                 keep_outputs=False, **kw)
         else:
-            engine = eng.NativeEngine(pool, shapes, max_seqs, max_blocks, 2048, None,
+            engine = eng.NativeEngine(pool, shapes, max_seqs, max_blocks, budget, None,
                                       shared_stream=args.adbs_driver == "runner-one-stream", **kw)
         use = np.zeros(len(shapes))
         rid, t0, tok0 = 0, None, 0
@@ -446,6 +448,7 @@ def run_adbs(args) -> int:
             "ms_per_iteration": dt / iters * 1e3,
             "block_usage_share": [round(float(x), 4) for x in use / max(use.sum(), 1)],
             "mean_blocks_in_use": float(use.sum() / iters),
+            "kv_GBps_decode_reads": float(use.sum() / iters) * 2 * B * d * 2 / (dt / iters) / 1e9,
             "finished": [c[2] for c in counts], "preemptions": [c[3] for c in counts], "waiting_at_end": [c[0] for c in counts],
             "quota_blocks_moved": counts[0][4],
         }
@@ -457,8 +460,8 @@ def run_adbs(args) -> int:
         "n_gpus": 1, "steps": iters, "warmup": warm, "ms_per_step": a["ms_per_iteration"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16 storage, f32 arithmetic", "data": "synthetic",
         "config": {"workload": "batch scheduler (Algorithm 3) over 13B/7B/7B-shaped models, Poisson arrivals 2:8:8, request "
-                               "lengths 2:1:1, %d head-blocks, %d slots per model; every job launched on the GPU, driver: %s"
-                               % (n_blocks, max_seqs, args.adbs_driver)},
+                               "lengths 2:1:1, %d requests per pass, %d head-blocks, %d slots per model, prefill budget %d tokens; every job "
+                               "launched on the GPU, driver: %s" % (S, n_blocks, max_seqs, budget, args.adbs_driver)},
         "rate_share": [round(float(x), 4) for x in rates / rates.sum()],
         "adbs": a, "no_quota": out["no-quota"],
     }
@@ -487,6 +490,8 @@ def main() -> int:
     ap.add_argument("--adbs-driver", choices=["runner", "runner-one-stream", "python"], default="runner",
                     help="who launches the scheduler's jobs: the library's runner (one stream per model, or one for all) "
                          "or the Python driver")
+    ap.add_argument("--adbs-scale", type=int, default=1,
+                    help="--adbs: multiply pool size, sequence slots, arrivals per pass and prefill token budget")
     ap.add_argument("--no-solo", action="store_true", help="skip the per-model solo passes after the timed loop")
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 1 GiB device copies after the timed loop")
     args = ap.parse_args()
