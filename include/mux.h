@@ -305,7 +305,8 @@ MUX_API int mux_sched_counts(const mux_sched_t *sched, int32_t model, int64_t *c
  * (table copies, staging areas, kernel workspaces: allocated in mux_runner_create on the
  * current device, freed in mux_runner_destroy); launches allocate nothing.
  *
- * mux_runner_create: `sched` must have been created over `pool`; every model is one layer,
+ * mux_runner_create: `sched` must have been created over `pool` and both must outlive the
+ *   runner (destroy the runner first); every model is one layer,
  *   its KV heads = the scheduler's `heads`.  n_q_heads: HOST array per model, a multiple of
  *   the model's KV heads.  streams: HOST array of hipStream_t per model (NULL = all on the
  *   default stream); models may share a stream.

@@ -354,7 +354,10 @@ class Scheduler:
             self.handle = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: the module's globals may already be gone
+            pass
 
     def submit(self, model: int, request_id: int, prompt_len: int, output_len: int) -> int:
         return load().mux_sched_submit(self.handle, model, request_id, prompt_len, output_len)
@@ -417,7 +420,10 @@ class Runner:
             self.handle = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: the module's globals may already be gone
+            pass
 
     def step(self) -> int:
         """One scheduler iteration (plus stream ordering when blocks changed hands); number of jobs."""

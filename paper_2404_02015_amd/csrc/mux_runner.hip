@@ -336,7 +336,7 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
     const size_t need = static_cast<size_t>(rows) + static_cast<size_t>(n_entries) * (kEntryInts + heads);
     if (need > r->area_ints) return MUX_ERR_INVALID;
     const bool as_arguments = !r->stage_always && need <= static_cast<size_t>(kInlineInts);
-    InlineArrays inl;
+    InlineArrays inl{};
     int32_t *host = inl.v, *dev = nullptr;
     int area = 0;
     if (!as_arguments) {
