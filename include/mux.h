@@ -306,27 +306,32 @@ MUX_API int mux_sched_counts(const mux_sched_t *sched, int32_t model, int64_t *c
  * current device, freed in mux_runner_destroy); launches allocate nothing.
  *
  * mux_runner_create: `sched` must have been created over `pool` and both must outlive the
- *   runner (destroy the runner first); every model is one layer,
- *   its KV heads = the scheduler's `heads`.  n_q_heads: HOST array per model, a multiple of
- *   the model's KV heads.  streams: HOST array of hipStream_t per model (NULL = all on the
- *   default stream); models may share a stream.
+ *   runner (destroy the runner first).  n_q_heads: HOST array per model, query heads of ONE
+ *   layer.  n_layers: HOST array per model, or NULL for one layer each; the scheduler's
+ *   `heads` of the model must be n_layers x (KV heads of a layer), its head index being
+ *   layer x KV heads + head, and n_q_heads a multiple of the KV heads of a layer.  streams:
+ *   HOST array of hipStream_t per model (NULL = all on the default stream); models may share
+ *   a stream.
  * mux_runner_step: mux_sched_step, plus the ordering the scheduler asks for: for every model
  *   whose blocks went back to the pool in this iteration, what was launched so far on that
  *   model's stream (the last readers of those blocks) is ordered, by an event and without a
  *   host wait, before what is launched next on the other models' streams.
- * mux_runner_launch: enqueues job `job` of the last step; returns without waiting.
- *   Prefill job of n requests with T tokens in total: k_new, v_new DEVICE [T][kv heads][d],
- *   q, out DEVICE [T][q heads][d], rows packed request by request in the job's order
- *   (positions 0 .. len-1 of each).  Decode job: k_new, v_new DEVICE [max_seqs][kv heads][d],
- *   q, out DEVICE [max_seqs][q heads][d], row = the sequence's SLOT (the row of the
- *   scheduler's table; rows of slots outside the job are neither read nor appended, their
- *   out rows up to the job's highest slot are zeroed).  Preempt jobs launch nothing.  The
- *   buffers must stay untouched until the work has finished on the model's stream.
- *   Jobs of one step are launched in job order, each at most once.
+ * mux_runner_launch: enqueues job `job` of the last step, for ALL layers of its model; returns
+ *   without waiting.  With L = the model's layers:
+ *   Prefill job of n requests with T tokens in total: k_new, v_new DEVICE [L][T][kv heads][d],
+ *   q, out DEVICE [L][T][q heads][d], rows packed request by request in the job's order
+ *   (positions 0 .. len-1 of each); one append + one attention launch per layer.
+ *   Decode job: k_new, v_new DEVICE [L][R][kv heads][d], q, out DEVICE [L][R][q heads][d], row =
+ *   the sequence's SLOT (the row of the scheduler's table); R = max_seqs, or for a model of one
+ *   layer any number of rows above the job's highest slot.  Rows of slots outside the job are
+ *   neither read nor appended; their out rows (up to the job's highest slot, all of them for
+ *   L > 1) are zeroed.  One launch for all layers (mux_decode_step).
+ *   Preempt jobs launch nothing.  The buffers must stay untouched until the work has finished
+ *   on the model's stream.  Jobs of one step are launched in job order, each at most once.
  * mux_runner_set_buffers / mux_runner_run_step: for engines that keep their Q/K/V/output in
- *   fixed buffers (shapes as for mux_runner_launch: the prefill set sized for the largest
- *   prefill job - max(max_prefill_tokens, max_blocks x block_size) tokens -, the decode set
- *   for max_seqs rows).  mux_runner_run_step = mux_runner_step followed by mux_runner_launch
+ *   fixed buffers (shapes as for mux_runner_launch: the decode set for max_seqs rows; the
+ *   prefill set large enough for the largest prefill job, max(max_prefill_tokens, max_blocks x
+ *   block_size) tokens - the layer stride of a prefill buffer is the job's own T rows).  mux_runner_run_step = mux_runner_step followed by mux_runner_launch
  *   of every job with its model's registered buffers and scale: one call per iteration.
  *   A job of a model without registered buffers -> MUX_ERR_INVALID (jobs before it were
  *   launched).
@@ -334,14 +339,15 @@ MUX_API int mux_sched_counts(const mux_sched_t *sched, int32_t model, int64_t *c
  *   them (every sequence of such a job yields one output token).
  * mux_runner_synchronize: waits for every model's stream.
  * mux_runner_read_table: waits for the model's stream and copies the runner's device copy of
- *   the model's table to host_out (HOST int32 [max_seqs][heads][max_blocks]; entries the
- *   scheduler never handed out are 0).  For checks; not part of the serving loop.
+ *   the model's table to host_out (HOST int32 [layers][max_seqs][KV heads of a layer]
+ *   [max_blocks]; entries the scheduler never handed out are 0).  For checks; not part of the
+ *   serving loop.
  * Errors: MUX_ERR_INVALID (arguments), MUX_ERR_HIP (runtime), MUX_ERR_NOMEM (host memory).
  * Not thread-safe: one caller at a time, the same as the scheduler it drives.
  * ------------------------------------------------------------------------------- */
 typedef struct mux_runner mux_runner_t;
 MUX_API int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, const int32_t *n_q_heads,
-                              void *const *streams);
+                              const int32_t *n_layers, void *const *streams);
 MUX_API int mux_runner_destroy(mux_runner_t *runner);
 MUX_API int mux_runner_step(mux_runner_t *runner, int32_t *n_jobs);
 MUX_API int mux_runner_launch(mux_runner_t *runner, int32_t job, void *out, const void *q, const void *k_new,

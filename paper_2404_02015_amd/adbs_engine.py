@@ -182,32 +182,45 @@ class Engine:
 
 
 class _NativeModel:
-    def __init__(self, pool, shape, max_seqs, max_tokens, device, stream):
+    def __init__(self, pool, shape, layers, max_seqs, max_tokens, device, stream):
         d = pool.head_dim
         kw = dict(dtype=torch.bfloat16, device=device)
-        self.shape, self.stream = shape, stream
-        # decode buffers: row = the sequence's slot; prefill buffers: the job's tokens, packed
-        self.k_dec, self.v_dec = (torch.randn(max_seqs, shape.n_kv_heads, d, **kw) for _ in range(2))
-        self.q_dec, self.out_dec = (torch.randn(max_seqs, shape.n_q_heads, d, **kw) for _ in range(2))
-        self.k_pre, self.v_pre = (torch.randn(max_tokens, shape.n_kv_heads, d, **kw) for _ in range(2))
-        self.q_pre, self.out_pre = (torch.randn(max_tokens, shape.n_q_heads, d, **kw) for _ in range(2))
+        self.shape, self.layers, self.stream = shape, layers, stream
+        # decode buffers: [layer][slot][heads][d]; prefill buffers: room for [layer][the job's tokens, packed][heads][d]
+        self.k_dec, self.v_dec = (torch.randn(layers, max_seqs, shape.n_kv_heads, d, **kw) for _ in range(2))
+        self.q_dec, self.out_dec = (torch.randn(layers, max_seqs, shape.n_q_heads, d, **kw) for _ in range(2))
+        self.k_pre, self.v_pre = (torch.randn(layers * max_tokens, shape.n_kv_heads, d, **kw) for _ in range(2))
+        self.q_pre, self.out_pre = (torch.randn(layers * max_tokens, shape.n_q_heads, d, **kw) for _ in range(2))
+
+    def layered(self, wide: torch.Tensor) -> torch.Tensor:
+        """[rows][layers * heads][d] (the layout of a value source: one wide layer) -> [layers][rows][heads][d]."""
+        rows, wide_heads, d = wide.shape
+        return wide.view(rows, self.layers, wide_heads // self.layers, d).permute(1, 0, 2, 3)
+
+    def wide(self, layered: torch.Tensor) -> torch.Tensor:
+        layers, rows, heads, d = layered.shape
+        return layered.permute(1, 0, 2, 3).reshape(rows, layers * heads, d)
 
 
 class NativeEngine:
-    """Engine's interface on top of mux_runner_*.  values = a source as for Engine, or None: the
-    buffers keep the random values they were created with (timing runs; step() then returns the
-    number of jobs and reads nothing back)."""
+    """Engine's interface on top of mux_runner_*.  shapes = the shape of ONE layer of every model,
+    layers = layers per model (default 1 each); the scheduler sees layers x KV heads blocks per
+    token span.  values = a source as for Engine, which sees a model as one wide layer of
+    layers x heads heads, or None: the buffers keep the random values they were created with
+    (timing runs; step() then returns the number of jobs and reads nothing back)."""
 
     def __init__(self, pool: mx.Pool, shapes: Sequence, max_seqs: int, max_blocks: int, max_prefill_tokens: int, values=None,
-                 device="cuda", keep_outputs: bool = True, shared_stream: bool = False, **sched_kw):
+                 device="cuda", keep_outputs: bool = True, shared_stream: bool = False, layers=None, **sched_kw):
         self.pool, self.shapes, self.values, self.device = pool, list(shapes), values, device
+        self.layers = [1] * len(self.shapes) if layers is None else [int(x) for x in layers]
         self.keep_outputs = keep_outputs and values is not None
-        self.sched = mx.Scheduler(pool, [s.n_kv_heads for s in shapes], max_seqs, max_blocks, max_prefill_tokens, **sched_kw)
+        self.sched = mx.Scheduler(pool, [s.n_kv_heads * n for s, n in zip(shapes, self.layers)], max_seqs, max_blocks,
+                                  max_prefill_tokens, **sched_kw)
         one = torch.cuda.Stream(device=device) if shared_stream else None
         streams = [one or torch.cuda.Stream(device=device) for _ in shapes]
-        self.runner = mx.Runner(self.sched, [s.n_q_heads for s in shapes], streams)
+        self.runner = mx.Runner(self.sched, [s.n_q_heads for s in shapes], streams, n_layers=self.layers)
         max_tokens = max(max_prefill_tokens, max_blocks * pool.block_size)
-        self.models = [_NativeModel(pool, s, max_seqs, max_tokens, device, st) for s, st in zip(shapes, streams)]
+        self.models = [_NativeModel(pool, s, n, max_seqs, max_tokens, device, st) for s, n, st in zip(shapes, self.layers, streams)]
         torch.cuda.synchronize()
         self.scale = 1.0 / math.sqrt(pool.head_dim)
         self.iterations = 0
@@ -231,13 +244,13 @@ class NativeEngine:
         if job["kind"] == mx.MUX_JOB_PREFILL:
             k, v, q = _job_values(self.values, model, ids, np.zeros_like(lens), lens)
             n = int(lens.sum())
-            st.k_pre[:n], st.v_pre[:n], st.q_pre[:n] = k, v, q
+            for buf, val in ((st.k_pre, k), (st.v_pre, v), (st.q_pre, q)):
+                buf[:st.layers * n].view(st.layers, n, buf.shape[1], buf.shape[2]).copy_(st.layered(val))
         else:
             k, v, q = _job_values(self.values, model, ids, lens - 1, lens)
             slots = torch.from_numpy(job["slots"].astype(np.int64)).to(self.device)
-            st.k_dec.index_copy_(0, slots, k)
-            st.v_dec.index_copy_(0, slots, v)
-            st.q_dec.index_copy_(0, slots, q)
+            for buf, val in ((st.k_dec, k), (st.v_dec, v), (st.q_dec, q)):
+                buf.index_copy_(1, slots, st.layered(val))
 
     def step(self):
         if self.values is None:
@@ -261,9 +274,10 @@ class NativeEngine:
                 out = None
                 if self.keep_outputs:
                     if prefill:
-                        out = st.out_pre[:int(job["lens"].sum())].clone()
+                        t = int(job["lens"].sum())
+                        out = st.wide(st.out_pre[:st.layers * t].view(st.layers, t, st.shape.n_q_heads, self.pool.head_dim))
                     else:
-                        out = st.out_dec.index_select(0, torch.from_numpy(job["slots"].astype(np.int64)).to(self.device))
+                        out = st.wide(st.out_dec.index_select(1, torch.from_numpy(job["slots"].astype(np.int64)).to(self.device)))
             results.append((job, out))
         if self.keep_outputs:
             self.runner.synchronize()

@@ -88,7 +88,7 @@ def load() -> C.CDLL:
     L.mux_sched_table.argtypes = [vp, i32]
     L.mux_sched_table.restype = C.POINTER(i32)
     L.mux_sched_counts.argtypes = [vp, i32, vp]
-    L.mux_runner_create.argtypes = [C.POINTER(vp), vp, vp, vp, vp]
+    L.mux_runner_create.argtypes = [C.POINTER(vp), vp, vp, vp, vp, vp]
     L.mux_runner_destroy.argtypes = [vp]
     L.mux_runner_step.argtypes = [vp, C.POINTER(i32)]
     L.mux_runner_launch.argtypes = [vp, i32, vp, vp, vp, vp, f32]
@@ -402,16 +402,17 @@ class Runner:
     the current stream for all).  The tensors passed to launch() must stay alive and untouched
     until the work has finished on the model's stream."""
 
-    def __init__(self, sched: Scheduler, n_q_heads, streams=None):
+    def __init__(self, sched: Scheduler, n_q_heads, streams=None, n_layers=None):
         self.sched = sched
         self.n_q_heads = np.ascontiguousarray(n_q_heads, dtype=np.int32)
-        if self.n_q_heads.size != sched.heads.size:
-            raise ValueError("one query-head count per model")
+        self.n_layers = np.ascontiguousarray(n_layers if n_layers is not None else np.ones(sched.heads.size), dtype=np.int32)
+        if self.n_q_heads.size != sched.heads.size or self.n_layers.size != sched.heads.size:
+            raise ValueError("one query-head count and one layer count per model")
         self.streams = list(streams) if streams is not None else [torch.cuda.current_stream()] * sched.heads.size
         handles = (C.c_void_p * len(self.streams))(*[s.cuda_stream or None for s in self.streams])
         h = C.c_void_p()
-        _check(load().mux_runner_create(C.byref(h), sched.pool.handle, sched.handle, self.n_q_heads.ctypes.data, handles),
-               "mux_runner_create")
+        _check(load().mux_runner_create(C.byref(h), sched.pool.handle, sched.handle, self.n_q_heads.ctypes.data,
+                                        self.n_layers.ctypes.data, handles), "mux_runner_create")
         self.handle = h.value
 
     def close(self):
@@ -457,9 +458,9 @@ class Runner:
         _check(load().mux_runner_synchronize(self.handle), "mux_runner_synchronize")
 
     def read_table(self, model: int) -> np.ndarray:
-        """Host copy of the runner's device table of a model, [max_seqs][heads][max_blocks]."""
-        heads = int(self.sched.heads[model])
-        host = np.empty((self.sched.max_seqs, heads, self.sched.max_blocks), np.int32)
+        """Host copy of the runner's device table of a model, [layers][max_seqs][KV heads of a layer][max_blocks]."""
+        layers = int(self.n_layers[model])
+        host = np.empty((layers, self.sched.max_seqs, int(self.sched.heads[model]) // layers, self.sched.max_blocks), np.int32)
         _check(load().mux_runner_read_table(self.handle, model, host.ctypes.data), "mux_runner_read_table")
         return host
 

@@ -21,19 +21,26 @@ namespace {
 constexpr int kRing = 4;          // staging areas per model: a job's area is rewritten 4 jobs later
 constexpr int kEntryInts = 5;     // slot, job row (-1: none), first column, columns, offset of the ids
 
+// Device tables are laid out [layer][max_seqs][kv heads of a layer][max_blocks]: the scheduler's
+// head index hh = layer * hkv + head.  Cell of (row, hh):
+__device__ __forceinline__ size_t table_cell(int row, int hh, int hkv, int max_seqs)
+{
+    return (static_cast<size_t>(hh / hkv) * max_seqs + row) * hkv + hh % hkv;
+}
+
 // One workgroup per entry: the ids of one sequence, head-major [heads][n_cols], go to columns
 // col0 .. col0+n_cols-1 of its row in the model's table and, for a prefill, of the job's table.
 __global__ void install_blocks_kernel(const int32_t *__restrict__ entries, const int32_t *__restrict__ ids,
-                                      int32_t *__restrict__ slot_tables, int32_t *__restrict__ job_tables, int heads,
-                                      int max_blocks)
+                                      int32_t *__restrict__ slot_tables, int32_t *__restrict__ job_tables, int heads, int hkv,
+                                      int max_seqs, int max_blocks)
 {
     const int32_t *e = entries + static_cast<size_t>(blockIdx.x) * kEntryInts;
     const int slot = e[0], job_row = e[1], col0 = e[2], n_cols = e[3], at = e[4];
     for (int i = threadIdx.x; i < heads * n_cols; i += blockDim.x) {
         const int h = i / n_cols, j = i - h * n_cols;
         const int32_t id = ids[at + i];
-        slot_tables[(static_cast<size_t>(slot) * heads + h) * max_blocks + col0 + j] = id;
-        if (job_row >= 0) job_tables[(static_cast<size_t>(job_row) * heads + h) * max_blocks + col0 + j] = id;
+        slot_tables[table_cell(slot, h, hkv, max_seqs) * max_blocks + col0 + j] = id;
+        if (job_row >= 0) job_tables[table_cell(job_row, h, hkv, max_seqs) * max_blocks + col0 + j] = id;
     }
 }
 
@@ -44,21 +51,22 @@ struct InlineArrays {
     int32_t v[kInlineInts];
 };
 __global__ void install_inline_kernel(InlineArrays a, int rows, int n_entries, int32_t *__restrict__ ctx_out,
-                                      int32_t *__restrict__ slot_tables, int heads, int max_blocks)
+                                      int32_t *__restrict__ slot_tables, int heads, int hkv, int max_seqs, int max_blocks)
 {
     for (int i = threadIdx.x; i < rows; i += blockDim.x) ctx_out[i] = a.v[i];
     const int ids0 = rows + n_entries * kEntryInts;
     for (int i = threadIdx.x; i < n_entries * heads; i += blockDim.x) {
         const int e = i / heads, h = i - e * heads;
         const int slot = a.v[rows + e * kEntryInts], col = a.v[rows + e * kEntryInts + 2];
-        slot_tables[(static_cast<size_t>(slot) * heads + h) * max_blocks + col] = a.v[ids0 + i];
+        slot_tables[table_cell(slot, h, hkv, max_seqs) * max_blocks + col] = a.v[ids0 + i];
     }
 }
 
 struct ModelRun {
-    int32_t hq = 0, hkv = 0;
+    int32_t hq = 0, hkv = 0;         // query and KV heads of ONE layer
+    int32_t layers = 1, heads = 0;   // heads = layers * hkv = the scheduler's head count
     hipStream_t stream = nullptr;
-    int32_t *tables = nullptr;       // DEVICE [max_seqs][hkv][max_blocks], row = the scheduler's slot
+    int32_t *tables = nullptr;       // DEVICE [layers][max_seqs][hkv][max_blocks], row = the scheduler's slot
     int32_t *job_tables = nullptr;   // DEVICE, same shape, row = position in the current prefill job
     int32_t *ctx = nullptr;          // DEVICE [max_seqs]: context lengths of the current decode job, by slot
     void *decode_ws = nullptr, *prefill_ws = nullptr;
@@ -152,11 +160,11 @@ int send_area(ModelRun &m, int area, const int32_t *host, int32_t *dev, size_t n
     return MUX_OK;
 }
 
-int install(ModelRun &m, const int32_t *entries_dev, const int32_t *ids_dev, int n_entries, bool prefill, int max_blocks)
+int install(ModelRun &m, const int32_t *entries_dev, const int32_t *ids_dev, int n_entries, bool prefill, int max_seqs, int max_blocks)
 {
     if (n_entries == 0) return MUX_OK;
     hipLaunchKernelGGL(install_blocks_kernel, dim3(static_cast<unsigned>(n_entries)), dim3(256), 0, m.stream, entries_dev, ids_dev,
-                       m.tables, prefill ? m.job_tables : nullptr, m.hkv, max_blocks);
+                       m.tables, prefill ? m.job_tables : nullptr, m.heads, m.hkv, max_seqs, max_blocks);
     return ok(hipGetLastError()) ? MUX_OK : MUX_ERR_HIP;
 }
 
@@ -164,14 +172,16 @@ int install(ModelRun &m, const int32_t *entries_dev, const int32_t *ids_dev, int
 
 extern "C" {
 
-int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, const int32_t *n_q_heads, void *const *streams)
+int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, const int32_t *n_q_heads, const int32_t *n_layers,
+                      void *const *streams)
 {
     if (!out || !pool || !sched || !n_q_heads || mux_sched_pool(sched) != pool) return MUX_ERR_INVALID;
     int32_t n_models = 0, max_seqs = 0, max_blocks = 0, budget = 0;
     mux_sched_geometry(sched, &n_models, &max_seqs, &max_blocks, &budget);
     for (int32_t i = 0; i < n_models; ++i) {
-        const int32_t hkv = mux_sched_heads(sched, i);
-        if (n_q_heads[i] <= 0 || n_q_heads[i] % hkv != 0) return MUX_ERR_INVALID;
+        const int32_t heads = mux_sched_heads(sched, i), layers = n_layers ? n_layers[i] : 1;
+        if (layers <= 0 || heads % layers != 0) return MUX_ERR_INVALID;
+        if (n_q_heads[i] <= 0 || n_q_heads[i] % (heads / layers) != 0) return MUX_ERR_INVALID;
     }
     const int64_t max_ctx = static_cast<int64_t>(max_blocks) * pool->block_size;
     if (max_ctx > 0x7fffffff) return MUX_ERR_UNSUPPORTED;
@@ -208,14 +218,17 @@ int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, 
     for (int32_t i = 0; i < n_models; ++i) {
         ModelRun &m = r->models[i];
         m.hq = n_q_heads[i];
-        m.hkv = mux_sched_heads(sched, i);
-        const size_t table_bytes = static_cast<size_t>(max_seqs) * m.hkv * max_blocks * sizeof(int32_t);
+        m.heads = mux_sched_heads(sched, i);
+        m.layers = n_layers ? n_layers[i] : 1;
+        m.hkv = m.heads / m.layers;
+        const size_t table_bytes = static_cast<size_t>(max_seqs) * m.heads * max_blocks * sizeof(int32_t);
         // the split of long contexts depends on both the number of rows and the longest context:
-        // size the workspace for the worst launch this scheduler can produce
-        for (int32_t rows = 1; rows <= max_seqs; ++rows)
+        // size the workspace for the worst launch this scheduler can produce (a model of several
+        // layers always launches all its slots: the layers of a table are max_seqs rows apart)
+        for (int32_t rows = m.layers > 1 ? max_seqs : 1; rows <= max_seqs; ++rows)
             for (int32_t nb = 1; nb <= max_blocks; ++nb)
                 m.decode_ws_bytes = std::max(m.decode_ws_bytes,
-                                             mux_decode_step_workspace_bytes(pool, 1, rows, m.hq, m.hkv, nb * pool->block_size));
+                                             mux_decode_step_workspace_bytes(pool, m.layers, rows, m.hq, m.hkv, nb * pool->block_size));
         m.prefill_ws_bytes = mux_prefill_workspace_bytes(pool, max_seqs, r->max_tokens, static_cast<int32_t>(max_ctx), m.hq, m.hkv);
         bool good = m.decode_ws_bytes != 0;
         good = good && ok(hipMalloc(&m.tables, table_bytes)) && ok(hipMalloc(&m.job_tables, table_bytes));
@@ -275,7 +288,7 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
     if (rc != MUX_OK) return rc;
     ModelRun &m = r->models[model];
     const int32_t *table = mux_sched_table(r->sched, model);
-    const int32_t B = r->pool->block_size, heads = m.hkv, cols = r->max_blocks;
+    const int32_t B = r->pool->block_size, heads = m.heads, cols = r->max_blocks;
 
     if (kind == MUX_JOB_PREFILL) {
         int32_t *host = nullptr, *dev = nullptr;
@@ -315,13 +328,23 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
         if (rc != MUX_OK) return rc;
         const int32_t *d_seq = dev, *d_pos = dev + total, *d_cu = dev + 2 * total, *d_start = d_cu + n + 1;
         const int32_t *d_entries = d_start + n, *d_ids = d_entries + kEntryInts * n;
-        rc = install(m, d_entries, d_ids, n, true, cols);
+        rc = install(m, d_entries, d_ids, n, true, r->max_seqs, cols);
         if (rc != MUX_OK) return rc;
         m.launched = true;
-        rc = mux_kv_append(r->pool, k_new, v_new, d_seq, d_pos, m.job_tables, static_cast<int32_t>(total), n, heads, cols, m.stream);
-        if (rc != MUX_OK) return rc;
-        return mux_prefill_attn(r->pool, out, q, d_cu, d_start, m.job_tables, n, static_cast<int32_t>(total), longest, longest, m.hq,
-                                heads, cols, scale, m.prefill_ws, m.prefill_ws_bytes, m.stream);
+        // layer by layer: buffers are [layer][token][heads][d], the job's tables [layer][max_seqs rows][hkv][max_blocks]
+        const size_t eb = static_cast<size_t>(r->pool->elem_bytes) * r->pool->head_dim * static_cast<size_t>(total);
+        for (int32_t l = 0; l < m.layers; ++l) {
+            const int32_t *tab = m.job_tables + static_cast<size_t>(l) * r->max_seqs * m.hkv * cols;
+            const char *kl = static_cast<const char *>(k_new) + l * eb * m.hkv, *vl = static_cast<const char *>(v_new) + l * eb * m.hkv;
+            const char *ql = static_cast<const char *>(q) + l * eb * m.hq;
+            char *ol = static_cast<char *>(out) + l * eb * m.hq;
+            rc = mux_kv_append(r->pool, kl, vl, d_seq, d_pos, tab, static_cast<int32_t>(total), n, m.hkv, cols, m.stream);
+            if (rc != MUX_OK) return rc;
+            rc = mux_prefill_attn(r->pool, ol, ql, d_cu, d_start, tab, n, static_cast<int32_t>(total), longest, longest, m.hq, m.hkv,
+                                  cols, scale, m.prefill_ws, m.prefill_ws_bytes, m.stream);
+            if (rc != MUX_OK) return rc;
+        }
+        return MUX_OK;
     }
 
     if (kind != MUX_JOB_DECODE) return MUX_ERR_INVALID;
@@ -333,6 +356,7 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
         longest = std::max(longest, r->lens[i]);
         n_entries += (r->flags[i] & MUX_JOB_FLAG_TABLE) ? 1 : 0;
     }
+    if (m.layers > 1) rows = r->max_seqs;   // the layers of the device table are max_seqs rows apart
     const size_t need = static_cast<size_t>(rows) + static_cast<size_t>(n_entries) * (kEntryInts + heads);
     if (need > r->area_ints) return MUX_ERR_INVALID;
     const bool as_arguments = !r->stage_always && need <= static_cast<size_t>(kInlineInts);
@@ -360,19 +384,20 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
     }
     const int32_t *ctx_dev = nullptr;
     if (as_arguments) {
-        hipLaunchKernelGGL(install_inline_kernel, dim3(1), dim3(256), 0, m.stream, inl, rows, n_entries, m.ctx, m.tables, heads, cols);
+        hipLaunchKernelGGL(install_inline_kernel, dim3(1), dim3(256), 0, m.stream, inl, rows, n_entries, m.ctx, m.tables, heads, m.hkv,
+                           r->max_seqs, cols);
         if (!ok(hipGetLastError())) return MUX_ERR_HIP;
         ctx_dev = m.ctx;
     } else {
         rc = send_area(m, area, host, dev, need);
         if (rc != MUX_OK) return rc;
-        rc = install(m, dev + rows, dev + rows + kEntryInts * n_entries, n_entries, false, cols);
+        rc = install(m, dev + rows, dev + rows + kEntryInts * n_entries, n_entries, false, r->max_seqs, cols);
         if (rc != MUX_OK) return rc;
         ctx_dev = dev;
     }
     m.launched = true;
-    return mux_decode_step(r->pool, out, q, k_new, v_new, m.tables, ctx_dev, 1, rows, m.hq, heads, cols, longest, scale, m.decode_ws,
-                           m.decode_ws_bytes, m.stream);
+    return mux_decode_step(r->pool, out, q, k_new, v_new, m.tables, ctx_dev, m.layers, rows, m.hq, m.hkv, cols, longest, scale,
+                           m.decode_ws, m.decode_ws_bytes, m.stream);
 }
 
 int mux_runner_set_buffers(mux_runner_t *r, int32_t model, void *prefill_out, const void *prefill_q, const void *prefill_k,
@@ -427,7 +452,7 @@ int mux_runner_read_table(mux_runner_t *r, int32_t model, int32_t *host_out)
 {
     if (!r || model < 0 || model >= static_cast<int32_t>(r->models.size()) || !host_out) return MUX_ERR_INVALID;
     ModelRun &m = r->models[model];
-    const size_t bytes = static_cast<size_t>(r->max_seqs) * m.hkv * r->max_blocks * sizeof(int32_t);
+    const size_t bytes = static_cast<size_t>(r->max_seqs) * m.heads * r->max_blocks * sizeof(int32_t);
     if (!ok(hipStreamSynchronize(m.stream)) || !ok(hipMemcpy(host_out, m.tables, bytes, hipMemcpyDeviceToHost))) return MUX_ERR_HIP;
     return MUX_OK;
 }

@@ -63,7 +63,7 @@ def oracle_job_outputs(op, os_, src, shapes, job, scale):
     return op.decode_attn(q, np.maximum(table[slots], 0), lens, hq, scale)
 
 
-@pytest.mark.parametrize("driver", ["python", "runner", "runner-one-stream", "runner-staged"])
+@pytest.mark.parametrize("driver", ["python", "runner", "runner-one-stream", "runner-staged", "runner-layers"])
 @pytest.mark.parametrize("case", ["roomy", "tight-quota", "preempting"])
 def test_scheduler_drives_kernels_like_the_oracle(case, driver, monkeypatch):
     print("[case] adbs %s, driver %s" % (case, driver), flush=True)
@@ -87,7 +87,12 @@ def test_scheduler_drives_kernels_like_the_oracle(case, driver, monkeypatch):
     else:
         # decode jobs send their arrays as kernel arguments when they fit; "staged" forces the pinned-memory copy instead
         monkeypatch.setenv("MUX_RUNNER_STAGE_ALWAYS", "1" if driver == "runner-staged" else "0")
-        engine = eng.NativeEngine(pool, shapes, max_seqs, max_blocks, budget, src, shared_stream=driver == "runner-one-stream", **kw)
+        # "layers": models a and b run as 2 layers of half the heads each; the scheduler, the value source and the
+        # oracle still see one wide layer (head index = layer x heads of a layer + head)
+        layers = [2, 2, 1] if driver == "runner-layers" else [1, 1, 1]
+        per_layer = [wl.ModelShape(s.name, s.n_q_heads // n, s.n_kv_heads // n, d) for s, n in zip(shapes, layers)]
+        engine = eng.NativeEngine(pool, per_layer, max_seqs, max_blocks, budget, src, shared_stream=driver == "runner-one-stream",
+                                  layers=layers, **kw)
     os_ = orc.OracleScheduler(op, [s.n_kv_heads for s in shapes], max_seqs, max_blocks, budget, **kw)
     scale = H.default_scale(d)
     rid, worst, kinds = 0, 0.0, set()
@@ -121,6 +126,7 @@ def test_scheduler_drives_kernels_like_the_oracle(case, driver, monkeypatch):
                 if wj["kind"] != orc.DECODE:
                     continue
                 got_t, want_t = engine.runner.read_table(wj["model"]), os_.table(wj["model"])
+                got_t = got_t.transpose(1, 0, 2, 3).reshape(want_t.shape)       # [layer][slot][head] -> [slot][layer x head]
                 for slot, n in zip(wj["slots"], wj["lens"]):
                     nb = (n + B - 1) // B
                     assert np.array_equal(got_t[slot, :, :nb], want_t[slot, :, :nb])

@@ -60,12 +60,14 @@ def test_runner_argument_errors_need_no_gpu():
     other = host_pool(64)
     import ctypes as C
     h, q = C.c_void_p(), np.array([4], np.int32)
-    assert lib.mux_runner_create(None, lp.handle, ls.handle, q.ctypes.data, None) == mx.MUX_ERR_INVALID
-    assert lib.mux_runner_create(C.byref(h), lp.handle, None, q.ctypes.data, None) == mx.MUX_ERR_INVALID
-    assert lib.mux_runner_create(C.byref(h), lp.handle, ls.handle, None, None) == mx.MUX_ERR_INVALID
-    assert lib.mux_runner_create(C.byref(h), other.handle, ls.handle, q.ctypes.data, None) == mx.MUX_ERR_INVALID   # not the scheduler's pool
+    assert lib.mux_runner_create(None, lp.handle, ls.handle, q.ctypes.data, None, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_runner_create(C.byref(h), lp.handle, None, q.ctypes.data, None, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_runner_create(C.byref(h), lp.handle, ls.handle, None, None, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_runner_create(C.byref(h), other.handle, ls.handle, q.ctypes.data, None, None) == mx.MUX_ERR_INVALID   # not the scheduler's pool
     q[0] = 3                                                                                                       # 3 query heads over 2 KV heads
-    assert lib.mux_runner_create(C.byref(h), lp.handle, ls.handle, q.ctypes.data, None) == mx.MUX_ERR_INVALID
+    assert lib.mux_runner_create(C.byref(h), lp.handle, ls.handle, q.ctypes.data, None, None) == mx.MUX_ERR_INVALID
+    q[0], layers = 4, np.array([3], np.int32)                                                                      # 2 heads do not split into 3 layers
+    assert lib.mux_runner_create(C.byref(h), lp.handle, ls.handle, q.ctypes.data, layers.ctypes.data, None) == mx.MUX_ERR_INVALID
     assert h.value is None
     n = C.c_int32()
     assert lib.mux_runner_step(None, C.byref(n)) == mx.MUX_ERR_INVALID
