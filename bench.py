@@ -406,7 +406,10 @@ def run_adbs(args) -> int:
     rates = np.array([2.0, 8.0, 8.0])
     length_scale = [2, 1, 1]
     S = max(int(args.adbs_scale), 1)                   # pool, slots, arrivals and prefill budget grow together
-    B, d, n_blocks, max_seqs, max_blocks = 16, 128, 40000 * S, min(64 * S, 1024), 96
+    layers = [40, 32, 32] if args.adbs_layers else [1, 1, 1]   # LLaMA-13B / 7B depths: the whole model's K/V
+    if args.adbs_layers and args.adbs_driver == "python":
+        raise SystemExit("--adbs-layers needs the runner (the Python driver handles one layer)")
+    B, d, n_blocks, max_seqs, max_blocks = 16, 128, 40000 * S * (32 if args.adbs_layers else 1), min(64 * S, 1024), 96
     budget = 2048 * S
     iters = max(args.steps, 1) * 8
     warm = max(args.warmup, 1) * 8 * (2 if S > 1 else 1)
@@ -418,7 +421,7 @@ def run_adbs(args) -> int:
         pool = mx.mux_pool_create(kv, n_blocks, B, d, mx.MUX_BF16, wl.placement_order(rng, n_blocks))
         kw = {}
         if mode == "adbs":
-            weights = rates * np.array([s.n_kv_heads for s in shapes])
+            weights = rates * np.array([s.n_kv_heads * n for s, n in zip(shapes, layers)])
             assert mx.mux_pool_init_quotas(pool, weights) == 0
             kw = dict(adapt_period=16, low=0.5, high=0.9, step=0.25)
         if args.adbs_driver == "python":
@@ -426,7 +429,7 @@ def run_adbs(args) -> int:
                                 keep_outputs=False, **kw)
         else:
             engine = eng.NativeEngine(pool, shapes, max_seqs, max_blocks, budget, None,
-                                      shared_stream=args.adbs_driver == "runner-one-stream", **kw)
+                                      shared_stream=args.adbs_driver == "runner-one-stream", layers=layers, **kw)
         use = np.zeros(len(shapes))
         rid, t0, tok0 = 0, None, 0
         for it in range(warm + iters):
@@ -461,7 +464,7 @@ def run_adbs(args) -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16 storage, f32 arithmetic", "data": "synthetic",
         "config": {"workload": "batch scheduler (Algorithm 3) over 13B/7B/7B-shaped models, Poisson arrivals 2:8:8, request "
                                "lengths 2:1:1, %d requests per pass, %d head-blocks, %d slots per model, prefill budget %d tokens; every job "
-                               "launched on the GPU, driver: %s" % (S, n_blocks, max_seqs, budget, args.adbs_driver)},
+                               "launched on the GPU, driver: %s; layers per model: %s" % (S, n_blocks, max_seqs, budget, args.adbs_driver, layers)},
         "rate_share": [round(float(x), 4) for x in rates / rates.sum()],
         "adbs": a, "no_quota": out["no-quota"],
     }
@@ -490,6 +493,8 @@ def main() -> int:
     ap.add_argument("--adbs-driver", choices=["runner", "runner-one-stream", "python"], default="runner",
                     help="who launches the scheduler's jobs: the library's runner (one stream per model, or one for all) "
                          "or the Python driver")
+    ap.add_argument("--adbs-layers", action="store_true",
+                    help="--adbs: models with all their layers (40 / 32 / 32) and a pool 32x as large: whole-model K/V traffic")
     ap.add_argument("--adbs-scale", type=int, default=1,
                     help="--adbs: multiply pool size, sequence slots, arrivals per pass and prefill token budget")
     ap.add_argument("--no-solo", action="store_true", help="skip the per-model solo passes after the timed loop")
