@@ -261,3 +261,20 @@ def test_block_manager_is_safe_from_several_host_threads():
         for a in held[t]:
             assert lib.mux_free_blocks(p.handle, t, a.size, a.ctypes.data) == 0
     assert mx.mux_pool_num_free(p) == n_blocks
+
+
+def test_decode_plan_splits_only_where_whole_rows_cannot_fill_the_gpu():
+    """Host-side span planning, seen through the workspace size (a plan without a split needs only
+    the work list): a few very long rows are split into spans, batches that already hold enough
+    whole rows are not, and contexts longer than one span (4 096 tokens) always are."""
+    p = host_pool(64)
+    lib = mx.load()
+
+    def is_split(n_seqs, hq, hkv, ctx):
+        return lib.mux_decode_workspace_bytes(p.handle, n_seqs, hq, hkv, ctx) > 16 + n_seqs * 8 + 16
+
+    assert is_split(2, 32, 32, 4000) and is_split(1, 8, 1, 4096) and is_split(2, 2, 2, 4000)
+    assert not is_split(8, 32, 32, 2048) and not is_split(64, 32, 32, 2048) and not is_split(16, 32, 32, 512)
+    assert not is_split(128, 64, 8, 2048) and not is_split(50, 64, 8, 512)
+    assert is_split(8, 32, 32, 8192) and is_split(128, 64, 8, 4097)
+    assert not is_split(4096, 32, 32, 16)
