@@ -189,6 +189,9 @@ class PrefillModel:
                 "cu": torch.from_numpy(cu).to(device), "start": torch.from_numpy(done.copy()).to(device),
                 "max_q": int(ql.max()), "max_ctx": int((done + ql).max()), "flops": flops,
                 "kv_bytes": int((done + ql)[ql > 0].astype(np.int64).sum()) * 2 * n_kv * d * 2,
+                # everything the stage moves: K/V prefix reads, Q read + O written, the chunk's K/V rows read and written
+                "all_bytes": int((done + ql)[ql > 0].astype(np.int64).sum()) * 2 * n_kv * d * 2 + 2 * nt * n_q * d * 2
+                             + 2 * 2 * nt * n_kv * d * 2,
             }
             st["out"] = torch.empty_like(st["q"])
             self.stages.append(st)
@@ -199,10 +202,13 @@ class PrefillModel:
         torch.cuda.synchronize()
         self.step_no = 0
         self.events = []
+        self.bytes_moved = 0      # algorithmic bytes of the recorded stages, appends included
 
     def step(self, record: bool):
         st = self.stages[self.step_no % len(self.stages)]
         self.step_no += 1
+        if record:
+            self.bytes_moved += st["all_bytes"]
         with torch.cuda.stream(self.stream):
             mx.mux_kv_append(self.pool, st["k"], st["v"], st["seq"], st["pos"], self.tables_dev, stream=self.stream)
             e0, e1 = torch.cuda.Event(enable_timing=record), torch.cuda.Event(enable_timing=record)
@@ -653,6 +659,9 @@ def main() -> int:
             "bound": "mfma", "peak_tflops": 2500.0, "frac": fl / t / 2.5e15, "avg_launch_ms": t / len(ev) * 1e3,
             "flops_per_launch": fl / len(ev), "kv_bytes_per_launch": sum(b for _, _, _, b in ev) / len(ev),
         }
+        if roofline is not None:
+            # what the memory system carried in the timed loop: the decode models' K/V plus what the prefill stages move
+            result["all_streams_GBps"] = (kv_bytes + sum(pm.bytes_moved for pm in prefills)) / dt / 1e9
         if roofline is None:   # prefill only: the MFMA-bound kernel is the dominant one
             result["metric"], result["unit"], result["value"] = "prefill-attn causal TFLOP/s (% of MFMA peak)", "TFLOP/s", fl / t / 1e12
             result["dtype"] = "bf16 MFMA, f32 accumulate"
