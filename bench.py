@@ -467,7 +467,7 @@ def run_adbs(args) -> int:
     line = {
         "metric": "ADBS-scheduled serving: output tokens/s, attention path only", "value": a["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": iters, "warmup": warm, "ms_per_step": a["ms_per_iteration"], "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 storage, f32 arithmetic", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "storage_dtype": "bf16", "data": "synthetic",
         "config": {"workload": "batch scheduler (Algorithm 3) over 13B/7B/7B-shaped models, Poisson arrivals 2:8:8, request "
                                "lengths 2:1:1, %d requests per pass, %d head-blocks, %d slots per model, prefill budget %d tokens; every job "
                                "launched on the GPU, driver: %s; layers per model: %s" % (S, n_blocks, max_seqs, budget, args.adbs_driver, layers)},
@@ -634,7 +634,7 @@ def main() -> int:
         "metric": "decode-attn KV GB/s (% of HBM peak) + tokens/s, multi-LLM mixed batch",
         "value": kv_bytes / dt / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 storage, f32 arithmetic", "data": "synthetic",
+        "dtype": "f32", "storage_dtype": "bf16", "data": "synthetic",
         "config": {
             "workload": "config %d: %s; block_size %d; %d head-blocks, seeded random placement; per step and model: "
                         "alloc -> table patch -> %s, one stream per model, decode kernels %s"
@@ -664,7 +664,7 @@ def main() -> int:
             result["all_streams_GBps"] = (kv_bytes + sum(pm.bytes_moved for pm in prefills)) / dt / 1e9
         if roofline is None:   # prefill only: the MFMA-bound kernel is the dominant one
             result["metric"], result["unit"], result["value"] = "prefill-attn causal TFLOP/s (% of MFMA peak)", "TFLOP/s", fl / t / 1e12
-            result["dtype"] = "bf16 MFMA, f32 accumulate"
+            result["dtype"] = "bf16"   # matrix products in bf16, accumulation in f32
             result["roofline"] = {"kernel": "prefill_attn_kernel", "bound": "mfma", "achieved": fl / t / 1e12, "peak": 2500.0,
                                   "unit": "TFLOP/s", "frac": fl / t / 2.5e15, "traffic": None}
     if solo:
