@@ -218,6 +218,18 @@ def test_max_ctx_hint_larger_than_needed_changes_nothing():
     H.assert_close(loose, want, "bf16")
 
 
+@pytest.mark.parametrize("hint", [1, 64, 100, 1000])
+def test_max_ctx_hint_smaller_than_a_context_cuts_it_there(hint):
+    """Tokens beyond max_ctx_len are ignored (the header says so): the result is the attention over the
+    first max_ctx_len tokens of the longer sequences, and nothing is read past the hint."""
+    _say("decode with max_ctx_len %d below some contexts" % hint)
+    lens = [300, 40, 100, 0, 1500]
+    ls, job, q, _, _ = _decode_case("bf16", 128, 16, 8, 2, lens, seed=78)
+    got = H.decode_gpu(ls, job, q, H.default_scale(128), max_ctx_len=hint)
+    want = H.decode_oracle(ls, job, q, H.default_scale(128), ctx_lens=np.minimum(job.lens, hint))
+    H.assert_close(got, want, "bf16")
+
+
 @pytest.mark.parametrize("idx", [2, 3, 5])
 def test_small_decode_configs_every_output(idx):
     """Shrunk versions of configurations 2, 3 and 5 (same models, fewer and shorter sequences)
