@@ -53,14 +53,33 @@ def build(verbose: bool = True) -> str:
     os.replace(tmp, OUT)
     if verbose:
         print("built", OUT)
+    build_demo(verbose)
     return OUT
+
+
+DEMO_SRC = os.path.join(PKG, "examples", "c_abi_demo.cpp")
+DEMO = os.path.join(PKG, "examples", "c_abi_demo")
+
+
+def build_demo(verbose: bool = True) -> str:
+    """A small host program that uses the library through include/mux.h alone (run by the GPU tests)."""
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wall", "-I" + os.path.join(ROOT, "include"), DEMO_SRC,
+           "-o", DEMO, "-L" + PKG, "-lmux", "-Wl,-rpath,$ORIGIN/.."]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for the C ABI demo:\n%s" % r.stderr)
+    if verbose:
+        print("built", DEMO)
+    return DEMO
 
 
 def is_stale() -> bool:
     if not os.path.exists(OUT):
         return True
     t = os.path.getmtime(OUT)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "mux.h")]
+    if not os.path.exists(DEMO):
+        return True
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "mux.h"), DEMO_SRC]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
