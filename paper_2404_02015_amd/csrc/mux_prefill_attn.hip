@@ -421,22 +421,40 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
         if (step + 2 < n_steps) run_step(step + 2, std::integral_constant<int, 2>{});
     }
 
-    wait_vmem<0>();   // the clamped copies issued past the last step must land before the LDS is given back
+    wait_vmem<0>();   // the clamped copies issued past the last step must land before the LDS is reused
+    raw_barrier();    // every wave is done with the tile buffers: from here on they carry the outputs
     if (!wave_active) return;
+    // The accumulators hold O^T: a lane owns 4 dims of one row per slab, i.e. 8-byte pieces spread
+    // over 16 rows per instruction.  Written to memory like that, the stores reach only ~3 TB/s
+    // (measured: they cost more than the kernel's whole K/V traffic on short prompts).  Each wave
+    // therefore turns its RS x D block around in LDS (row stride padded by 16 bytes: conflict-free
+    // both ways) and stores whole rows, 16 bytes per lane, 1 KiB of consecutive rows per instruction.
+    constexpr int OSTR = ROWB + 16;
+    static_assert(kWaves * RS * OSTR <= kBufs * (KBUF + VBUF), "the output blocks must fit the tile buffers");
+    char *oblk = smem + wave * (RS * OSTR);
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
         const float l_tot = l_acc[b][0];
-        const int r = my_row0 + 16 * b + c;
-        if (r >= q_len) continue;                // surplus row of a ragged tile
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-        char *orow = static_cast<char *>(a.out) + (static_cast<long long>(q_lo + r) * a.n_q_heads + head) * (D * 2);
+        char *orow = oblk + (16 * b + c) * OSTR + 8 * g;
 #pragma unroll
         for (int n = 0; n < NT; ++n) {
             u32x2 o;
             o[0] = pack_bf16(acc[b][n][0] * inv, acc[b][n][1] * inv);
             o[1] = pack_bf16(acc[b][n][2] * inv, acc[b][n][3] * inv);
-            *reinterpret_cast<u32x2 *>(orow + (16 * n + 4 * g) * 2) = o;   // dims 16n+4g .. +3 of this row
+            *reinterpret_cast<u32x2 *>(orow + 32 * n) = o;   // dims 16n+4g .. +3 of this row
         }
+    }
+    // LDS operations of one wave complete in order: the reads below see all lanes' writes above
+    constexpr int RPI = 1024 / ROWB;             // rows per store instruction
+#pragma unroll
+    for (int i = 0; i < RS / RPI; ++i) {
+        const int row = i * RPI + lane / PPR, piece = lane % PPR;
+        const int r = my_row0 + row;
+        const u32x4 val = *reinterpret_cast<const u32x4 *>(oblk + row * OSTR + piece * 16);
+        if (r < q_len)                           // surplus rows of a ragged tile are dropped
+            *reinterpret_cast<u32x4 *>(static_cast<char *>(a.out) + (static_cast<long long>(q_lo + r) * a.n_q_heads + head) * ROWB +
+                                       piece * 16) = val;
     }
 }
 
