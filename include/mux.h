@@ -206,9 +206,9 @@ MUX_API size_t mux_decode_step_workspace_bytes(const mux_pool_t *pool, int32_t n
  * q_start: DEVICE int32 [n_seqs], tokens cached before this chunk.  max_q_len,
  * max_ctx_len: HOST upper bounds on the chunk lengths and on q_start + chunk length.
  * workspace: DEVICE scratch of at least mux_prefill_workspace_bytes(...) bytes, 16-byte
- * aligned; that function returns 0 (workspace may be NULL) for bf16 pools with 16-token
- * blocks, which run on the matrix cores; other pools take a slow generic path that may
- * need scratch for long contexts.
+ * aligned; that function returns 0 (workspace may be NULL) for bf16 pools whose blocks hold
+ * a power of two >= 8 tokens, which run on the matrix cores; other pools take a slow generic
+ * path that may need scratch for long contexts.
  * ------------------------------------------------------------------------------- */
 MUX_API int mux_prefill_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *cu_q_lens,
                      const int32_t *q_start, const int32_t *block_tables, int32_t n_seqs,

@@ -48,8 +48,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
-constexpr int kBS = 16;              // tokens per block on this path
-constexpr int kKT = 32;              // tokens per pipeline step (two blocks)
+constexpr int kBS = 16;              // tokens per block of the instantiations with the block size built in
+constexpr int kKT = 32;              // tokens per pipeline step (two blocks of 16)
 constexpr int kMaxCachedIds = 1024;  // block ids kept in LDS (16 384 tokens of context)
 #ifndef MUX_PREFILL_BUFS
 #define MUX_PREFILL_BUFS 3
@@ -73,6 +73,7 @@ struct PrefillArgs {
     int n_row_tiles;   // ceil(max_q_len / rows per workgroup)
     int n_passes;      // head passes per kv head
     int tile_bundle;   // row tiles of one unit dispatched back to back (see the kernel's blockIdx mapping)
+    int log2_block;    // log2(tokens per block), for the instantiations that take the block size at run time
     float scale_log2e;
 };
 
@@ -148,13 +149,17 @@ __device__ __forceinline__ void wait_vmem()   // at most N vector-memory operati
 __device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8)); }
 
 // D: head size.  HT: query heads per workgroup (1, 2 or 4); the other kWaves / HT waves take
-// further row slices.  CB: 16-row column blocks per wave.
+// further row slices.  CB: 16-row column blocks per wave.  B16: blocks of 16 tokens (every
+// configuration of the paper's workloads), block arithmetic folded at compile time; otherwise the
+// block size is a run-time power of two >= 8 (a wave's 8-token run of a tile copy must lie in one block).
 #ifndef MUX_PREFILL_MIN_WGS
 #define MUX_PREFILL_MIN_WGS 2
 #endif
-template <int D, int HT, int CB>
+template <int D, int HT, int CB, bool B16>
 __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_kernel(const PrefillArgs a)
 {
+    const int lb = B16 ? 4 : a.log2_block;       // log2(tokens per block)
+    const int BS = 1 << lb;
     constexpr int RS = 16 * CB;                  // query rows per wave
     constexpr int RT = kWaves / HT;              // row slices per workgroup
     constexpr int QT = RS * RT;                  // query rows per workgroup
@@ -214,7 +219,7 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
     if (q_lo < 0 || row0 >= q_len || start < 0) return;
     const int rows_here = min(QT, q_len - row0);
     int kv_end = start + row0 + rows_here;       // keys 0 .. kv_end-1 are visible to the last row
-    kv_end = min(kv_end, a.max_blocks * kBS);
+    kv_end = min(kv_end, a.max_blocks * BS);
     const int n_steps = (kv_end + kKT - 1) / kKT;
     if (n_steps <= 0) return;
     const int total_len = start + q_len;         // tokens of this sequence that hold real K/V
@@ -260,7 +265,7 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
     // Block ids of the whole key range go to LDS once, so that the K/V loads inside the loop
     // do not wait for a table load first (contexts past kMaxCachedIds blocks read the table).
     const int *trow = a.tables + (static_cast<long long>(s) * a.n_kv_heads + kvh) * a.max_blocks;
-    const int n_ids = min(min(2 * n_steps, a.max_blocks), kMaxCachedIds);
+    const int n_ids = min(min((n_steps * kKT + BS - 1) >> lb, a.max_blocks), kMaxCachedIds);
     for (int i = tid; i < n_ids; i += kThreads) sm_ids[i] = min(max(trow[i], 0), a.num_blocks - 1);
     __syncthreads();
 
@@ -272,36 +277,46 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
     // The step index is clamped so that every iteration issues the same number of loads and the
     // wait counts below stay exact.
     constexpr int TPR = 64 / PPR;                        // tokens per 1 KiB run
-    static_assert(kBS % (PPT * TPR) == 0, "the runs of a wave must not straddle blocks");
-    const int my_blk = wave * PPT * TPR / kBS;           // which of the step's two blocks this wave copies
+    constexpr int WT = PPT * TPR;                        // tokens of a tile that one wave copies
+    static_assert(kBS % WT == 0 && WT == 8, "the runs of a wave must not straddle blocks");
+    const int wave_tok0 = wave * WT;                     // first token of the tile this wave copies
     unsigned koff[PPT], voff[PPT];
 #pragma unroll
     for (int p = 0; p < PPT; ++p) {
         const int slot = (wave * PPT + p) * 64 + lane;   // 16-byte slot inside the tile
         const int tok = slot / PPR, pos = slot % PPR;
-        koff[p] = (tok % kBS) * ROWB + (pos ^ kswz(tok)) * 16;
-        voff[p] = kBS * ROWB + (tok % kBS) * ROWB + (pos ^ vswz(tok)) * 16;
+        // with 16-token blocks the row inside the block is the same in every step and part of the
+        // lane's offset; otherwise it goes into the wave-uniform base (see issue)
+        const int row = B16 ? tok % kBS : tok - wave_tok0;
+        koff[p] = row * ROWB + (pos ^ kswz(tok)) * 16;
+        voff[p] = (B16 ? kBS * ROWB : 0) + row * ROWB + (pos ^ vswz(tok)) * 16;
     }
     auto block_id = [&](int step_raw) {                  // id of this wave's block in a step (same in all lanes)
-        const int blk = min(step_raw, n_steps - 1) * 2 + my_blk;
+        const int blk = (min(step_raw, n_steps - 1) * kKT + wave_tok0) >> lb;
         if (blk < n_ids) return sm_ids[blk];
         return blk < a.max_blocks ? min(max(trow[blk], 0), a.num_blocks - 1) : 0;   // a stale or corrupt entry must not leave the pool
     };
-    auto issue = [&](int id, int buf) {
+    auto issue = [&](int id, int step_raw, int buf) {
         const char *base = a.kv_base + static_cast<long long>(__builtin_amdgcn_readfirstlane(id)) * a.block_bytes;
+        const char *vbase = base;
+        if constexpr (!B16) {
+            const int row0 = (min(step_raw, n_steps - 1) * kKT + wave_tok0) & (BS - 1);   // first row of the wave's run in its block
+            base += row0 * ROWB;
+            vbase = base + BS * ROWB;
+        }
         const unsigned kb = smem_lds + buf * (KBUF + VBUF);
         const unsigned vb = kb + KBUF;
 #pragma unroll
         for (int p = 0; p < PPT; ++p) {
             const int run = wave * PPT + p;              // which 1 KiB run of the tile
             lds_dma16(base, koff[p], kb + run * 1024);
-            lds_dma16(base, voff[p], vb + run * 1024);
+            lds_dma16(vbase, voff[p], vb + run * 1024);
         }
     };
     constexpr int LPS = 2 * PPT;                         // copies per step per lane
 
     wait_vmem<0>();   // q rows and table entries have arrived: from here on only tile copies are in flight
-    for (int t = 0; t < kBufs - 1; ++t) issue(block_id(t), t);
+    for (int t = 0; t < kBufs - 1; ++t) issue(block_id(t), t, t);
     int next_id = block_id(kBufs - 1);   // fetched one iteration ahead of its use
     // Per-lane LDS addresses of the operand reads inside tile 0 (they never change): K piece of
     // slab k in row c (the second 16-token half sits 16 rows further), V piece pair of slab n in
@@ -327,7 +342,7 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
         // this wave's copies for `step` have landed once only the younger steps' copies are in flight
         wait_vmem<(kBufs - 2) * LPS>();
         raw_barrier();     // everyone's copies for `step` are in LDS, and everyone is done with step - 1 ...
-        issue(next_id, (buf + kBufs - 1) % kBufs);             // ... so its buffer can be refilled
+        issue(next_id, step + kBufs - 1, (buf + kBufs - 1) % kBufs);   // ... so its buffer can be refilled
         next_id = block_id(step + kBufs);
         const int kv0 = step * kKT;
         if (kv0 + kKT > total_len) {
@@ -458,7 +473,7 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
     }
 }
 
-template <int D, int HT, int CB>
+template <int D, int HT, int CB, bool B16>
 void launch_mfma(PrefillArgs a, int max_q_len, hipStream_t st)
 {
     constexpr int QT = 16 * CB * (kWaves / HT);
@@ -471,21 +486,30 @@ void launch_mfma(PrefillArgs a, int max_q_len, hipStream_t st)
     const long long bundles = (a.n_row_tiles + a.tile_bundle - 1) / a.tile_bundle;
     const long long grid = (units + 7) / 8 * 8 * bundles * a.tile_bundle;   // see the blockIdx mapping in the kernel
     constexpr int kLds = kBufs * 2 * kKT * D * 2 + kMaxCachedIds * 4;
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_attn_kernel<D, HT, CB>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_attn_kernel<D, HT, CB, B16>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     (void)attr;   // more than 64 KiB of LDS per workgroup has to be granted once per kernel
-    hipLaunchKernelGGL((prefill_attn_kernel<D, HT, CB>), dim3(static_cast<unsigned>(grid)), dim3(kThreads), kLds, st, a);
+    hipLaunchKernelGGL((prefill_attn_kernel<D, HT, CB, B16>), dim3(static_cast<unsigned>(grid)), dim3(kThreads), kLds, st, a);
+}
+
+template <int D, int CB, bool B16>
+void launch_by_heads2(int ht, const PrefillArgs &a, int max_q_len, hipStream_t st)
+{
+    if (ht == 4)
+        launch_mfma<D, 4, CB, B16>(a, max_q_len, st);
+    else if (ht == 2)
+        launch_mfma<D, 2, CB, B16>(a, max_q_len, st);
+    else
+        launch_mfma<D, 1, CB, B16>(a, max_q_len, st);
 }
 
 template <int D, int CB>
 void launch_by_heads(int ht, const PrefillArgs &a, int max_q_len, hipStream_t st)
 {
-    if (ht == 4)
-        launch_mfma<D, 4, CB>(a, max_q_len, st);
-    else if (ht == 2)
-        launch_mfma<D, 2, CB>(a, max_q_len, st);
+    if (a.log2_block == 4)
+        launch_by_heads2<D, CB, true>(ht, a, max_q_len, st);
     else
-        launch_mfma<D, 1, CB>(a, max_q_len, st);
+        launch_by_heads2<D, CB, false>(ht, a, max_q_len, st);
 }
 
 }  // namespace
@@ -496,7 +520,12 @@ int mux_launch_prefill_rows_as_decode(const mux_pool *pool, void *out, const voi
                                       int32_t max_ctx_len, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks,
                                       float scale, void *workspace, void *stream);
 
-bool mux_prefill_uses_mfma(const mux_pool *pool) { return pool->dtype == MUX_BF16 && pool->block_size == kBS; }
+// bf16 pools whose blocks hold a power of two >= 8 tokens run on the matrix cores
+bool mux_prefill_uses_mfma(const mux_pool *pool)
+{
+    const int b = pool->block_size;
+    return pool->dtype == MUX_BF16 && b >= 8 && (b & (b - 1)) == 0;
+}
 
 int mux_launch_prefill_attn(const mux_pool *pool, void *out, const void *q, const int32_t *cu_q_lens,
                             const int32_t *q_start, const int32_t *tables, int32_t n_seqs, int32_t total_q,
@@ -521,6 +550,8 @@ int mux_launch_prefill_attn(const mux_pool *pool, void *out, const void *q, cons
     a.n_kv_heads = n_kv_heads;
     a.max_blocks = max_blocks;
     a.scale_log2e = scale * kLog2e;
+    for (a.log2_block = 0; (1 << a.log2_block) < pool->block_size; ++a.log2_block) {
+    }
     const int group = n_q_heads / n_kv_heads;
     const int ht = group >= 4 ? 4 : (group >= 2 ? 2 : 1);
     // Two column blocks per wave (each K / V operand read feeds two matrix instructions) once the

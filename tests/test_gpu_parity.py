@@ -289,6 +289,9 @@ def _prefill_case(dtype, head_dim, block_size, n_q, n_kv, lens, q_starts, seed, 
     ("bf16", 128, 16, 2, 2), ("bf16", 128, 16, 4, 2), ("bf16", 128, 16, 8, 2), ("bf16", 128, 16, 16, 2),
     ("bf16", 128, 16, 6, 2), ("bf16", 128, 16, 5, 1), ("bf16", 64, 16, 4, 4), ("bf16", 64, 16, 8, 1),
     ("fp32", 128, 16, 2, 2), ("fp32", 64, 8, 4, 2), ("bf16", 128, 8, 2, 2), ("bf16", 64, 32, 2, 1),
+    # other block sizes on the matrix-core path (powers of two from 8 on) and off it (4, 24)
+    ("bf16", 128, 32, 4, 2), ("bf16", 128, 64, 8, 1), ("bf16", 128, 128, 2, 2), ("bf16", 64, 8, 4, 4), ("bf16", 64, 64, 2, 2),
+    ("bf16", 128, 4, 2, 2), ("bf16", 128, 24, 2, 1),
 ])
 def test_prefill_matches_oracle_across_shapes(dtype, head_dim, block_size, n_q, n_kv):
     # fresh prompts and later chunks; lengths around tile (16/32/64) and block boundaries; a 1-row chunk
@@ -306,14 +309,14 @@ def test_prefill_matches_oracle_across_shapes(dtype, head_dim, block_size, n_q, 
     print("max abs err %.2e" % err)
 
 
-@pytest.mark.parametrize("chunk", [1, 7, 16, 33, 64, 100])
-def test_chunked_prefill_equals_oracle_and_unchunked(chunk):
+@pytest.mark.parametrize("chunk,block_size", [(1, 16), (7, 16), (16, 16), (33, 16), (64, 16), (100, 16), (33, 8), (50, 32), (40, 64)])
+def test_chunked_prefill_equals_oracle_and_unchunked(chunk, block_size):
     """Prompts processed in chunks of any size (alloc -> append -> attend per chunk) give the
     rows an unchunked pass gives."""
     lens = np.array([19, 150, 77], dtype=np.int32)
     n_q, n_kv, d = 4, 2, 128
     rng = np.random.Generator(np.random.PCG64(5))
-    ls = H.Lockstep(512, 16, d, "bf16", wl.placement_order(rng, 512))
+    ls = H.Lockstep(512, block_size, d, "bf16", wl.placement_order(rng, 512))
     job = H.open_job(ls, 0, wl.ModelShape("t", n_q, n_kv, d), 3, 160)
     q_all = wl.randn_values(55, (int(lens.sum()), n_q, d)).cuda()
     cu_all = np.concatenate([[0], np.cumsum(lens)])
