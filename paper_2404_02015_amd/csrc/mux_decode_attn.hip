@@ -515,29 +515,45 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
         }
     } else {
         const long long tile_bytes = static_cast<long long>(B) * D * EB;
-        for (int j = 0; j < n_mine; ++j) {
-            const char *t = tile_ptr(j);
-            const int first_tok = (blk_lo + wave + kWaves * j) * B;
-            const int rows_here = min(B, L - first_tok);
-            for (int r0 = 0; r0 < rows_here; r0 += RPL) {
-                u32x4 k[1], v[1];
-                k[0] = u32x4{0, 0, 0, 0};
-                v[0] = u32x4{0, 0, 0, 0};
-                if (r0 + rg < rows_here) {  // never read past the tile
-                    const char *src = t + static_cast<long long>(r0) * (D * EB) + lane * 16;
-                    k[0] = *reinterpret_cast<const u32x4 *>(src);
-                    v[0] = *reinterpret_cast<const u32x4 *>(src + tile_bytes);
-                    if (a.k_new != nullptr && first_tok + r0 + rg == L - 1) {  // the token a fused step appends
-                        const long long nsrc = ((static_cast<long long>(s) * a.n_kv_heads + kvh) * D + c0) * EB;
-                        k[0] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.k_new) + nsrc);
-                        v[0] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.v_new) + nsrc);
-                        if (pass == 0) {
-                            *reinterpret_cast<u32x4 *>(const_cast<char *>(src)) = k[0];
-                            *reinterpret_cast<u32x4 *>(const_cast<char *>(src) + tile_bytes) = v[0];
-                        }
+        // The wave's blocks, RPL rows at a time.  The loads of the next group are issued before
+        // the current one is folded in; lanes past a block's rows load its last row again (the
+        // fold ignores them), so the loads are unconditional and the waits cover one group only.
+        auto rows_of = [&](int j) { return min(B, L - (blk_lo + wave + kWaves * j) * B); };
+        auto load_group = [&](int j, int r0, int rows_here, u32x4 &k, u32x4 &v) {
+            const int r = min(r0 + rg, rows_here - 1);
+            char *src = const_cast<char *>(tile_ptr(j)) + static_cast<long long>(r) * (D * EB) + (lane % LPR) * 16;
+            k = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+            v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + tile_bytes));
+            const int tok0 = (blk_lo + wave + kWaves * j) * B + r0;   // first token of the group (same in all lanes)
+            if (a.k_new != nullptr && tok0 <= L - 1 && L - 1 < tok0 + min(RPL, rows_here - r0)) {
+                if (tok0 + rg == L - 1) {   // the token a fused step appends (a row of this block: see the check above)
+                    const long long nsrc = ((static_cast<long long>(s) * a.n_kv_heads + kvh) * D + c0) * EB;
+                    k = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.k_new) + nsrc);
+                    v = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.v_new) + nsrc);
+                    if (pass == 0) {
+                        *reinterpret_cast<u32x4 *>(src) = k;
+                        *reinterpret_cast<u32x4 *>(src + tile_bytes) = v;
                     }
                 }
-                fold(k, v, std::true_type{}, rows_here - r0);
+            }
+        };
+        if (n_mine > 0) {
+            int j = 0, r0 = 0, rows_here = rows_of(0);
+            u32x4 kc[1], vc[1], kn[1], vn[1];
+            load_group(0, 0, rows_here, kc[0], vc[0]);
+            for (;;) {
+                int nj = j, nr0 = r0 + RPL, nrows = rows_here;
+                if (nr0 >= rows_here) {
+                    nj = j + 1;
+                    nr0 = 0;
+                    nrows = nj < n_mine ? rows_of(nj) : 0;
+                }
+                const bool more = nj < n_mine;
+                if (more) load_group(nj, nr0, nrows, kn[0], vn[0]);
+                fold(kc, vc, std::true_type{}, rows_here - r0);
+                if (!more) break;
+                kc[0] = kn[0], vc[0] = vn[0];
+                j = nj, r0 = nr0, rows_here = nrows;
             }
         }
     }
