@@ -337,8 +337,12 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     constexpr int RPL = 64 / LPR;         // rows per load instruction
     static_assert(LPR >= 4 && LPR <= 32, "unsupported head size");
     constexpr bool kFixed = BS > 0;
-    static_assert(!kFixed || BS % RPL == 0, "fixed block size must hold whole load groups");
-    constexpr int NG = kFixed ? BS / RPL : 1;  // loads per tile handled at once
+    // A block of a compile-time size is consumed in sub-tiles of 16 tokens (one sub-tile for
+    // the 16-token blocks of the paper's workloads): the registers of a wave hold two of them.
+    constexpr int TB = 16;                     // tokens per sub-tile
+    constexpr int SUBS = kFixed ? BS / TB : 1;   // sub-tiles per block
+    static_assert(!kFixed || (BS % TB == 0 && TB % RPL == 0), "fixed block size must hold whole sub-tiles of whole load groups");
+    constexpr int NG = kFixed ? TB / RPL : 1;  // loads per sub-tile, handled at once
 
     const int B = kFixed ? BS : a.block_size;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -454,7 +458,9 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
         }
     };
 
-    if constexpr (kFixed) {
+    if constexpr (kFixed && SUBS == 1) {
+        // blocks of 16 tokens: one sub-tile per block (kept apart from the general case below so that its code,
+        // the one every measured configuration runs, does not depend on it)
         constexpr int kTileBytes = BS * D * EB;
         auto load_tile = [&](int j, u32x4 (&k)[NG], u32x4 (&v)[NG]) {
             const char *t = tile_ptr(j) + static_cast<unsigned>(lane * 16);
@@ -506,6 +512,72 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
                 consume_full(kb, vb);
             }
             if (j + 1 < n_mine) {
+                load_tile(j + 1, kb, vb);
+                consume_full(ka, va);
+                consume_last(j + 1, kb, vb);
+            } else {
+                consume_last(j, ka, va);
+            }
+        }
+    } else if constexpr (kFixed) {
+        constexpr int kTileBytes = BS * D * EB;      // K tile of a block; its V tile follows
+        constexpr int kSubBytes = TB * D * EB;
+        // sub-tile jj of the wave: sub-tile jj % SUBS of its block jj / SUBS
+        auto sub_ptr = [&](int jj) { return tile_ptr(jj / SUBS) + (jj % SUBS) * kSubBytes; };
+        auto load_tile = [&](int jj, u32x4 (&k)[NG], u32x4 (&v)[NG]) {
+            const char *t = sub_ptr(jj) + static_cast<unsigned>(lane * 16);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) k[g] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(t + g * 1024));
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+                v[g] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(t + kTileBytes + g * 1024));
+        };
+        // Every sub-tile but the wave's last one is full, so only the last may need masking; it is
+        // also the only one that can hold the token a fused step appends.
+        auto consume_full = [&](const u32x4 (&k)[NG], const u32x4 (&v)[NG]) { fold(k, v, std::false_type{}, TB); };
+        auto consume_last = [&](int jj, u32x4 (&k)[NG], u32x4 (&v)[NG]) {
+            const int blk = blk_lo + wave + kWaves * (jj / SUBS);
+            const int n_valid = L - blk * BS - (jj % SUBS) * TB;  // wave-uniform, >= 1
+            if (a.k_new != nullptr && blk == n_blk_seq - 1) {
+                // the new token's row: take it from k_new / v_new, and let pass 0 store it in the pool
+                const int r = n_valid - 1;
+                char *tile = const_cast<char *>(sub_ptr(jj));
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+                    if (g * RPL + rg == r) {
+                        const long long src = ((static_cast<long long>(s) * a.n_kv_heads + kvh) * D + c0) * EB;
+                        k[g] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.k_new) + src);
+                        v[g] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.v_new) + src);
+                        if (pass == 0) {
+                            char *dst = tile + static_cast<long long>(r) * (D * EB) + c0 * EB;
+                            *reinterpret_cast<u32x4 *>(dst) = k[g];
+                            *reinterpret_cast<u32x4 *>(dst + kTileBytes) = v[g];
+                        }
+                    }
+            }
+            if (n_valid >= TB)
+                fold(k, v, std::false_type{}, TB);
+            else
+                fold(k, v, std::true_type{}, n_valid);
+        };
+        // sub-tiles of this wave: all of its blocks but the last, and of that one those that hold tokens
+        const int n_sub = n_mine > 0
+                              ? (n_mine - 1) * SUBS + (min(BS, L - (blk_lo + wave + kWaves * (n_mine - 1)) * BS) + TB - 1) / TB
+                              : 0;
+        // Two register sets alternate; the loads of the next sub-tile are always issued before
+        // the current one is consumed, and unconditionally inside the loop so that the wait
+        // counters only cover the sub-tile being consumed.
+        if (n_sub > 0) {
+            u32x4 ka[NG], va[NG], kb[NG], vb[NG];
+            load_tile(0, ka, va);
+            int j = 0;
+            for (; j + 2 < n_sub; j += 2) {
+                load_tile(j + 1, kb, vb);
+                consume_full(ka, va);
+                load_tile(j + 2, ka, va);
+                consume_full(kb, vb);
+            }
+            if (j + 1 < n_sub) {
                 load_tile(j + 1, kb, vb);
                 consume_full(ka, va);
                 consume_last(j + 1, kb, vb);
@@ -872,7 +944,11 @@ AttnKernel kernel_by_heads(int gt)
 template <bool BF16, int D>
 AttnKernel kernel_by_block(int block_size, int gt)
 {
-    return block_size == 16 ? kernel_by_heads<BF16, D, 16>(gt) : kernel_by_heads<BF16, D, 0>(gt);
+    // the block sizes serving systems use get the unrolled, prefetching tile loop; the rest the run-time one
+    if (block_size == 16) return kernel_by_heads<BF16, D, 16>(gt);
+    if (BF16 && block_size == 32) return kernel_by_heads<BF16, D, 32>(gt);
+    if (BF16 && block_size == 64) return kernel_by_heads<BF16, D, 64>(gt);
+    return kernel_by_heads<BF16, D, 0>(gt);
 }
 
 // The matrix-core kernel covers bf16 pools with 16-token blocks and groups of >= 4 query heads.

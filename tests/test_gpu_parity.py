@@ -126,6 +126,7 @@ def test_config1_two_models_share_one_pool(dtype):
     ("bf16", 128, 16, 32, 2), ("bf16", 64, 16, 4, 4), ("bf16", 64, 16, 8, 1),
     ("fp32", 128, 16, 4, 2), ("fp32", 64, 16, 3, 3),
     ("bf16", 128, 1, 2, 2), ("bf16", 128, 8, 4, 2), ("bf16", 128, 32, 2, 2), ("bf16", 64, 8, 2, 1),
+    ("bf16", 128, 64, 4, 4), ("bf16", 128, 32, 8, 1), ("bf16", 64, 64, 4, 2), ("bf16", 64, 32, 16, 2), ("bf16", 128, 128, 2, 2),
     ("fp32", 128, 8, 2, 2), ("fp32", 64, 1, 2, 2), ("bf16", 128, 24, 2, 2),
 ])
 def test_decode_matches_oracle_across_shapes(dtype, head_dim, block_size, n_q, n_kv):
@@ -419,6 +420,7 @@ def test_small_config4_prefill_and_decode_share_the_pool():
     ("bf16", 128, 16, 4, 4, 1), ("bf16", 128, 16, 4, 4, 3), ("bf16", 128, 16, 16, 2, 2), ("bf16", 128, 16, 40, 1, 2),
     ("bf16", 128, 16, 6, 2, 2), ("bf16", 64, 16, 8, 2, 2), ("fp32", 128, 16, 2, 2, 2), ("bf16", 128, 8, 4, 2, 2),
     ("fp32", 64, 1, 2, 1, 2), ("bf16", 128, 16, 36, 2, 1),
+    ("bf16", 128, 32, 4, 2, 2), ("bf16", 128, 64, 4, 4, 2), ("bf16", 64, 32, 8, 1, 1), ("bf16", 128, 24, 2, 2, 2),
 ])
 def test_fused_step_equals_append_then_decode(dtype, head_dim, block_size, n_q, n_kv, n_layers):
     """mux_decode_step must leave the pool bit-identical to mux_kv_append (checked against the
