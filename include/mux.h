@@ -328,6 +328,12 @@ MUX_API int mux_sched_counts(const mux_sched_t *sched, int32_t model, int64_t *c
  *   L > 1) are zeroed.  One launch for all layers (mux_decode_step).
  *   Preempt jobs launch nothing.  The buffers must stay untouched until the work has finished
  *   on the model's stream.  Jobs of one step are launched in job order, each at most once.
+ * mux_runner_launch_layer: the same for ONE layer of the job's model, for engines that run
+ *   attention layer by layer between their other kernels: k_new, v_new, q, out are that
+ *   layer's slices ([T] or [R] rows, shapes as above without the layer dimension).  Layer 0
+ *   of a job comes first (it stages the job's arrays and installs its block ids); the other
+ *   layers of the same job follow in any order, before layer 0 of the model's next job.
+ *   A layer launched twice appends its rows twice (same bytes) and is otherwise harmless.
  * mux_runner_set_buffers / mux_runner_run_step: for engines that keep their Q/K/V/output in
  *   fixed buffers (shapes as for mux_runner_launch: the decode set for max_seqs rows; the
  *   prefill set large enough for the largest prefill job, max(max_prefill_tokens, max_blocks x
@@ -352,6 +358,8 @@ MUX_API int mux_runner_destroy(mux_runner_t *runner);
 MUX_API int mux_runner_step(mux_runner_t *runner, int32_t *n_jobs);
 MUX_API int mux_runner_launch(mux_runner_t *runner, int32_t job, void *out, const void *q, const void *k_new,
                               const void *v_new, float scale);
+MUX_API int mux_runner_launch_layer(mux_runner_t *runner, int32_t job, int32_t layer, void *out, const void *q,
+                                    const void *k_new, const void *v_new, float scale);
 MUX_API int mux_runner_set_buffers(mux_runner_t *runner, int32_t model, void *prefill_out, const void *prefill_q,
                                    const void *prefill_k, const void *prefill_v, void *decode_out, const void *decode_q,
                                    const void *decode_k, const void *decode_v, float scale);

@@ -29,7 +29,7 @@ EXPORTS = [
     "mux_sched_step", "mux_sched_job", "mux_sched_job_seqs", "mux_sched_table", "mux_sched_counts",
     "mux_device_cu_count", "mux_stream_create_masked", "mux_stream_destroy", "mux_probe_stream_read", "mux_probe_mfma",
     "mux_estimate_tpt", "mux_find_batch_size", "mux_runner_create", "mux_runner_destroy", "mux_runner_step",
-    "mux_runner_launch", "mux_runner_set_buffers", "mux_runner_run_step", "mux_runner_counts", "mux_runner_synchronize", "mux_runner_read_table",
+    "mux_runner_launch", "mux_runner_launch_layer", "mux_runner_set_buffers", "mux_runner_run_step", "mux_runner_counts", "mux_runner_synchronize", "mux_runner_read_table",
 ]
 
 MUX_JOB_PREFILL, MUX_JOB_DECODE, MUX_JOB_PREEMPT = 1, 2, 3
@@ -92,6 +92,7 @@ def load() -> C.CDLL:
     L.mux_runner_destroy.argtypes = [vp]
     L.mux_runner_step.argtypes = [vp, C.POINTER(i32)]
     L.mux_runner_launch.argtypes = [vp, i32, vp, vp, vp, vp, f32]
+    L.mux_runner_launch_layer.argtypes = [vp, i32, i32, vp, vp, vp, vp, f32]
     L.mux_runner_set_buffers.argtypes = [vp, i32] + [vp] * 8 + [f32]
     L.mux_runner_run_step.argtypes = [vp, C.POINTER(i32)]
     L.mux_runner_counts.argtypes = [vp, vp]
@@ -434,6 +435,11 @@ class Runner:
 
     def launch(self, job: int, out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, scale: float) -> None:
         _check(load().mux_runner_launch(self.handle, job, _dev(out), _dev(q), _dev(k_new), _dev(v_new), scale), "mux_runner_launch")
+
+    def launch_layer(self, job: int, layer: int, out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                     scale: float) -> None:
+        _check(load().mux_runner_launch_layer(self.handle, job, layer, _dev(out), _dev(q), _dev(k_new), _dev(v_new), scale),
+               "mux_runner_launch_layer")
 
     def set_buffers(self, model: int, prefill, decode, scale: float) -> None:
         """prefill, decode = (out, q, k_new, v_new) tensors the model's jobs use from now on (kept alive here)."""

@@ -82,6 +82,12 @@ struct ModelRun {
     const void *reg_q[2] = {}, *reg_k[2] = {}, *reg_v[2] = {};
     float reg_scale = 0.f;
     bool launched = false;           // since `done` was last recorded
+    // the job whose arrays were staged and whose block ids were installed last (mux_runner_launch[_layer])
+    struct Prepared {
+        int64_t step = -1;               // scheduler iteration the job belongs to
+        int32_t job = -1, kind = 0, n = 0, total = 0, longest = 0, rows = 0;
+        const int32_t *seq = nullptr, *pos = nullptr, *cu = nullptr, *start = nullptr, *ctx = nullptr;   // DEVICE
+    } prep;
 };
 
 }  // namespace
@@ -93,7 +99,7 @@ struct mux_runner {
     size_t area_ints = 0;
     std::vector<ModelRun> models;
     bool one_stream = true;
-    int64_t jobs_launched = 0, seqs_launched = 0;
+    int64_t jobs_launched = 0, seqs_launched = 0, steps = 0;
     bool stage_always = false;   // MUX_RUNNER_STAGE_ALWAYS=1 when the runner was created: never pass arrays as arguments
     std::vector<int64_t> ids64;
     std::vector<int32_t> slots, lens, flags;
@@ -227,8 +233,9 @@ int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, 
         // layers always launches all its slots: the layers of a table are max_seqs rows apart)
         for (int32_t rows = m.layers > 1 ? max_seqs : 1; rows <= max_seqs; ++rows)
             for (int32_t nb = 1; nb <= max_blocks; ++nb)
-                m.decode_ws_bytes = std::max(m.decode_ws_bytes,
-                                             mux_decode_step_workspace_bytes(pool, m.layers, rows, m.hq, m.hkv, nb * pool->block_size));
+                for (int32_t layers : {1, m.layers})   // all layers in one launch, or one layer at a time
+                    m.decode_ws_bytes = std::max(m.decode_ws_bytes,
+                                                 mux_decode_step_workspace_bytes(pool, layers, rows, m.hq, m.hkv, nb * pool->block_size));
         m.prefill_ws_bytes = mux_prefill_workspace_bytes(pool, max_seqs, r->max_tokens, static_cast<int32_t>(max_ctx), m.hq, m.hkv);
         bool good = m.decode_ws_bytes != 0;
         good = good && ok(hipMalloc(&m.tables, table_bytes)) && ok(hipMalloc(&m.job_tables, table_bytes));
@@ -265,6 +272,7 @@ int mux_runner_step(mux_runner_t *r, int32_t *n_jobs)
     if (!r || !n_jobs) return MUX_ERR_INVALID;
     const int rc = mux_sched_step(r->sched, n_jobs);
     if (rc != MUX_OK) return rc;
+    ++r->steps;
     for (size_t i = 0; i < r->models.size(); ++i)
         if (mux_sched_released_blocks(r->sched, static_cast<int32_t>(i))) {
             const int rc2 = order_after(r, r->models[i]);
@@ -273,22 +281,24 @@ int mux_runner_step(mux_runner_t *r, int32_t *n_jobs)
     return MUX_OK;
 }
 
-int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, const void *k_new, const void *v_new, float scale)
+// Stages the job's arrays, installs the block ids it brought and remembers where the arrays are:
+// everything a launch needs apart from the K/V/Q values.  *model_out = the job's model, or -1 for
+// a job that launches nothing (a preemption).
+static int prepare_job(mux_runner_t *r, int32_t job, int32_t *model_out)
 {
-    if (!r) return MUX_ERR_INVALID;
     int32_t kind = 0, model = 0, n = 0;
     int rc = mux_sched_job(r->sched, job, &kind, &model, &n);
     if (rc != MUX_OK) return rc;
+    *model_out = -1;
     if (kind == MUX_JOB_PREEMPT || n == 0) return MUX_OK;
-    if (!out || !q || !k_new || !v_new) return MUX_ERR_INVALID;
-    if (n > r->max_seqs) return MUX_ERR_INVALID;
-    ++r->jobs_launched;
-    r->seqs_launched += n;
+    if (n > r->max_seqs || (kind != MUX_JOB_PREFILL && kind != MUX_JOB_DECODE)) return MUX_ERR_INVALID;
     rc = mux_sched_job_seqs(r->sched, job, nullptr, r->slots.data(), r->lens.data(), r->flags.data());
     if (rc != MUX_OK) return rc;
     ModelRun &m = r->models[model];
     const int32_t *table = mux_sched_table(r->sched, model);
     const int32_t B = r->pool->block_size, heads = m.heads, cols = r->max_blocks;
+    ModelRun::Prepared p;
+    p.step = r->steps, p.job = job, p.kind = kind, p.n = n;
 
     if (kind == MUX_JOB_PREFILL) {
         int32_t *host = nullptr, *dev = nullptr;
@@ -314,9 +324,9 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
             if (slot < 0 || slot >= r->max_seqs || nb > cols) return MUX_ERR_INVALID;
             cu[i] = t;
             q_start[i] = 0;
-            for (int32_t p = 0; p < len; ++p, ++t) {
+            for (int32_t pos = 0; pos < len; ++pos, ++t) {
                 tok_seq[t] = i;
-                tok_pos[t] = p;
+                tok_pos[t] = pos;
             }
             int32_t *e = entries + kEntryInts * i;
             e[0] = slot, e[1] = i, e[2] = 0, e[3] = nb, e[4] = at;
@@ -326,78 +336,128 @@ int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, co
         cu[n] = t;
         rc = send_area(m, area, host, dev, need);
         if (rc != MUX_OK) return rc;
-        const int32_t *d_seq = dev, *d_pos = dev + total, *d_cu = dev + 2 * total, *d_start = d_cu + n + 1;
-        const int32_t *d_entries = d_start + n, *d_ids = d_entries + kEntryInts * n;
-        rc = install(m, d_entries, d_ids, n, true, r->max_seqs, cols);
+        p.seq = dev, p.pos = dev + total, p.cu = dev + 2 * total, p.start = p.cu + n + 1;
+        p.total = static_cast<int32_t>(total), p.longest = longest;
+        rc = install(m, p.start + n, p.start + n + kEntryInts * n, n, true, r->max_seqs, cols);
         if (rc != MUX_OK) return rc;
-        m.launched = true;
-        // layer by layer: buffers are [layer][token][heads][d], the job's tables [layer][max_seqs rows][hkv][max_blocks]
-        const size_t eb = static_cast<size_t>(r->pool->elem_bytes) * r->pool->head_dim * static_cast<size_t>(total);
-        for (int32_t l = 0; l < m.layers; ++l) {
-            const int32_t *tab = m.job_tables + static_cast<size_t>(l) * r->max_seqs * m.hkv * cols;
-            const char *kl = static_cast<const char *>(k_new) + l * eb * m.hkv, *vl = static_cast<const char *>(v_new) + l * eb * m.hkv;
-            const char *ql = static_cast<const char *>(q) + l * eb * m.hq;
-            char *ol = static_cast<char *>(out) + l * eb * m.hq;
-            rc = mux_kv_append(r->pool, kl, vl, d_seq, d_pos, tab, static_cast<int32_t>(total), n, m.hkv, cols, m.stream);
+    } else {
+        // arrays: context length per slot (0 = not in this step), up to the highest slot | entries | ids
+        int32_t rows = 0, longest = 0, n_entries = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            if (r->slots[i] < 0 || r->slots[i] >= r->max_seqs) return MUX_ERR_INVALID;
+            rows = std::max(rows, r->slots[i] + 1);
+            longest = std::max(longest, r->lens[i]);
+            n_entries += (r->flags[i] & MUX_JOB_FLAG_TABLE) ? 1 : 0;
+        }
+        if (m.layers > 1) rows = r->max_seqs;   // the layers of the device table are max_seqs rows apart
+        const size_t need = static_cast<size_t>(rows) + static_cast<size_t>(n_entries) * (kEntryInts + heads);
+        if (need > r->area_ints) return MUX_ERR_INVALID;
+        const bool as_arguments = !r->stage_always && need <= static_cast<size_t>(kInlineInts);
+        InlineArrays inl{};
+        int32_t *host = inl.v, *dev = nullptr;
+        int area = 0;
+        if (!as_arguments) {
+            rc = claim_area(m, r->area_ints, &host, &dev, &area);
             if (rc != MUX_OK) return rc;
-            rc = mux_prefill_attn(r->pool, ol, ql, d_cu, d_start, tab, n, static_cast<int32_t>(total), longest, longest, m.hq, m.hkv,
-                                  cols, scale, m.prefill_ws, m.prefill_ws_bytes, m.stream);
+        }
+        int32_t *ctx = host, *entries = host + rows, *ids = entries + kEntryInts * n_entries;
+        std::fill(ctx, ctx + rows, 0);
+        int32_t e_at = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            const int32_t slot = r->slots[i], len = r->lens[i];
+            ctx[slot] = len;
+            if (!(r->flags[i] & MUX_JOB_FLAG_TABLE)) continue;
+            const int32_t col = (len - 1) / B;   // the block the appended token opened
+            if (len <= 0 || col >= cols) return MUX_ERR_INVALID;
+            int32_t *e = entries + kEntryInts * e_at;
+            e[0] = slot, e[1] = -1, e[2] = col, e[3] = 1, e[4] = e_at * heads;
+            const int32_t *row = table + static_cast<size_t>(slot) * heads * cols;
+            for (int32_t h = 0; h < heads; ++h) ids[e_at * heads + h] = row[static_cast<size_t>(h) * cols + col];
+            ++e_at;
+        }
+        if (as_arguments) {
+            hipLaunchKernelGGL(install_inline_kernel, dim3(1), dim3(256), 0, m.stream, inl, rows, n_entries, m.ctx, m.tables, heads, m.hkv,
+                               r->max_seqs, cols);
+            if (!ok(hipGetLastError())) return MUX_ERR_HIP;
+            p.ctx = m.ctx;
+        } else {
+            rc = send_area(m, area, host, dev, need);
+            if (rc != MUX_OK) return rc;
+            rc = install(m, dev + rows, dev + rows + kEntryInts * n_entries, n_entries, false, r->max_seqs, cols);
+            if (rc != MUX_OK) return rc;
+            p.ctx = dev;
+        }
+        p.rows = rows, p.longest = longest;
+    }
+    m.launched = true;
+    m.prep = p;
+    ++r->jobs_launched;
+    r->seqs_launched += n;
+    *model_out = model;
+    return MUX_OK;
+}
+
+// Append + attention of the prepared job for layers l0 .. l1-1.  The buffers start at layer l0.
+static int run_layers(mux_runner_t *r, ModelRun &m, int32_t l0, int32_t l1, void *out, const void *q, const void *k_new,
+                      const void *v_new, float scale)
+{
+    const ModelRun::Prepared &p = m.prep;
+    const int32_t cols = r->max_blocks;
+    const size_t layer_cells = static_cast<size_t>(r->max_seqs) * m.hkv * cols;   // table entries of one layer
+    if (p.kind == MUX_JOB_PREFILL) {
+        // layer by layer: buffers are [layer][token][heads][d], the job's tables [layer][max_seqs rows][hkv][max_blocks]
+        const size_t eb = static_cast<size_t>(r->pool->elem_bytes) * r->pool->head_dim * static_cast<size_t>(p.total);
+        for (int32_t l = l0; l < l1; ++l) {
+            const int32_t *tab = m.job_tables + l * layer_cells;
+            const size_t at = static_cast<size_t>(l - l0) * eb;
+            const char *kl = static_cast<const char *>(k_new) + at * m.hkv, *vl = static_cast<const char *>(v_new) + at * m.hkv;
+            const char *ql = static_cast<const char *>(q) + at * m.hq;
+            char *ol = static_cast<char *>(out) + at * m.hq;
+            int rc = mux_kv_append(r->pool, kl, vl, p.seq, p.pos, tab, p.total, p.n, m.hkv, cols, m.stream);
+            if (rc != MUX_OK) return rc;
+            rc = mux_prefill_attn(r->pool, ol, ql, p.cu, p.start, tab, p.n, p.total, p.longest, p.longest, m.hq, m.hkv, cols, scale,
+                                  m.prefill_ws, m.prefill_ws_bytes, m.stream);
             if (rc != MUX_OK) return rc;
         }
         return MUX_OK;
     }
+    // one launch for the layers asked for (their tables follow one another)
+    return mux_decode_step(r->pool, out, q, k_new, v_new, m.tables + l0 * layer_cells, p.ctx, l1 - l0, p.rows, m.hq, m.hkv, cols, p.longest,
+                           scale, m.decode_ws, m.decode_ws_bytes, m.stream);
+}
 
-    if (kind != MUX_JOB_DECODE) return MUX_ERR_INVALID;
-    // arrays: context length per slot (0 = not in this step), up to the highest slot | entries | ids
-    int32_t rows = 0, longest = 0, n_entries = 0;
-    for (int32_t i = 0; i < n; ++i) {
-        if (r->slots[i] < 0 || r->slots[i] >= r->max_seqs) return MUX_ERR_INVALID;
-        rows = std::max(rows, r->slots[i] + 1);
-        longest = std::max(longest, r->lens[i]);
-        n_entries += (r->flags[i] & MUX_JOB_FLAG_TABLE) ? 1 : 0;
-    }
-    if (m.layers > 1) rows = r->max_seqs;   // the layers of the device table are max_seqs rows apart
-    const size_t need = static_cast<size_t>(rows) + static_cast<size_t>(n_entries) * (kEntryInts + heads);
-    if (need > r->area_ints) return MUX_ERR_INVALID;
-    const bool as_arguments = !r->stage_always && need <= static_cast<size_t>(kInlineInts);
-    InlineArrays inl{};
-    int32_t *host = inl.v, *dev = nullptr;
-    int area = 0;
-    if (!as_arguments) {
-        rc = claim_area(m, r->area_ints, &host, &dev, &area);
+int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, const void *k_new, const void *v_new, float scale)
+{
+    if (!r) return MUX_ERR_INVALID;
+    int32_t kind = 0, model = 0, n = 0;
+    int rc = mux_sched_job(r->sched, job, &kind, &model, &n);
+    if (rc != MUX_OK) return rc;
+    if (kind == MUX_JOB_PREEMPT || n == 0) return MUX_OK;
+    if (!out || !q || !k_new || !v_new) return MUX_ERR_INVALID;
+    rc = prepare_job(r, job, &model);
+    if (rc != MUX_OK || model < 0) return rc;
+    ModelRun &m = r->models[model];
+    return run_layers(r, m, 0, m.layers, out, q, k_new, v_new, scale);
+}
+
+int mux_runner_launch_layer(mux_runner_t *r, int32_t job, int32_t layer, void *out, const void *q, const void *k_new,
+                            const void *v_new, float scale)
+{
+    if (!r) return MUX_ERR_INVALID;
+    int32_t kind = 0, model = 0, n = 0;
+    int rc = mux_sched_job(r->sched, job, &kind, &model, &n);
+    if (rc != MUX_OK) return rc;
+    if (layer < 0 || layer >= r->models[model].layers) return MUX_ERR_INVALID;
+    if (kind == MUX_JOB_PREEMPT || n == 0) return MUX_OK;
+    if (!out || !q || !k_new || !v_new) return MUX_ERR_INVALID;
+    ModelRun &m = r->models[model];
+    if (layer == 0) {
+        rc = prepare_job(r, job, &model);
         if (rc != MUX_OK) return rc;
+    } else if (m.prep.step != r->steps || m.prep.job != job) {
+        return MUX_ERR_INVALID;   // layer 0 of this job comes first
     }
-    int32_t *ctx = host, *entries = host + rows, *ids = entries + kEntryInts * n_entries;
-    std::fill(ctx, ctx + rows, 0);
-    int32_t e_at = 0;
-    for (int32_t i = 0; i < n; ++i) {
-        const int32_t slot = r->slots[i], len = r->lens[i];
-        ctx[slot] = len;
-        if (!(r->flags[i] & MUX_JOB_FLAG_TABLE)) continue;
-        const int32_t col = (len - 1) / B;   // the block the appended token opened
-        if (len <= 0 || col >= cols) return MUX_ERR_INVALID;
-        int32_t *e = entries + kEntryInts * e_at;
-        e[0] = slot, e[1] = -1, e[2] = col, e[3] = 1, e[4] = e_at * heads;
-        const int32_t *row = table + static_cast<size_t>(slot) * heads * cols;
-        for (int32_t h = 0; h < heads; ++h) ids[e_at * heads + h] = row[static_cast<size_t>(h) * cols + col];
-        ++e_at;
-    }
-    const int32_t *ctx_dev = nullptr;
-    if (as_arguments) {
-        hipLaunchKernelGGL(install_inline_kernel, dim3(1), dim3(256), 0, m.stream, inl, rows, n_entries, m.ctx, m.tables, heads, m.hkv,
-                           r->max_seqs, cols);
-        if (!ok(hipGetLastError())) return MUX_ERR_HIP;
-        ctx_dev = m.ctx;
-    } else {
-        rc = send_area(m, area, host, dev, need);
-        if (rc != MUX_OK) return rc;
-        rc = install(m, dev + rows, dev + rows + kEntryInts * n_entries, n_entries, false, r->max_seqs, cols);
-        if (rc != MUX_OK) return rc;
-        ctx_dev = dev;
-    }
-    m.launched = true;
-    return mux_decode_step(r->pool, out, q, k_new, v_new, m.tables, ctx_dev, m.layers, rows, m.hq, m.hkv, cols, longest, scale,
-                           m.decode_ws, m.decode_ws_bytes, m.stream);
+    return run_layers(r, m, layer, layer + 1, out, q, k_new, v_new, scale);
 }
 
 int mux_runner_set_buffers(mux_runner_t *r, int32_t model, void *prefill_out, const void *prefill_q, const void *prefill_k,

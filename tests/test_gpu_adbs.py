@@ -189,3 +189,58 @@ def test_run_step_with_registered_buffers_equals_step_plus_launch():
     assert a.idle() and b.idle() and rid > 10
     assert torch.equal(kv_a, kv_b)
     assert a.runner.counts() == b.runner.counts() and a.tokens() > rid
+
+
+def test_layer_by_layer_launches_equal_the_all_layers_launch():
+    """mux_runner_launch_layer, one layer at a time (as an engine with other kernels between the
+    attention layers would call it), leaves the same bytes in the pool and the same outputs as
+    mux_runner_launch for all layers at once."""
+    print("[case] runner layer by layer against all layers at once", flush=True)
+    per_layer = [wl.ModelShape("a", 4, 4, 128), wl.ModelShape("b", 8, 2, 128)]
+    layers = [3, 2]
+    d, B, n_blocks, max_seqs, max_blocks, budget = 128, 16, 900, 5, 12, 128
+    order = wl.placement_order(np.random.default_rng(15), n_blocks)
+    sides = []
+    for _ in range(2):
+        kv = torch.zeros(n_blocks * 2 * B * d * 2, dtype=torch.uint8, device="cuda")
+        pool = mx.mux_pool_create(kv, n_blocks, B, d, mx.MUX_BF16, order)
+        torch.manual_seed(21)
+        sides.append((kv, pool, eng.NativeEngine(pool, per_layer, max_seqs, max_blocks, budget, None, layers=layers)))
+    (kv_a, _, a), (kv_b, _, b) = sides
+    rng = np.random.default_rng(16)
+    rid = 0
+    for it in range(300):
+        if it < 30:
+            for _ in range(int(rng.poisson(0.6))):
+                m, plen, olen = int(rng.integers(2)), int(rng.integers(1, 120)), int(rng.integers(1, 50))
+                a.submit(m, rid, plen, olen)
+                b.submit(m, rid, plen, olen)
+                rid += 1
+        n_a = a.step()                                                  # all layers of a job in one call
+        assert n_a == b.runner.step()
+        for j, job in enumerate(b.sched.jobs(n_a)):
+            st = b.models[job["model"]]
+            if job["kind"] == mx.MUX_JOB_PREEMPT:
+                continue
+            for layer in range(st.layers):
+                if job["kind"] == mx.MUX_JOB_PREFILL:
+                    t = int(job["lens"].sum())
+                    sl = slice(layer * t, (layer + 1) * t)
+                    b.runner.launch_layer(j, layer, st.out_pre[sl], st.q_pre[sl], st.k_pre[sl], st.v_pre[sl], b.scale)
+                else:
+                    b.runner.launch_layer(j, layer, st.out_dec[layer], st.q_dec[layer], st.k_dec[layer], st.v_dec[layer], b.scale)
+        a.runner.synchronize()
+        b.runner.synchronize()
+        for st_a, st_b in zip(a.models, b.models):
+            assert torch.equal(st_a.out_dec.view(torch.int16), st_b.out_dec.view(torch.int16))
+            assert torch.equal(st_a.out_pre.view(torch.int16), st_b.out_pre.view(torch.int16))
+        if it >= 30 and a.idle():
+            break
+    assert a.idle() and b.idle() and rid > 8
+    assert torch.equal(kv_a, kv_b) and a.runner.counts() == b.runner.counts()
+    # a later layer of a job whose layer 0 was not launched in this iteration is refused
+    b.submit(0, 10_000, 20, 3)
+    assert b.runner.step() >= 1
+    st = b.models[0]
+    with pytest.raises(mx.MuxError):
+        b.runner.launch_layer(0, 1, st.out_pre[:20], st.q_pre[:20], st.k_pre[:20], st.v_pre[:20], b.scale)

@@ -72,6 +72,7 @@ def test_runner_argument_errors_need_no_gpu():
     n = C.c_int32()
     assert lib.mux_runner_step(None, C.byref(n)) == mx.MUX_ERR_INVALID
     assert lib.mux_runner_launch(None, 0, None, None, None, None, 1.0) == mx.MUX_ERR_INVALID
+    assert lib.mux_runner_launch_layer(None, 0, 0, None, None, None, None, 1.0) == mx.MUX_ERR_INVALID
     assert lib.mux_runner_destroy(None) == mx.MUX_ERR_INVALID
     assert lib.mux_runner_synchronize(None) == mx.MUX_ERR_INVALID
     assert lib.mux_runner_read_table(None, 0, None) == mx.MUX_ERR_INVALID
