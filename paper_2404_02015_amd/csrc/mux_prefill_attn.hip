@@ -107,14 +107,8 @@ __device__ __forceinline__ float row_max_across_groups(float x)
 }
 
 // Transposing LDS read: within each group of 16 lanes, lane i receives element (i % 4) of the
-// four 8-byte chunks addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12 of the group.
-__device__ __forceinline__ u32x2 lds_read_tr16(const char *p)
-{
-    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-    return __builtin_bit_cast(u32x2, r);
-}
-// The same two reads from an LDS byte address held as a number (see the pinned offsets in the kernel).
+// four 8-byte chunks addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12 of the group.  The LDS
+// byte address is held as a number (see the pinned offsets in the kernel).
 __device__ __forceinline__ u32x2 lds_read_tr16_at(unsigned addr)
 {
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -355,8 +349,6 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
             raw_barrier();
         }
         if (wave_active && kv0 <= wave_last_pos) {
-            const char *kb = smem + buf * (KBUF + VBUF);
-            const char *vb = kb + KBUF;
             // S^T for the two 16-token halves and the CB column blocks
             f32x4 st[CB][2];
 #pragma unroll
