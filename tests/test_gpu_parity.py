@@ -563,3 +563,26 @@ def test_decode_step_captured_in_a_graph_replays_correctly():
         worst = max(worst, H.assert_close(out, want, "bf16", "replay %d" % step))
     ls.check_counters()
     print("graph replays: max abs err %.2e" % worst, flush=True)
+
+
+@pytest.mark.parametrize("dtype,block_size", [("bf16", 16), ("bf16", 32), ("fp32", 8)])
+def test_degenerate_launches(dtype, block_size):
+    """Launches with nothing (or next to nothing) to do: a batch whose contexts are all empty, a
+    chunked prefill in which some sequences contribute no rows, an append of zero tokens.  No
+    output row may be left unwritten or hold anything but what the definition gives."""
+    _say("degenerate launches %s B=%d" % (dtype, block_size))
+    # decode: every context empty -> all zeros (also through the fused step)
+    ls, job, q, got, _ = _decode_case(dtype, 128, block_size, 4, 2, [0, 0, 0], seed=90)
+    assert not got.float().abs().max().item()
+    # prefill: sequences 0 and 2 have no rows in this chunk, sequence 1 has 37 behind 20 cached tokens, sequence 3 one row
+    lens, starts = [33, 57, 0, 1], [33, 20, 0, 0]
+    ls, job, q, got, want = _prefill_case(dtype, 128, block_size, 4, 2, lens, starts, seed=91)
+    assert got.shape[0] == 38
+    H.assert_close(got, want, dtype)
+    # append of zero tokens: accepted, nothing written
+    before = ls.kv.clone()
+    z = torch.zeros(0, 2, 128, dtype=H.torch_dtype(dtype), device="cuda")
+    zi = torch.zeros(0, dtype=torch.int32, device="cuda")
+    mx.mux_kv_append(ls.lib, z, z, zi, zi, job.tables_dev)
+    torch.cuda.synchronize()
+    assert torch.equal(before, ls.kv)
