@@ -475,6 +475,8 @@ void launch_mfma(PrefillArgs a, int max_q_len, hipStream_t st)
     const long long units = static_cast<long long>(a.n_seqs) * a.n_kv_heads * a.n_passes;
     // with fewer than ~4 rounds of workgroups balance beats L2 reuse
     a.tile_bundle = units * a.n_row_tiles <= 4 * kWgsPerCu * 256 ? 1 : a.n_row_tiles;
+    static const int forced_bundle = std::getenv("MUX_PREFILL_BUNDLE") ? std::atoi(std::getenv("MUX_PREFILL_BUNDLE")) : 0;
+    if (forced_bundle > 0) a.tile_bundle = std::min(forced_bundle, a.n_row_tiles);
     const long long bundles = (a.n_row_tiles + a.tile_bundle - 1) / a.tile_bundle;
     const long long grid = (units + 7) / 8 * 8 * bundles * a.tile_bundle;   // see the blockIdx mapping in the kernel
     constexpr int kLds = kBufs * 2 * kKT * D * 2 + kMaxCachedIds * 4;
