@@ -63,7 +63,8 @@ DEMO = os.path.join(PKG, "examples", "c_abi_demo")
 
 def build_demo(verbose: bool = True) -> str:
     """A small host program that uses the library through include/mux.h alone (run by the GPU tests)."""
-    cmd = [HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wall", "-I" + os.path.join(ROOT, "include"), DEMO_SRC,
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wall", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I" + os.path.join(ROOT, "include"), DEMO_SRC,
            "-o", DEMO, "-L" + PKG, "-lmux", "-Wl,-rpath,$ORIGIN/.."]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
