@@ -626,6 +626,7 @@ def main() -> int:
             "traffic_source": MEASURED_TRAFFIC_CFG2["source"] if args.config == 2 else None,
             "avg_launch_ms": busy / len(durs) * 1e3, "algorithmic_bytes_per_launch": float(np.mean(algo)),
             "launches": len(durs), "raw_avg_launch_ms": float(np.mean(durs) * 1e3), "overlap": float(np.sum(durs) / busy),
+            "raw_median_launch_ms": float(np.median(durs) * 1e3), "raw_min_launch_ms": float(np.min(durs) * 1e3),
             "note": "avg_launch_ms = time with at least one decode launch running / launches; raw_avg_launch_ms = mean "
                     "start-to-end duration of a launch; overlap = their ratio (1.0 when launches never run concurrently)",
         }
