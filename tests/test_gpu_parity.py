@@ -586,3 +586,13 @@ def test_degenerate_launches(dtype, block_size):
     mx.mux_kv_append(ls.lib, z, z, zi, zi, job.tables_dev)
     torch.cuda.synchronize()
     assert torch.equal(before, ls.kv)
+
+
+@pytest.mark.parametrize("n_q,n_kv", [(2, 1), (8, 1)])
+def test_decode_one_very_long_context(n_q, n_kv):
+    """A 40 000-token context (2 500 blocks, ten spans of the longest span a workgroup handles) beside
+    short ones: many partial results per row, merged by the combine kernel."""
+    _say("decode with a 40 000-token context, Hq=%d Hkv=%d" % (n_q, n_kv))
+    ls, job, q, got, want = _decode_case("bf16", 128, 16, n_q, n_kv, [40000, 5, 0, 4097], seed=95 + n_q)
+    err = H.assert_close(got, want, "bf16")
+    print("max abs err %.2e" % err)
