@@ -96,7 +96,7 @@ class DecodeModel:
         self.len_steps = torch.from_numpy(self.lens[None, :] + steps).to(device)
         self.pos_len = torch.stack([self.pos_steps[0] - 1, self.len_steps[0] - 1]).contiguous()   # state before step 0
         max_final = int(job.lens.max()) + total_steps + 1
-        ws = mx.mux_decode_workspace_bytes(pool, self.n, n_q, n_kv, max_final)
+        ws = mx.mux_decode_workspace_bound(pool, self.n, n_q, n_kv, max_final)   # the hint grows step by step: cover every plan
         self.workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=device)
         # pinned staging ring for table patches: flat table indices and the ids, which
         # mux_alloc_blocks writes there itself

@@ -171,6 +171,12 @@ MUX_API int mux_decode_attn(mux_pool_t *pool, void *out, const void *q, const in
                     size_t workspace_bytes, void *stream);
 MUX_API size_t mux_decode_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs, int32_t n_q_heads,
                                   int32_t n_kv_heads, int32_t max_ctx_len);
+/* For callers that allocate one workspace up front: the largest value mux_decode_workspace_bytes
+ * returns for ANY call with 1 .. max_seqs sequences and 1 .. max_ctx_len as its max_ctx_len.  A
+ * smaller call can need more than the largest one (few long rows are cut into many spans), so
+ * sizing for the largest call alone is not enough.  Host arithmetic only; 0 for bad arguments. */
+MUX_API size_t mux_decode_workspace_bound(const mux_pool_t *pool, int32_t max_seqs, int32_t n_q_heads,
+                                  int32_t n_kv_heads, int32_t max_ctx_len);
 
 /* ---------------------------------------------------------------------------------
  * Fused decoding step (Section 3.4, Implementation: in one decoding step an engine fills the
@@ -185,7 +191,10 @@ MUX_API size_t mux_decode_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs
  * [max_blocks] (every layer has its own blocks); ctx_lens: DEVICE [n_seqs], lengths AFTER the
  * append (the new token sits at position ctx_lens[s] - 1; sequences with ctx_lens[s] == 0
  * append nothing and return zeros).  The blocks of the new positions must already be in the
- * tables.  workspace: at least mux_decode_step_workspace_bytes(...) bytes, 16-byte aligned.
+ * tables.  max_ctx_len must bound ctx_lens as in mux_decode_attn; a sequence whose ctx_lens[s]
+ * exceeds it appends NOTHING (its new token lies beyond the part of the context this launch
+ * was sized for) and attends to its first max_ctx_len cached tokens only.
+ * workspace: at least mux_decode_step_workspace_bytes(...) bytes, 16-byte aligned.
  * ------------------------------------------------------------------------------- */
 MUX_API int mux_decode_step(mux_pool_t *pool, void *out, const void *q, const void *k_new, const void *v_new,
                     const int32_t *block_tables, const int32_t *ctx_lens, int32_t n_layers, int32_t n_seqs,
@@ -217,6 +226,10 @@ MUX_API int mux_prefill_attn(mux_pool_t *pool, void *out, const void *q, const i
                      size_t workspace_bytes, void *stream);
 MUX_API size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs, int32_t total_q,
                                    int32_t max_ctx_len, int32_t n_q_heads, int32_t n_kv_heads);
+/* The largest value mux_prefill_workspace_bytes returns for any call with 1 .. max_total_q query
+ * rows and 1 .. max_ctx_len as its max_ctx_len (0 for pools that run on the matrix cores). */
+MUX_API size_t mux_prefill_workspace_bound(const mux_pool_t *pool, int32_t max_total_q, int32_t max_ctx_len,
+                                   int32_t n_q_heads, int32_t n_kv_heads);
 
 /* Human-readable name of a status code (static storage). */
 /* ---------------------------------------------------------------------------------

@@ -70,9 +70,8 @@ class _ModelState:
         self.q_all = torch.zeros(max_seqs, shape.n_q_heads, pool.head_dim, dtype=torch.bfloat16, device=device)
         self.out_all = torch.zeros_like(self.q_all)
         self.stream = torch.cuda.Stream(device=device)
-        # the split of long contexts depends on the longest context of the launch: size for the worst one
-        ws = max(mx.mux_decode_workspace_bytes(pool, max_seqs, shape.n_q_heads, shape.n_kv_heads, nb * pool.block_size)
-                 for nb in range(1, max_blocks + 1))
+        # the split of long contexts depends on the rows and the longest context of the launch: size for the worst one
+        ws = mx.mux_decode_workspace_bound(pool, max_seqs, shape.n_q_heads, shape.n_kv_heads, max_blocks * pool.block_size)
         self.workspace = torch.empty(ws, dtype=torch.uint8, device=device)
         self.done = torch.cuda.Event()
         self.tokens = 0          # output tokens produced

@@ -30,6 +30,7 @@ EXPORTS = [
     "mux_device_cu_count", "mux_stream_create_masked", "mux_stream_destroy", "mux_probe_stream_read", "mux_probe_mfma",
     "mux_estimate_tpt", "mux_find_batch_size", "mux_runner_create", "mux_runner_destroy", "mux_runner_step",
     "mux_runner_launch", "mux_runner_launch_layer", "mux_runner_set_buffers", "mux_runner_run_step", "mux_runner_counts", "mux_runner_synchronize", "mux_runner_read_table",
+    "mux_decode_workspace_bound", "mux_prefill_workspace_bound",
 ]
 
 MUX_JOB_PREFILL, MUX_JOB_DECODE, MUX_JOB_PREEMPT = 1, 2, 3
@@ -108,6 +109,10 @@ def load() -> C.CDLL:
     L.mux_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, sz, vp]
     L.mux_decode_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     L.mux_decode_workspace_bytes.restype = sz
+    L.mux_decode_workspace_bound.argtypes = [vp, i32, i32, i32, i32]
+    L.mux_decode_workspace_bound.restype = sz
+    L.mux_prefill_workspace_bound.argtypes = [vp, i32, i32, i32, i32]
+    L.mux_prefill_workspace_bound.restype = sz
     L.mux_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, sz, vp]
     L.mux_decode_step_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
     L.mux_decode_step_workspace_bytes.restype = sz
@@ -274,6 +279,14 @@ def mux_kv_append(pool: Pool, k_new: torch.Tensor, v_new: torch.Tensor, tok_seq:
 
 def mux_decode_workspace_bytes(pool: Pool, n_seqs: int, n_q_heads: int, n_kv_heads: int, max_ctx_len: int) -> int:
     return load().mux_decode_workspace_bytes(pool.handle, n_seqs, n_q_heads, n_kv_heads, max_ctx_len)
+
+
+def mux_decode_workspace_bound(pool: Pool, max_seqs: int, n_q_heads: int, n_kv_heads: int, max_ctx_len: int) -> int:
+    return load().mux_decode_workspace_bound(pool.handle, max_seqs, n_q_heads, n_kv_heads, max_ctx_len)
+
+
+def mux_prefill_workspace_bound(pool: Pool, max_total_q: int, max_ctx_len: int, n_q_heads: int, n_kv_heads: int) -> int:
+    return load().mux_prefill_workspace_bound(pool.handle, max_total_q, max_ctx_len, n_q_heads, n_kv_heads)
 
 
 def mux_decode_attn(pool: Pool, out: torch.Tensor, q: torch.Tensor, block_tables: torch.Tensor, ctx_lens: torch.Tensor,

@@ -282,6 +282,13 @@ size_t mux_decode_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs, int32_
     return mux_plan_decode(pool, n_seqs, n_q_heads, n_kv_heads, max_ctx_len).workspace_bytes;
 }
 
+size_t mux_decode_workspace_bound(const mux_pool_t *pool, int32_t max_seqs, int32_t n_q_heads, int32_t n_kv_heads,
+                                  int32_t max_ctx_len)
+{
+    if (!pool || max_seqs <= 0 || !heads_ok(n_q_heads, n_kv_heads) || max_ctx_len <= 0) return 0;
+    return mux_decode_workspace_upper_bound(pool, max_seqs, n_q_heads, n_kv_heads, max_ctx_len);
+}
+
 int mux_decode_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *block_tables,
                     const int32_t *ctx_lens, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads,
                     int32_t max_blocks, int32_t max_ctx_len, float scale, void *workspace, size_t workspace_bytes,
@@ -336,6 +343,14 @@ size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs, int32
     if (!pool || n_seqs <= 0 || total_q <= 0 || max_ctx_len <= 0 || !heads_ok(n_q_heads, n_kv_heads)) return 0;
     if (mux_prefill_uses_mfma(pool)) return 0;
     return mux_plan_decode(pool, total_q, n_q_heads, n_kv_heads, max_ctx_len).workspace_bytes;
+}
+
+size_t mux_prefill_workspace_bound(const mux_pool_t *pool, int32_t max_total_q, int32_t max_ctx_len, int32_t n_q_heads,
+                                   int32_t n_kv_heads)
+{
+    if (!pool || max_total_q <= 0 || max_ctx_len <= 0 || !heads_ok(n_q_heads, n_kv_heads)) return 0;
+    if (mux_prefill_uses_mfma(pool)) return 0;
+    return mux_decode_workspace_upper_bound(pool, max_total_q, n_q_heads, n_kv_heads, max_ctx_len);
 }
 
 int mux_prefill_attn(mux_pool_t *pool, void *out, const void *q, const int32_t *cu_q_lens, const int32_t *q_start,

@@ -136,8 +136,9 @@ struct DecodeArgs {
     int grid_wgs;   // workgroups of the attention launch
 };
 
-// Row r of q/out -> (block-table row, context length).
-__device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &table_row, int &len)
+// Row r of q/out -> (block-table row, context length).  The length is cut at max_ctx_len (the
+// host's bound, which sized the launch); *cut, when asked for, tells whether that happened.
+__device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &table_row, int &len, bool *cut = nullptr)
 {
     if (a.cu_q_lens == nullptr) {
         table_row = r;
@@ -151,6 +152,7 @@ __device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &tab
         table_row = lo;
         len = a.q_start[lo] + (r - a.cu_q_lens[lo]) + 1;  // causal: keys up to and including its own
     }
+    if (cut) *cut = len > a.max_ctx_len;
     len = min(max(len, 0), a.max_ctx_len);
 }
 
@@ -360,9 +362,14 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     // past the sequence's blocks are never used), so the two latencies overlap.
     const int blk_lo = split * a.span_blocks;
     int table_row, L;
-    resolve_row(a, s, table_row, L);
+    bool cut;
+    resolve_row(a, s, table_row, L, &cut);
     table_row = __builtin_amdgcn_readfirstlane(table_row);   // same for every lane: keep the block loop scalar
     L = __builtin_amdgcn_readfirstlane(L);
+    // A fused step appends the row's new token at position L - 1.  A row whose context was cut at
+    // max_ctx_len has its new token beyond the cut: nothing is appended for it (position L - 1 of
+    // the cut context holds an older token, which must stay as it is).
+    const bool appends = a.k_new != nullptr && __builtin_amdgcn_readfirstlane(static_cast<int>(cut)) == 0;
     const int *row = a.tables + (static_cast<long long>(table_row) * a.n_kv_heads + kvh) * a.max_blocks;
     int my_ids = 0;
     {
@@ -476,7 +483,7 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
         auto consume_last = [&](int j, u32x4 (&k)[NG], u32x4 (&v)[NG]) {
             const int blk = blk_lo + wave + kWaves * j;
             const int n_valid = L - blk * BS;  // wave-uniform, >= 1
-            if (a.k_new != nullptr && blk == n_blk_seq - 1) {
+            if (appends && blk == n_blk_seq - 1) {
                 // the new token's row: take it from k_new / v_new, and let pass 0 store it in the pool
                 const int r = n_valid - 1;
                 char *tile = const_cast<char *>(tile_ptr(j));
@@ -538,7 +545,7 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
         auto consume_last = [&](int jj, u32x4 (&k)[NG], u32x4 (&v)[NG]) {
             const int blk = blk_lo + wave + kWaves * (jj / SUBS);
             const int n_valid = L - blk * BS - (jj % SUBS) * TB;  // wave-uniform, >= 1
-            if (a.k_new != nullptr && blk == n_blk_seq - 1) {
+            if (appends && blk == n_blk_seq - 1) {
                 // the new token's row: take it from k_new / v_new, and let pass 0 store it in the pool
                 const int r = n_valid - 1;
                 char *tile = const_cast<char *>(sub_ptr(jj));
@@ -597,7 +604,7 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
             k = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
             v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + tile_bytes));
             const int tok0 = (blk_lo + wave + kWaves * j) * B + r0;   // first token of the group (same in all lanes)
-            if (a.k_new != nullptr && tok0 <= L - 1 && L - 1 < tok0 + min(RPL, rows_here - r0)) {
+            if (appends && tok0 <= L - 1 && L - 1 < tok0 + min(RPL, rows_here - r0)) {
                 if (tok0 + rg == L - 1) {   // the token a fused step appends (a row of this block: see the check above)
                     const long long nsrc = ((static_cast<long long>(s) * a.n_kv_heads + kvh) * D + c0) * EB;
                     k = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(a.k_new) + nsrc);
@@ -732,9 +739,11 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
     for (bool first = true; take_work(a, tid, cursor, first, s, split, kvh, pass); first = false) {
     const int blk_lo = split * a.span_blocks;
     int table_row, L;
-    resolve_row(a, s, table_row, L);
+    bool cut;
+    resolve_row(a, s, table_row, L, &cut);
     table_row = __builtin_amdgcn_readfirstlane(table_row);   // same for every lane: keep the block loop scalar
     L = __builtin_amdgcn_readfirstlane(L);
+    const bool appends = a.k_new != nullptr && __builtin_amdgcn_readfirstlane(static_cast<int>(cut)) == 0;   // a row cut at max_ctx_len appends nothing (see the vector kernel)
     const int *row = a.tables + (static_cast<long long>(table_row) * a.n_kv_heads + kvh) * a.max_blocks;
     int my_ids = 0;
     {
@@ -782,7 +791,7 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
     // row from k_new / v_new (and, in pass 0, stores it in the pool).
     auto patch_new_row = [&](int j, u32x4 (&k)[NP], u32x4 (&v)[NP]) {
         const int blk = blk_lo + wave + kWaves * j;
-        if (a.k_new == nullptr || blk != n_blk_seq - 1) return;
+        if (!appends || blk != n_blk_seq - 1) return;
         const int r = L - 1 - blk * BS;
         int id = __builtin_amdgcn_readlane(my_ids, j);
         id = min(max(id, 0), a.num_blocks - 1);
@@ -993,6 +1002,10 @@ long long resident_workgroups(AttnKernel fn)
 
 }  // namespace
 
+// A launch is cut into at least this many pieces (row x kv head x head pass x span) when its rows
+// are long enough to be cut at all.
+constexpr long long kWantedPieces = 2048;
+
 mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads,
                                 int32_t max_ctx_len)
 {
@@ -1017,7 +1030,7 @@ mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_
         span = forced;
     } else {
         const long long items = static_cast<long long>(n_seqs) * n_kv_heads * plan.n_passes;
-        long long want_splits = (2048 + items - 1) / items;
+        long long want_splits = (kWantedPieces + items - 1) / items;
         // Splitting adds the work-list and merge kernels to the chain (~20 us end to end) and only pays
         // when whole rows cannot keep the GPU busy: a lone workgroup streams ~50 GB/s, so a
         // few hundred of them already saturate the memory system, and the longest-first
@@ -1048,6 +1061,27 @@ mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_
         plan.n_splits > 1 ? static_cast<size_t>(n_seqs) * n_q_heads * plan.n_splits * (pool->head_dim + 2) * sizeof(float) : 0;
     plan.workspace_bytes = plan.plan_bytes + partials;
     return plan;
+}
+
+// The largest workspace any launch of 1 .. max_rows rows with max_ctx_len of at most
+// max_ctx_len tokens can ask for.  Fewer rows or shorter contexts can need MORE than the largest
+// launch (few rows are cut into many spans, each with its partial results), so the bound is a scan:
+// the number of spans depends on the row count only while rows x kv heads x passes is below
+// kWantedPieces; beyond that it depends on the context alone and the workspace grows with the rows.
+size_t mux_decode_workspace_upper_bound(const mux_pool *pool, int32_t max_rows, int32_t n_q_heads, int32_t n_kv_heads,
+                                        int32_t max_ctx_len)
+{
+    const int B = pool->block_size;
+    const int32_t max_blocks = static_cast<int32_t>((static_cast<long long>(max_ctx_len) + B - 1) / B);
+    const int32_t knee = static_cast<int32_t>(std::min<long long>(max_rows, kWantedPieces));
+    size_t worst = 0;
+    for (int32_t nb = 1; nb <= max_blocks; ++nb) {
+        const int32_t ctx = static_cast<int32_t>(std::min<long long>(static_cast<long long>(nb) * B, max_ctx_len));
+        for (int32_t rows = 1; rows <= knee; ++rows)
+            worst = std::max(worst, mux_plan_decode(pool, rows, n_q_heads, n_kv_heads, ctx).workspace_bytes);
+        worst = std::max(worst, mux_plan_decode(pool, max_rows, n_q_heads, n_kv_heads, ctx).workspace_bytes);
+    }
+    return worst;
 }
 
 namespace {
@@ -1148,7 +1182,7 @@ int mux_launch_decode_attn(const mux_pool *pool, const mux_decode_plan &plan, vo
                        max_blocks, max_ctx_len, scale, workspace, stream);
 }
 
-// Generic prefill (fp32 pools, block sizes other than 16): every query row is handled as a
+// Generic prefill (fp32 pools, block sizes that are not a power of two >= 8): every query row is handled as a
 // decode row whose context ends at its own position.  Correct for any supported pool, but it
 // re-reads the keys for every row; the matrix-core kernel covers the hot configuration.
 int mux_launch_prefill_rows_as_decode(const mux_pool *pool, void *out, const void *q, const int32_t *cu_q_lens,

@@ -46,6 +46,8 @@ struct mux_decode_plan {
 };
 mux_decode_plan mux_plan_decode(const mux_pool *pool, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads,
                                 int32_t max_ctx_len);
+size_t mux_decode_workspace_upper_bound(const mux_pool *pool, int32_t max_rows, int32_t n_q_heads, int32_t n_kv_heads,
+                                        int32_t max_ctx_len);
 int mux_launch_decode_attn(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q,
                            const int32_t *tables, const int32_t *ctx_lens, int32_t n_seqs, int32_t n_q_heads,
                            int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len, float scale,

@@ -228,15 +228,14 @@ int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, 
         m.layers = n_layers ? n_layers[i] : 1;
         m.hkv = m.heads / m.layers;
         const size_t table_bytes = static_cast<size_t>(max_seqs) * m.heads * max_blocks * sizeof(int32_t);
-        // the split of long contexts depends on both the number of rows and the longest context:
-        // size the workspace for the worst launch this scheduler can produce (a model of several
-        // layers always launches all its slots: the layers of a table are max_seqs rows apart)
-        for (int32_t rows = m.layers > 1 ? max_seqs : 1; rows <= max_seqs; ++rows)
-            for (int32_t nb = 1; nb <= max_blocks; ++nb)
-                for (int32_t layers : {1, m.layers})   // all layers in one launch, or one layer at a time
-                    m.decode_ws_bytes = std::max(m.decode_ws_bytes,
-                                                 mux_decode_step_workspace_bytes(pool, layers, rows, m.hq, m.hkv, nb * pool->block_size));
-        m.prefill_ws_bytes = mux_prefill_workspace_bytes(pool, max_seqs, r->max_tokens, static_cast<int32_t>(max_ctx), m.hq, m.hkv);
+        // The split of long contexts depends on both the number of rows and the longest context, and
+        // a small job can need more scratch than the largest one: size both workspaces for the worst
+        // launch this scheduler can produce (all layers in one launch, or one layer at a time; a
+        // prefill job holds 1 .. max_tokens rows behind contexts of up to max_ctx tokens).
+        for (int32_t layers : {1, m.layers})
+            m.decode_ws_bytes = std::max(m.decode_ws_bytes, mux_decode_workspace_upper_bound(pool, layers * max_seqs, m.hq, m.hkv,
+                                                                                             static_cast<int32_t>(max_ctx)));
+        m.prefill_ws_bytes = mux_prefill_workspace_bound(pool, r->max_tokens, static_cast<int32_t>(max_ctx), m.hq, m.hkv);
         bool good = m.decode_ws_bytes != 0;
         good = good && ok(hipMalloc(&m.tables, table_bytes)) && ok(hipMalloc(&m.job_tables, table_bytes));
         good = good && ok(hipMemset(m.tables, 0, table_bytes)) && ok(hipMemset(m.job_tables, 0, table_bytes));

@@ -5,6 +5,7 @@ tables; the harness compares what they return.
 from __future__ import annotations
 
 import math
+import time
 from dataclasses import dataclass
 from typing import Dict, List, Optional
 
@@ -105,11 +106,23 @@ def open_job(ls: Lockstep, model_id: int, shape: wl.ModelShape, n_seqs: int, max
     return JobState(model_id, shape, np.zeros(n_seqs, dtype=np.int32), tables, dev, sampled)
 
 
+@dataclass
+class AppendRecord:
+    """The inputs of one append call, kept so that the oracle can be fed later, a slice of
+    sequences at a time (tok_seq is sorted, so a slice of sequences is a range of tokens)."""
+    tok_seq: np.ndarray
+    tok_pos: np.ndarray
+    k_new: torch.Tensor
+    v_new: torch.Tensor
+
+
 def extend(ls: Lockstep, job: JobState, new_lens: np.ndarray, seed: int, on_device_values: bool = False,
-           stream=None, bank: Optional[Dict[str, torch.Tensor]] = None):
+           stream=None, bank: Optional[Dict[str, torch.Tensor]] = None, record: Optional[List[AppendRecord]] = None):
     """Grow every sequence of `job` to new_lens tokens: allocate blocks (both sides, ids must
     agree), draw K/V for the new tokens, append on the GPU and - for sampled sequences - into
-    the oracle.  Returns the (k_new, v_new, tok_seq, tok_pos) device tensors of the call."""
+    the oracle.  With `record` the oracle is not fed now; the call's inputs are appended to the
+    list instead (see decode_check_streaming).  Returns the (k_new, v_new, tok_seq, tok_pos)
+    device tensors of the call."""
     new_lens = np.asarray(new_lens, dtype=np.int32)
     assert (new_lens >= job.lens).all()
     B, n_kv, d = ls.block_size, job.shape.n_kv_heads, ls.head_dim
@@ -144,12 +157,71 @@ def extend(ls: Lockstep, job: JobState, new_lens: np.ndarray, seed: int, on_devi
     tp_dev = torch.from_numpy(tok_pos).to(ls.device)
     mx.mux_kv_append(ls.lib, k_new, v_new, ts_dev, tp_dev, job.tables_dev, stream=stream)
     keep = job.sampled[tok_seq]
-    if keep.any():
+    if record is not None:
+        record.append(AppendRecord(tok_seq, tok_pos, k_new, v_new))
+    elif keep.any():
         idx = torch.from_numpy(np.nonzero(keep)[0]).to(ls.device)
         k_h, v_h = to_oracle(k_new.index_select(0, idx)), to_oracle(v_new.index_select(0, idx))
         ls.orc.kv_append(k_h, v_h, tok_seq[keep], tok_pos[keep], job.tables)
     job.lens = new_lens.copy()
     return k_new, v_new, ts_dev, tp_dev
+
+
+def seq_slices(lens: np.ndarray, bytes_per_token: int, slice_bytes: int):
+    """Cut sequences 0..n-1 into consecutive slices [s0, s1) of at most slice_bytes of K/V
+    (always at least one sequence)."""
+    s0, n = 0, int(lens.size)
+    while s0 < n:
+        s1, tok = s0, 0
+        while s1 < n and (s1 == s0 or (tok + int(lens[s1])) * bytes_per_token <= slice_bytes):
+            tok += int(lens[s1])
+            s1 += 1
+        yield s0, s1
+        s0 = s1
+
+
+def feed_oracle_slice(ls: Lockstep, job: JobState, records: List[AppendRecord], s0: int, s1: int) -> None:
+    """Append what `records` hold for sequences s0 .. s1-1 into the oracle's pool, at the ids
+    of the oracle's own block manager (job.tables: both managers returned the same ids)."""
+    for rec in records:
+        r0, r1 = int(np.searchsorted(rec.tok_seq, s0, "left")), int(np.searchsorted(rec.tok_seq, s1, "left"))
+        if r1 > r0:
+            ls.orc.kv_append(to_oracle(rec.k_new[r0:r1]), to_oracle(rec.v_new[r0:r1]), rec.tok_seq[r0:r1],
+                             rec.tok_pos[r0:r1], job.tables)
+
+
+def drop_oracle_slice(ls: Lockstep, job: JobState, s0: int, s1: int) -> None:
+    B = ls.block_size
+    ids = [job.tables[s, :, :(int(job.lens[s]) + B - 1) // B].ravel() for s in range(s0, s1)]
+    if ids:
+        ls.orc.drop_tiles(np.concatenate(ids))
+
+
+def decode_check_streaming(ls: Lockstep, job: JobState, records: List[AppendRecord], q: torch.Tensor, got: torch.Tensor,
+                           scale: float, slice_bytes: int = 256 << 20, progress=None) -> np.ndarray:
+    """EVERY sequence of `job` against the oracle, a slice of sequences at a time so that the
+    oracle's host pool stays small: feed the slice's recorded appends to the oracle, attend,
+    compare every output element, drop the slice's tiles.  `progress(text)` is called about every
+    20 s of a long check.  Returns the max-abs error per sequence."""
+    per_tok = 2 * job.shape.n_kv_heads * ls.head_dim * ls.elem
+    qh, gh = to_oracle(q), got.detach().float().cpu().numpy()
+    errs = np.zeros(job.n_seqs)
+    last = time.time()
+    for s0, s1 in seq_slices(job.lens, per_tok, slice_bytes):
+        if progress is not None and time.time() - last > 20.0:
+            last = time.time()
+            progress("oracle check of model %d: %d of %d sequences done" % (job.model_id, s0, job.n_seqs))
+        feed_oracle_slice(ls, job, records, s0, s1)
+        want = ls.orc.decode_attn(qh[s0:s1], job.tables[s0:s1], job.lens[s0:s1], job.shape.n_q_heads, scale)
+        drop_oracle_slice(ls, job, s0, s1)
+        g = gh[s0:s1]
+        assert np.isfinite(g).all(), "non-finite output in sequences %d..%d" % (s0, s1)
+        e = np.abs(g - want).reshape(s1 - s0, -1).max(axis=1)
+        errs[s0:s1] = e
+        bad = np.nonzero(e > tolerance(ls.dtype))[0]
+        assert bad.size == 0, "sequence %d (%d tokens): max-abs error %.3e > %.1e" % (
+            s0 + bad[0], job.lens[s0 + bad[0]], e[bad[0]], tolerance(ls.dtype))
+    return errs
 
 
 def make_q(ls: Lockstep, job: JobState, seed: int, n_rows: Optional[int] = None) -> torch.Tensor:

@@ -142,6 +142,58 @@ def test_scheduler_drives_kernels_like_the_oracle(case, driver, monkeypatch):
     print("adbs %s: %d requests, %d iterations, max abs err %.2e" % (case, rid, engine.iterations, worst), flush=True)
 
 
+def test_runner_on_a_pool_outside_the_matrix_core_path():
+    """Blocks of 12 tokens: prefill takes the generic path, whose scratch depends on the job (few
+    rows behind a long context are cut into many spans and need far more than the largest job).
+    The runner sizes its scratch once, for the worst job the scheduler can form; every job must
+    launch and match the oracle.  Long prompts against a small token budget make such jobs."""
+    print("[case] adbs runner, 12-token blocks (generic prefill path)", flush=True)
+    shapes = [wl.ModelShape("a", 8, 2, 128), wl.ModelShape("b", 4, 4, 128)]
+    d, B, n_blocks, max_seqs, max_blocks, budget = 128, 12, 3000, 5, 64, 64
+    rng = np.random.default_rng(12)
+    order = wl.placement_order(rng, n_blocks)
+    kv = torch.empty(n_blocks * 2 * B * d * 2, dtype=torch.uint8, device="cuda")
+    kv.view(torch.int16).fill_(0x7FC1)
+    pool = mx.mux_pool_create(kv, n_blocks, B, d, mx.MUX_BF16, order)
+    op = orc.OraclePool(n_blocks, B, d, init_free_order=order)
+    # the premise: some job shape needs more scratch than the largest job
+    largest = mx.mux_prefill_workspace_bytes(pool, max_seqs, max_blocks * B, max_blocks * B, 8, 2)
+    assert mx.mux_prefill_workspace_bytes(pool, 1, 600, 600, 8, 2) > largest       # one 600-token prompt of model a
+    assert mx.mux_prefill_workspace_bound(pool, max_blocks * B, max_blocks * B, 8, 2) > largest
+    src = SeededSource(shapes, d, max_blocks * B, seed=78)
+    engine = eng.NativeEngine(pool, shapes, max_seqs, max_blocks, budget, src)
+    os_ = orc.OracleScheduler(op, [s.n_kv_heads for s in shapes], max_seqs, max_blocks, budget)
+    scale = H.default_scale(d)
+    rid, worst, longest_prefill = 0, 0.0, 0
+    for it in range(200):
+        if it < 16:
+            arrivals = [(int(rng.integers(2)), int(rng.integers(1, 700)), int(rng.integers(1, 12))) for _ in range(int(rng.poisson(0.8)))]
+            if it in (0, 9):
+                arrivals.append((0, 600 + it, 3))      # the job shape that needs the most scratch
+            for m, plen, olen in arrivals:
+                engine.submit(m, rid, plen, olen)
+                assert os_.submit(m, rid, plen, olen) == 0
+                rid += 1
+        results = engine.step()
+        want_jobs = os_.step()
+        assert len(results) == len(want_jobs)
+        for (job, out), wj in zip(results, want_jobs):
+            assert job["kind"] == wj["kind"] and job["model"] == wj["model"]
+            for k in ("ids", "slots", "lens", "flags"):
+                assert np.array_equal(job[k], wj[k])
+            if job["kind"] == mx.MUX_JOB_PREEMPT:
+                continue
+            if job["kind"] == mx.MUX_JOB_PREFILL:
+                longest_prefill = max(longest_prefill, int(job["lens"].max()))
+            want = oracle_job_outputs(op, os_, src, shapes, wj, scale)
+            worst = max(worst, H.assert_close(out, want, "bf16", "job of model %d, iteration %d" % (job["model"], it)))
+        if it >= 16 and engine.idle():
+            break
+    torch.cuda.synchronize()
+    assert engine.idle() and rid > 6 and longest_prefill > 300
+    print("adbs, 12-token blocks: %d requests, longest prefill %d tokens, max abs err %.2e" % (rid, longest_prefill, worst), flush=True)
+
+
 def test_run_step_with_registered_buffers_equals_step_plus_launch():
     """mux_runner_run_step (one call per iteration, buffers registered once) does what mux_runner_step +
     mux_runner_launch per job do: same jobs, same bytes in the pool, same outputs, bit for bit."""

@@ -470,6 +470,48 @@ def test_fused_step_equals_append_then_decode(dtype, head_dim, block_size, n_q, 
     assert np.array_equal(got, want_img)
 
 
+@pytest.mark.parametrize("dtype,block_size,n_q,n_kv", [("bf16", 16, 4, 4), ("bf16", 16, 16, 2), ("fp32", 8, 2, 2), ("bf16", 32, 4, 2)])
+def test_fused_step_leaves_rows_beyond_the_length_bound_alone(dtype, block_size, n_q, n_kv):
+    """mux_decode_step with a max_ctx_len below some rows' lengths: those rows append nothing (not
+    one pool byte changes for them) and attend to their first max_ctx_len tokens, exactly as
+    mux_decode_attn does with the same bound; the other rows append and attend as usual."""
+    print("[case] fused step with rows beyond max_ctx_len, %s B=%d Hq=%d Hkv=%d" % (dtype, block_size, n_q, n_kv), flush=True)
+    d = 128
+    lens = np.array([40, 100, 33, 64, 7, 65], np.int32)       # lengths after this step's append
+    bound = 64                                                 # rows 1 and 5 lie beyond it
+    rng = np.random.Generator(np.random.PCG64(91))
+    ls = H.Lockstep(800, block_size, d, dtype, wl.placement_order(rng, 800))
+    st = H.open_job(ls, 0, wl.ModelShape("t", n_q, n_kv, d), lens.size, 160)
+    H.extend(ls, st, lens - 1, seed=41)                                      # history
+    wl.grow_tables(ls.alloc, 0, st.tables, lens - 1, lens, block_size, want_changed=False)
+    st.tables_dev.copy_(torch.from_numpy(st.tables))
+    before = ls.pool_image().copy()
+    k_new = wl.randn_values(42, (1, lens.size, n_kv, d), dtype).cuda()
+    v_new = wl.randn_values(43, (1, lens.size, n_kv, d), dtype).cuda()
+    q = wl.randn_values(44, (1, lens.size, n_q, d), dtype).cuda()
+    out = torch.full_like(q, float("nan"))
+    scale = H.default_scale(d)
+    ws = torch.empty(max(mx.mux_decode_step_workspace_bytes(ls.lib, 1, lens.size, n_q, n_kv, bound), 16), dtype=torch.uint8, device="cuda")
+    mx.mux_decode_step(ls.lib, out, q, k_new, v_new, st.tables_dev[None].contiguous(), torch.from_numpy(lens).cuda(), bound, scale, ws)
+    torch.cuda.synchronize()
+    inside = np.nonzero(lens <= bound)[0].astype(np.int32)
+    # pool: exactly the new rows of the sequences inside the bound were written
+    want_img = before.copy()
+    kb, vb = H.to_oracle(k_new[0]), H.to_oracle(v_new[0])
+    row16 = d * ls.elem // 2
+    for s in inside:
+        p = int(lens[s]) - 1
+        for h in range(n_kv):
+            bid = st.tables[s, h, p // block_size]
+            want_img[bid, 0, p % block_size] = kb[s, h].view(np.uint16).reshape(row16)
+            want_img[bid, 1, p % block_size] = vb[s, h].view(np.uint16).reshape(row16)
+    assert np.array_equal(ls.pool_image(), want_img)
+    # outputs: the oracle with the appended tokens for rows inside the bound, the first `bound` tokens for the others
+    ls.orc.kv_append(kb[inside], vb[inside], inside, lens[inside] - 1, st.tables)
+    want = ls.orc.decode_attn(H.to_oracle(q[0]), st.tables, np.minimum(lens, bound), n_q, scale)
+    H.assert_close(out[0], want, dtype)
+
+
 def test_decode_on_a_cu_masked_stream_is_bit_identical():
     """A stream restricted to a quarter of the compute units (spread over all XCDs) runs the same
     kernels: outputs equal those of an ordinary stream bit for bit, and the oracle's within tolerance."""
@@ -492,6 +534,33 @@ def test_decode_on_a_cu_masked_stream_is_bit_identical():
         ms.stream.synchronize()
         assert torch.equal(masked.view(torch.int16), plain.view(torch.int16))
         H.assert_close(masked, H.decode_oracle(ls, st, q, scale), "bf16")
+    finally:
+        torch.cuda.synchronize()
+        ms.close()
+
+
+@pytest.mark.parametrize("n_q,n_kv,share", [(8, 8, 4), (16, 2, 4), (8, 8, 2)])
+def test_prefill_on_a_cu_masked_stream_is_bit_identical(n_q, n_kv, share):
+    """The prefill kernel maps workgroup index to XCD to keep the row tiles of a (sequence, head)
+    on one L2; on a stream restricted to 1/share of the compute units (spread over all XCDs) that
+    only changes where a workgroup runs, never what it computes: outputs equal those of an
+    ordinary stream bit for bit (many row tiles per head, chunks behind cached prefixes, enough
+    workgroups for several rounds on the masked share), and the oracle's within tolerance."""
+    print("[case] prefill on a CU-masked stream Hq=%d Hkv=%d share 1/%d" % (n_q, n_kv, share), flush=True)
+    n_cu = mx.mux_device_cu_count()
+    assert n_cu >= 64
+    lens = np.array([700, 1300, 129, 512, 64, 1000, 333, 2048], np.int32)
+    q_starts = np.array([0, 788, 0, 256, 63, 0, 300, 1536], np.int32)
+    ls, job, q, plain, want = _prefill_case("bf16", 128, 16, n_q, n_kv, lens, q_starts, seed=70 + n_q)
+    q_lens = lens - q_starts
+    ms = mx.MaskedStream(range(n_cu // share))
+    try:
+        with torch.cuda.stream(ms.stream):
+            masked = H.prefill_gpu(ls, job, q, q_lens, q_starts, H.default_scale(128), stream=ms.stream)
+        ms.stream.synchronize()
+        assert torch.equal(masked.view(torch.int16), plain.view(torch.int16))
+        err = H.assert_close(masked, want, "bf16")
+        print("max abs err %.2e" % err, flush=True)
     finally:
         torch.cuda.synchronize()
         ms.close()

@@ -278,3 +278,31 @@ def test_decode_plan_splits_only_where_whole_rows_cannot_fill_the_gpu():
     assert not is_split(128, 64, 8, 2048) and not is_split(50, 64, 8, 512)
     assert is_split(8, 32, 32, 8192) and is_split(128, 64, 8, 4097)
     assert not is_split(4096, 32, 32, 16)
+
+
+def test_workspace_bounds_cover_every_smaller_call():
+    """A runner or engine that allocates its scratch once must size it for the worst call, which
+    is not the largest one: few long rows are cut into many spans.  The bound functions must cover
+    every (rows, context) below their arguments - checked by a full sweep on a small range and at
+    sampled points on a large one - and be attained by some call."""
+    for dtype, B, hq, hkv in ((mx.MUX_FP32, 16, 8, 1), (mx.MUX_BF16, 12, 4, 4), (mx.MUX_BF16, 16, 32, 32), (mx.MUX_BF16, 16, 64, 8)):
+        pool = host_pool(64, B, 128, dtype)
+        max_rows, max_ctx = 40, 40 * B
+        bound = mx.mux_decode_workspace_bound(pool, max_rows, hq, hkv, max_ctx)
+        every = [mx.mux_decode_workspace_bytes(pool, r, hq, hkv, c) for r in range(1, max_rows + 1) for c in range(1, max_ctx + 1, 3)]
+        assert max(every) == bound
+        assert bound >= mx.mux_decode_workspace_bytes(pool, max_rows, hq, hkv, max_ctx)
+    # a prefill job of the generic path (fp32 pool): 1 031 rows behind a 1 024-token context need far more
+    # scratch than the largest job a scheduler with a 4 096-token budget and 256-block tables can form
+    pool = host_pool(64, 16, 128, mx.MUX_FP32)
+    largest = mx.mux_prefill_workspace_bytes(pool, 8, 4096, 4096, 8, 1)
+    small = mx.mux_prefill_workspace_bytes(pool, 2, 1031, 1024, 8, 1)
+    bound = mx.mux_prefill_workspace_bound(pool, 4096, 4096, 8, 1)
+    assert small > largest and bound >= small
+    rng = np.random.default_rng(3)
+    for _ in range(3000):
+        rows, ctx = int(rng.integers(1, 4097)), int(rng.integers(1, 4097))
+        assert mx.mux_prefill_workspace_bytes(pool, 1, rows, ctx, 8, 1) <= bound
+    # pools that run prefill on the matrix cores need no scratch at all
+    assert mx.mux_prefill_workspace_bound(host_pool(64, 16, 128, mx.MUX_BF16), 4096, 4096, 8, 1) == 0
+    assert mx.mux_decode_workspace_bound(pool, 0, 8, 1, 16) == 0 and mx.mux_decode_workspace_bound(pool, 4, 8, 3, 16) == 0

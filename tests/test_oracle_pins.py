@@ -336,3 +336,71 @@ def test_bf16_widening_matches_torch(oracle):
     pool.kv_append(bits, bits, np.zeros(64, np.int32), np.arange(64, dtype=np.int32), table)
     K, _ = pool.gather(table[0, 0], 64)
     assert np.array_equal(K, t.float().numpy()[:, 0])
+
+
+# ---------------------------------------------------------------------------------
+# streaming mode: dropping tiles, and checking a batch a slice of sequences at a time
+# ---------------------------------------------------------------------------------
+def test_drop_tiles_forgets_exactly_the_listed_blocks(oracle):
+    pool, tables, lens, q, k, v, tok_seq, tok_pos = make_case(oracle, 31, 3, 2, 2, 16, 4, [9, 4, 6])
+    before = pool.decode_attn(q, tables, lens, 2, 0.3)
+    ids_seq0 = tables[0, :, :3].ravel()
+    keep = {int(b): (pool.read_row(int(b), 0, 0).copy(), pool.read_row(int(b), 0, 1).copy())
+            for b in np.concatenate([tables[1, :, :1].ravel(), tables[2, :, :2].ravel()])}
+    n_free = pool.num_free()
+    pool.drop_tiles(ids_seq0)
+    for b in ids_seq0:                                   # the listed tiles are gone ...
+        with pytest.raises(oracle.OracleError) as e:
+            pool.read_row(int(b), 0, 0)
+        assert e.value.status == oracle.ERR_INVALID
+    with pytest.raises(oracle.OracleError):
+        pool.gather(tables[0, 0], 9)
+    for b, (kr, vr) in keep.items():                     # ... every other tile is untouched
+        assert np.array_equal(pool.read_row(b, 0, 0), kr) and np.array_equal(pool.read_row(b, 0, 1), vr)
+    assert pool.num_free() == n_free                     # dropping data is not freeing blocks
+    assert np.array_equal(pool.decode_attn(q[1:], tables[1:], lens[1:], 2, 0.3), before[1:])
+    with pytest.raises(oracle.OracleError) as e:         # bad id: INVALID
+        pool.drop_tiles(np.array([pool.num_blocks], np.int32))
+    assert e.value.status == oracle.ERR_INVALID
+    pool.drop_tiles(ids_seq0)                            # dropping twice is harmless
+    # appending the same rows again restores the outputs bit for bit
+    sel = tok_seq == 0
+    pool.kv_append(k[sel], v[sel], tok_seq[sel], tok_pos[sel], tables)
+    assert np.array_equal(pool.decode_attn(q, tables, lens, 2, 0.3), before)
+
+
+def test_sliced_check_equals_the_whole_batch_and_catches_a_planted_error(oracle):
+    """The full-size GPU tests feed the oracle a slice of sequences at a time; on a batch small
+    enough to hold at once, the sliced walk must reproduce the all-at-once oracle bit for bit,
+    leave no tile behind, and name the sequence of a planted wrong output."""
+    import types
+
+    import mux_harness as H
+
+    B, d, n_kv, n_q = 4, 16, 2, 4
+    lens = np.array([13, 1, 8, 0, 21, 5, 16], np.int32)
+    whole, tables, _, q, k, v, tok_seq, tok_pos = make_case(oracle, 47, lens.size, n_q, n_kv, d, B, lens, scramble=False)
+    want = whole.decode_attn(q, tables, lens, n_q, 0.25)
+    # the same appends as two recorded calls (history, then each sequence's last token), as CPU tensors
+    last = np.zeros(tok_seq.size, bool)
+    last[np.cumsum(lens[lens > 0]) - 1] = True
+    as_t = lambda a: torch.from_numpy(a.view(np.int16).copy()).view(torch.bfloat16)
+    recs = [H.AppendRecord(tok_seq[~last], tok_pos[~last], as_t(k[~last]), as_t(v[~last])),
+            H.AppendRecord(tok_seq[last], tok_pos[last], as_t(k[last]), as_t(v[last]))]
+    streamed = oracle.OraclePool(whole.num_blocks, B, d, oracle.BF16, None)
+    assert np.array_equal(streamed.alloc(0, int(tables.max()) + 1), np.arange(int(tables.max()) + 1))
+    ls = types.SimpleNamespace(orc=streamed, block_size=B, head_dim=d, elem=2, dtype="bf16")
+    job = H.JobState(0, wl.ModelShape("t", n_q, n_kv, d), lens, tables, None, np.zeros(lens.size, bool))
+    per_seq_bytes = 2 * n_kv * d * 2
+    slices = list(H.seq_slices(lens, per_seq_bytes, 20 * per_seq_bytes))
+    assert len(slices) >= 4 and slices[0][0] == 0 and slices[-1][1] == lens.size
+    assert all(a[1] == b[0] for a, b in zip(slices, slices[1:]))
+    errs = H.decode_check_streaming(ls, job, recs, as_t(q), torch.from_numpy(want), 0.25, slice_bytes=20 * per_seq_bytes)
+    assert errs.shape == (lens.size,) and not errs.any()          # bit-identical to the all-at-once oracle
+    for b in range(int(tables.max()) + 1):                         # nothing is left in the streamed pool
+        with pytest.raises(oracle.OracleError):
+            streamed.read_row(b, 0, 0)
+    wrong = want.copy()
+    wrong[4, 1, 3] += 0.05
+    with pytest.raises(AssertionError, match="sequence 4"):
+        H.decode_check_streaming(ls, job, recs, as_t(q), torch.from_numpy(wrong), 0.25, slice_bytes=20 * per_seq_bytes)
