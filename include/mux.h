@@ -54,7 +54,8 @@ typedef enum {
     MUX_ERR_NOMEM = -2,       /* not enough free blocks; ALL-OR-NOTHING: nothing changed */
     MUX_ERR_QUOTA = -3,       /* the request would take the model past its token-block quota; nothing changed */
     MUX_ERR_HIP = -4,         /* a HIP runtime call or kernel launch failed */
-    MUX_ERR_UNSUPPORTED = -5  /* shape or dtype outside what the kernels are built for */
+    MUX_ERR_UNSUPPORTED = -5, /* shape or dtype outside what the kernels are built for */
+    MUX_ERR_TOO_LARGE = -6    /* the call needs more scratch than the library's fixed scratch array holds */
 } mux_status_t;
 
 #define MUX_MAX_MODELS 1024 /* model_id must lie in [0, MUX_MAX_MODELS) */
@@ -177,6 +178,24 @@ MUX_API size_t mux_decode_workspace_bytes(const mux_pool_t *pool, int32_t n_seqs
  * sizing for the largest call alone is not enough.  Host arithmetic only; 0 for bad arguments. */
 MUX_API size_t mux_decode_workspace_bound(const mux_pool_t *pool, int32_t max_seqs, int32_t n_q_heads,
                                   int32_t n_kv_heads, int32_t max_ctx_len);
+
+/* ---------------------------------------------------------------------------------
+ * Decode attention without a workspace argument, for callers that cannot allocate device
+ * memory at all: code running under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and bit-identical results as
+ * mux_decode_attn; the call's scratch lives in a fixed array of MUX_STATIC_SCRATCH_BYTES that
+ * is part of the library's device image (every GPU the library runs on holds it until the
+ * process ends).  The call allocates nothing and frees nothing, on the host side too.
+ * A call whose mux_decode_workspace_bytes(...) exceeds MUX_STATIC_SCRATCH_BYTES is refused with
+ * MUX_ERR_TOO_LARGE and launches nothing.  Every call on one GPU uses that GPU's one array:
+ * two such calls must not overlap on a GPU (same stream, or ordered by events) - overlapping
+ * calls race on the scratch and give wrong outputs.  The array keeps the previous call's
+ * contents; nothing in it needs to start at zero and no call reads what another one left.
+ * ------------------------------------------------------------------------------- */
+#define MUX_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+MUX_API int mux_decode_attn_static(mux_pool_t *pool, void *out, const void *q, const int32_t *block_tables,
+                                   const int32_t *ctx_lens, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads,
+                                   int32_t max_blocks, int32_t max_ctx_len, float scale, void *stream);
 
 /* ---------------------------------------------------------------------------------
  * Fused decoding step (Section 3.4, Implementation: in one decoding step an engine fills the

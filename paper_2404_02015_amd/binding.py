@@ -17,7 +17,8 @@ import torch  # must be imported before libmux.so so both share one HIP runtime
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmux.so")
 
-MUX_OK, MUX_ERR_INVALID, MUX_ERR_NOMEM, MUX_ERR_QUOTA, MUX_ERR_HIP, MUX_ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+MUX_OK, MUX_ERR_INVALID, MUX_ERR_NOMEM, MUX_ERR_QUOTA, MUX_ERR_HIP, MUX_ERR_UNSUPPORTED, MUX_ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
+MUX_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 MUX_BF16, MUX_FP32 = 0, 1
 
 EXPORTS = [
@@ -30,7 +31,7 @@ EXPORTS = [
     "mux_device_cu_count", "mux_stream_create_masked", "mux_stream_destroy", "mux_probe_stream_read", "mux_probe_mfma",
     "mux_estimate_tpt", "mux_find_batch_size", "mux_runner_create", "mux_runner_destroy", "mux_runner_step",
     "mux_runner_launch", "mux_runner_launch_layer", "mux_runner_set_buffers", "mux_runner_run_step", "mux_runner_counts", "mux_runner_synchronize", "mux_runner_read_table",
-    "mux_decode_workspace_bound", "mux_prefill_workspace_bound",
+    "mux_decode_attn_static", "mux_decode_workspace_bound", "mux_prefill_workspace_bound",
 ]
 
 MUX_JOB_PREFILL, MUX_JOB_DECODE, MUX_JOB_PREEMPT = 1, 2, 3
@@ -107,6 +108,7 @@ def load() -> C.CDLL:
     L.mux_free_blocks.argtypes = [vp, i32, i64, vp]
     L.mux_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
     L.mux_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, sz, vp]
+    L.mux_decode_attn_static.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp]
     L.mux_decode_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     L.mux_decode_workspace_bytes.restype = sz
     L.mux_decode_workspace_bound.argtypes = [vp, i32, i32, i32, i32]
@@ -300,6 +302,18 @@ def mux_decode_attn(pool: Pool, out: torch.Tensor, q: torch.Tensor, block_tables
                                 _dev(block_tables, torch.int32), _dev(ctx_lens, torch.int32), n_seqs, n_q, n_kv,
                                 max_blocks, max_ctx_len, scale, _dev(workspace), ws_bytes, _stream(stream))
     _check(rc, "mux_decode_attn")
+
+
+def mux_decode_attn_static(pool: Pool, out: torch.Tensor, q: torch.Tensor, block_tables: torch.Tensor,
+                           ctx_lens: torch.Tensor, max_ctx_len: int, scale: float, stream=None) -> None:
+    n_seqs, n_q, d = q.shape
+    n_seqs2, n_kv, max_blocks = block_tables.shape
+    if d != pool.head_dim or n_seqs2 != n_seqs or out.shape != q.shape or ctx_lens.numel() != n_seqs:
+        raise MuxError(MUX_ERR_INVALID, "mux_decode_attn_static")
+    rc = load().mux_decode_attn_static(_device_pool(pool), _dev(out, pool.torch_dtype), _dev(q, pool.torch_dtype),
+                                       _dev(block_tables, torch.int32), _dev(ctx_lens, torch.int32), n_seqs, n_q, n_kv,
+                                       max_blocks, max_ctx_len, scale, _stream(stream))
+    _check(rc, "mux_decode_attn_static")
 
 
 def mux_decode_step_workspace_bytes(pool: Pool, n_layers: int, n_seqs: int, n_q_heads: int, n_kv_heads: int,

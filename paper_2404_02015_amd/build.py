@@ -17,7 +17,7 @@ CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libmux.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
 
-SOURCES = ["mux_api.cpp", "mux_sched.cpp", "mux_stream.cpp", "mux_estimator.cpp", "mux_probes.hip", "mux_runner.hip", "mux_kv_append.hip", "mux_decode_attn.hip", "mux_prefill_attn.hip"]
+SOURCES = ["mux_api.cpp", "mux_sched.cpp", "mux_stream.cpp", "mux_estimator.cpp", "mux_probes.hip", "mux_runner.hip", "mux_kv_append.hip", "mux_decode_attn.hip", "mux_prefill_attn.hip", "mux_static_scratch.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

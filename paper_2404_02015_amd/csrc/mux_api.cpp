@@ -380,6 +380,7 @@ const char *mux_status_string(int status)
         case MUX_ERR_QUOTA: return "MUX_ERR_QUOTA";
         case MUX_ERR_HIP: return "MUX_ERR_HIP";
         case MUX_ERR_UNSUPPORTED: return "MUX_ERR_UNSUPPORTED";
+        case MUX_ERR_TOO_LARGE: return "MUX_ERR_TOO_LARGE";
         default: return "MUX_ERR_UNKNOWN";
     }
 }

@@ -306,3 +306,18 @@ def test_workspace_bounds_cover_every_smaller_call():
     # pools that run prefill on the matrix cores need no scratch at all
     assert mx.mux_prefill_workspace_bound(host_pool(64, 16, 128, mx.MUX_BF16), 4096, 4096, 8, 1) == 0
     assert mx.mux_decode_workspace_bound(pool, 0, 8, 1, 16) == 0 and mx.mux_decode_workspace_bound(pool, 4, 8, 3, 16) == 0
+
+
+def test_static_scratch_call_refuses_oversized_launches_on_the_host():
+    """mux_decode_attn_static checks the launch against its fixed scratch before it touches the GPU."""
+    pool = host_pool(64, 16, 128, mx.MUX_BF16)
+    n_seqs, n_q, n_kv, max_blocks = 4096, 32, 32, 1024
+    assert mx.mux_decode_workspace_bytes(pool, n_seqs, n_q, n_kv, max_blocks * 16) > mx.MUX_STATIC_SCRATCH_BYTES
+    buf = torch.zeros(64, dtype=torch.uint8)
+    rc = mx.load().mux_decode_attn_static(pool.handle, buf.data_ptr(), buf.data_ptr(), buf.data_ptr(), buf.data_ptr(),
+                                          n_seqs, n_q, n_kv, max_blocks, max_blocks * 16, 1.0, None)
+    assert rc == mx.MUX_ERR_TOO_LARGE and mx.status_string(rc) == "MUX_ERR_TOO_LARGE"
+    assert mx.load().mux_decode_attn_static(pool.handle, buf.data_ptr(), buf.data_ptr(), buf.data_ptr(), buf.data_ptr(),
+                                            4, 6, 4, 8, 64, 1.0, None) == mx.MUX_ERR_INVALID
+    header = open(os.path.join(ROOT, "include", "mux.h")).read()
+    assert "#define MUX_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)" in header and mx.MUX_STATIC_SCRATCH_BYTES == 32 * 1024 * 1024
