@@ -40,7 +40,9 @@ from paper_2404_02015_amd import workloads as wl  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per decode_attn launch on configuration 2, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (each scaled by a plain 1 GiB copy in the same run): 567 486 KiB x 2.000 fetched + 512 KiB written.
-MEASURED_TRAFFIC_CFG2 = {"bytes": 567567.7 * 1024 * 2.0 + 512.0 * 1024, "source": "profiles/decode_attn_config2_pmc.md"}
+MEASURED_TRAFFIC_CFG2 = {"bytes": 567567.7 * 1024 * 2.0 + 512.0 * 1024, "source": "profiles/decode_attn_config2_pmc.md",
+                         "note": "stored figure from the profile named in traffic_source (two rocprofv3 --pmc runs of this "
+                                 "script, 7 steps each), not counters of this run"}
 
 
 class DecodeModel:
@@ -256,60 +258,68 @@ def build_workload(cfg_index: int, total_steps: int, device: str = "cuda"):
     return w, pool, models, prefills
 
 
-def cpu_baseline(models, budget_s: float = 12.0):
-    """Time the CPU oracle (as it stands) on a bounded sample of the workload's sequences."""
+def cpu_baseline(models, budget_s: float = 12.0, single_core: bool = True):
+    """Time the CPU oracle (as it stands) on a bounded sample of the workload's sequences: from
+    every decode model of the configuration, its longest sequences up to ~1/8 of its tokens and
+    at most 192 MB of K/V (the oracle's pool holds the sample; the loop repeats passes over it
+    until the time budget is spent)."""
     from oracle import mux_oracle as orc
 
     orc.build()
-    m = models[0]
-    B, d, n_kv, n_q = m.B, m.shape.head_dim, m.shape.n_kv_heads, m.shape.n_q_heads
-    order = np.argsort(-m.lens, kind="stable")
-    # sample: sequences of the first model, longest first, until ~1/4 of its tokens
-    target = int(m.lens.astype(np.int64).sum() // 4)
-    pick, tok = [], 0
-    for s in order:
-        pick.append(int(s))
-        tok += int(m.lens[s])
-        if tok >= target:
-            break
-    pick = np.array(sorted(pick))
-    lens = m.lens[pick]
-    nb = int(((lens + B - 1) // B).sum()) * n_kv
-    pool = orc.OraclePool(nb + 8, B, d, orc.BF16)
-    tables = wl.build_tables(lambda mid, k: pool.alloc(mid, k), 0, lens, n_kv, B, int((lens.max() + B - 1) // B))
     rng = np.random.default_rng(1)
-    for i, L in enumerate(lens):  # values do not matter for the timing; N(0,1) in bf16
-        k = (rng.standard_normal((int(L), n_kv, d), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
-        v = (rng.standard_normal((int(L), n_kv, d), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
-        pool.kv_append(k, v, np.full(int(L), i, np.int32), np.arange(int(L), dtype=np.int32), tables)
-    q = (rng.standard_normal((len(pick), n_q, d), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
-    t0 = time.perf_counter()
-    reps = 0
-    while True:
-        pool.decode_attn(q, tables, lens, n_q, m.scale)
-        reps += 1
-        dt = time.perf_counter() - t0
-        if dt > budget_s:
-            break
-    kv_bytes = int(lens.astype(np.int64).sum()) * m.kv_bytes_per_token
+    samples, per_model = [], []
+    for m in models:
+        B, d, n_kv, n_q = m.B, m.shape.head_dim, m.shape.n_kv_heads, m.shape.n_q_heads
+        order = np.argsort(-m.lens, kind="stable")
+        target = min(int(m.lens.astype(np.int64).sum() // 8), (192 << 20) // m.kv_bytes_per_token)
+        pick, tok = [], 0
+        for s in order:
+            if pick and tok + int(m.lens[s]) > target:
+                break
+            pick.append(int(s))
+            tok += int(m.lens[s])
+        lens = m.lens[np.array(sorted(pick))]
+        nb = int(((lens + B - 1) // B).sum()) * n_kv
+        pool = orc.OraclePool(nb + 8, B, d, orc.BF16)
+        tables = wl.build_tables(lambda mid, k: pool.alloc(mid, k), 0, lens, n_kv, B, int((lens.max() + B - 1) // B))
+        for i, L in enumerate(lens):  # values do not matter for the timing; N(0,1) in bf16
+            k = (rng.standard_normal((int(L), n_kv, d), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+            v = (rng.standard_normal((int(L), n_kv, d), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+            pool.kv_append(k, v, np.full(int(L), i, np.int32), np.arange(int(L), dtype=np.int32), tables)
+        q = (rng.standard_normal((len(lens), n_q, d), dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+        samples.append((pool, q, tables, lens, n_q, m.scale, int(lens.astype(np.int64).sum()) * m.kv_bytes_per_token, m.shape.name))
     cores = orc.num_threads()
-    # the same sample on one core (a few passes)
-    orc.set_num_threads(1)
-    t1 = time.perf_counter()
-    reps1 = 0
-    while True:
-        pool.decode_attn(q, tables, lens, n_q, m.scale)
-        reps1 += 1
-        dt1 = time.perf_counter() - t1
-        if dt1 > budget_s / 4:
-            break
-    orc.set_num_threads(cores)
-    return {
-        "value": kv_bytes * reps / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-        "sample": "%d longest-first sequences of model 0 (%d tokens, %.1f MB of K/V), %d passes in %.1f s"
-                  % (len(pick), int(lens.sum()), kv_bytes / 1e6, reps, dt),
-        "single_core_value": kv_bytes * reps1 / dt1 / 1e9,
+
+    def run(budget):
+        """Passes over all models' samples until the budget is spent; returns bytes/s overall and per model."""
+        spent = [0.0] * len(samples)
+        reps = 0
+        t0 = time.perf_counter()
+        while True:
+            for i, (pool, q, tables, lens, n_q, scale, _, _) in enumerate(samples):
+                t1 = time.perf_counter()
+                pool.decode_attn(q, tables, lens, n_q, scale)
+                spent[i] += time.perf_counter() - t1
+            reps += 1
+            if time.perf_counter() - t0 > budget:
+                break
+        dt = time.perf_counter() - t0
+        total = sum(smp[6] for smp in samples)
+        return total * reps / dt / 1e9, [smp[6] * reps / max(t, 1e-9) / 1e9 for smp, t in zip(samples, spent)], reps, dt
+
+    all_gbs, per_gbs, reps, dt = run(budget_s)
+    out = {
+        "value": all_gbs, "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "sample": "longest sequences of every decode model up to 1/8 of its tokens and 192 MB: %s; %d passes in %.1f s"
+                  % ("; ".join("%s %d seqs, %d tokens, %.1f MB" % (smp[7], len(smp[3]), int(smp[3].sum()), smp[6] / 1e6) for smp in samples),
+                     reps, dt),
+        "per_model_GBps": [round(x, 2) for x in per_gbs],
     }
+    if single_core:
+        orc.set_num_threads(1)
+        out["single_core_value"] = run(budget_s / 4)[0]
+        orc.set_num_threads(cores)
+    return out
 
 
 def measure_ceilings(device: str = "cuda"):
@@ -504,6 +514,9 @@ def main() -> int:
     ap.add_argument("--adbs-scale", type=int, default=1,
                     help="--adbs: multiply pool size, sequence slots, arrivals per pass and prefill token budget")
     ap.add_argument("--no-solo", action="store_true", help="skip the per-model solo passes after the timed loop")
+    ap.add_argument("--models", type=int, default=0, help="run only the first N decode models of the configuration (0 = all)")
+    ap.add_argument("--sustain-ms", type=float, default=150.0,
+                    help="after the timed steps, keep stepping for about this long and report the rate of that longer window too")
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 1 GiB device copies after the timed loop")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -519,9 +532,12 @@ def main() -> int:
     mx.load()
     if args.adbs:
         return run_adbs(args)
-    SOLO_STEPS = 10
-    total = args.steps + args.warmup + SOLO_STEPS
+    SOLO_STEPS = 20
+    SUSTAIN_STEPS = 0 if args.sustain_ms <= 0 else {2: 400, 3: 300, 4: 150, 5: 15}.get(args.config, 100)
+    total = args.steps + args.warmup + SOLO_STEPS + SUSTAIN_STEPS
     w, pool, models, prefills = build_workload(args.config, total)
+    if args.models > 0:
+        models = models[:args.models]
     step_models = [] if args.only == "prefill" else models
     for m in models:
         m.fused = args.fused
@@ -577,18 +593,45 @@ def main() -> int:
     t_enqueued = time.perf_counter() - t0
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    # each decode model alone, for comparison with the colocated run
+    # the same loop over a longer window (the timed region above is only steps x ms_per_step long)
+    sustained = None
+    if SUSTAIN_STEPS > 0 and (step_models or prefills):
+        n_timed = [len(m.decode_events) for m in step_models]
+        t1 = time.perf_counter()
+        b1 = 0
+        n1 = 0
+        while n1 < SUSTAIN_STEPS and (time.perf_counter() - t1) * 1e3 < args.sustain_ms:
+            for pm in prefills:
+                pm.step(record=False)
+            for m in step_models:
+                b, ev = m.step(record=False, after=last)
+                last = ev if args.chain_decode else None
+                b1 += b
+            n1 += 1
+        torch.cuda.synchronize()
+        dt1 = time.perf_counter() - t1
+        sustained = {"steps": n1, "window_ms": dt1 * 1e3, "GBps": b1 / dt1 / 1e9, "ms_per_step": dt1 / n1 * 1e3}
+    # each decode model alone: nothing else runs on the GPU, so a launch's start-to-end duration is its own
     solo = []
-    if len(step_models) > 1 and not args.no_solo:
+    solo_durs, solo_algo = [], []
+    if step_models and not args.no_solo:
         for m in step_models:
             torch.cuda.synchronize()
+            n_before = len(m.decode_events)
             t1 = time.perf_counter()
             b1 = 0
             for _ in range(SOLO_STEPS):
-                b, _ = m.step(record=False)
+                b, _ = m.step(record=True)
                 b1 += b
             torch.cuda.synchronize()
-            solo.append({"model": m.shape.name, "seqs": m.n, "GBps": b1 / max(time.perf_counter() - t1, 1e-9) / 1e9})
+            wall = time.perf_counter() - t1
+            mine = m.decode_events[n_before:]
+            del m.decode_events[n_before:]
+            d = [e0.elapsed_time(e1) * 1e-3 for e0, e1, _ in mine]
+            solo_durs += d
+            solo_algo += [bb for _, _, bb in mine]
+            solo.append({"model": m.shape.name, "seqs": m.n, "GBps": b1 / max(wall, 1e-9) / 1e9,
+                         "launch_ms": float(np.mean(d) * 1e3), "launch_GBps": float(np.sum([bb for _, _, bb in mine]) / np.sum(d) / 1e9)})
     if args.pmc_calibration:
         # a plain copy of known size in the same process, for scaling rocprofv3 --pmc byte counters
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -618,17 +661,35 @@ def main() -> int:
             else:
                 cur_hi = max(cur_hi, hi)
         busy = (busy + cur_hi - cur_lo) * 1e-3
-        achieved = float(np.sum(algo) / busy / 1e9)
+        union = float(np.sum(algo) / busy / 1e9)             # bytes / time with at least one decode launch running
+        overlapped = float(np.sum(algo) / np.sum(durs) / 1e9)  # bytes / start-to-end durations, shared time counted per launch
+        if solo_durs:
+            # launches of the same models with nothing else on the GPU: the kernel's own duration
+            achieved, avg_ms, per_launch = float(np.sum(solo_algo) / np.sum(solo_durs) / 1e9), float(np.mean(solo_durs) * 1e3), float(np.mean(solo_algo))
+            basis = ("solo: %d launches per model after the timed region, one model at a time, HIP events on the model's stream "
+                     "around the decode launch (no other kernel runs meanwhile)" % SOLO_STEPS)
+        else:
+            achieved, avg_ms, per_launch = overlapped, float(np.mean(durs) * 1e3), float(np.mean(algo))
+            basis = "timed region: mean start-to-end duration of a decode launch (launches of different models may overlap)"
         roofline = {
             "kernel": "decode_attn_kernel (preceded by decode_plan_kernel, followed by decode_combine_kernel for split contexts), one launch per model per step",
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "frac_basis": basis,
             "traffic": MEASURED_TRAFFIC_CFG2["bytes"] if args.config == 2 else None,
             "traffic_source": MEASURED_TRAFFIC_CFG2["source"] if args.config == 2 else None,
-            "avg_launch_ms": busy / len(durs) * 1e3, "algorithmic_bytes_per_launch": float(np.mean(algo)),
-            "launches": len(durs), "raw_avg_launch_ms": float(np.mean(durs) * 1e3), "overlap": float(np.sum(durs) / busy),
-            "raw_median_launch_ms": float(np.median(durs) * 1e3), "raw_min_launch_ms": float(np.min(durs) * 1e3),
-            "note": "avg_launch_ms = time with at least one decode launch running / launches; raw_avg_launch_ms = mean "
-                    "start-to-end duration of a launch; overlap = their ratio (1.0 when launches never run concurrently)",
+            "traffic_note": MEASURED_TRAFFIC_CFG2["note"] if args.config == 2 else None,
+            "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": per_launch, "launches": len(solo_durs) or len(durs),
+            "frac_solo": achieved / HBM_PEAK_GBS if solo_durs else None,
+            "timed_region": {
+                "launches": len(durs), "algorithmic_bytes_per_launch": float(np.mean(algo)),
+                "frac_union": union / HBM_PEAK_GBS, "union_GBps": union, "union_ms_per_launch": busy / len(durs) * 1e3,
+                "frac_overlapped": overlapped / HBM_PEAK_GBS, "overlapped_avg_launch_ms": float(np.mean(durs) * 1e3),
+                "overlapped_median_launch_ms": float(np.median(durs) * 1e3), "overlapped_min_launch_ms": float(np.min(durs) * 1e3),
+                "overlap": float(np.sum(durs) / busy),
+                "note": "launches of different models run on different streams and overlap: union = bytes / time with at least "
+                        "one decode launch running; overlapped = bytes / mean start-to-end duration of a launch, which counts "
+                        "the time two launches share once per launch; overlap = their ratio",
+            },
         }
     n_seqs = sum(m.n for m in step_models)
     result = {
@@ -668,6 +729,8 @@ def main() -> int:
             result["dtype"] = "bf16"   # matrix products in bf16, accumulation in f32
             result["roofline"] = {"kernel": "prefill_attn_kernel", "bound": "mfma", "achieved": fl / t / 1e12, "peak": 2500.0,
                                   "unit": "TFLOP/s", "frac": fl / t / 2.5e15, "traffic": None}
+    if sustained:
+        result["sustained"] = sustained
     if solo:
         result["solo_decode"] = solo
     result["ceilings"] = measure_ceilings()
@@ -676,7 +739,7 @@ def main() -> int:
     if partition:
         result["config"]["cu_partition"] = partition
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(models)
+        result["cpu_baseline"] = cpu_baseline(models, single_core=args.config <= 2)
     print(json.dumps(result))
     return 0
 

@@ -10,8 +10,22 @@
  * blocks go back to the pool when the request ends.
  *
  * Conventions for every call
- *   - plain C linkage, no exceptions, no global state; the return value is a status
- *     (MUX_OK or a negative mux_status_t) unless stated otherwise.
+ *   - plain C linkage, no exceptions; the return value is a status (MUX_OK or a negative
+ *     mux_status_t) unless stated otherwise.  All state lives in the objects the calls
+ *     take (pool, scheduler, runner).  The library itself keeps three things per process,
+ *     none of which a caller can observe through results: a mutex-guarded table of
+ *     "workgroups of kernel K resident on device D" (a hardware property, asked from the
+ *     runtime on first use), the device addresses of mux_decode_attn_static's scratch
+ *     array, and the tuning switches below.
+ *   - tuning switches, read from the environment ONCE per process on first use (defaults
+ *     are what the published measurements use; none changes a result beyond summation
+ *     order): MUX_DECODE_SPAN_BLOCKS=n (blocks per span of a split context),
+ *     MUX_DECODE_WG_PER_CU=n (overrides the occupancy query), MUX_DECODE_PLAN_KERNEL=1
+ *     (always build the work list in a kernel of its own), MUX_DECODE_SPLIT_SHORT=1 (split
+ *     contexts by the piece-count rule alone), MUX_PREFILL_BUNDLE=n (row tiles of one
+ *     (sequence, head) dispatched back to back on one XCD), MUX_PREFILL_CB=1|2 (16-row
+ *     column blocks per wave), MUX_RUNNER_STAGE_ALWAYS=1 (read by mux_runner_create: job
+ *     arrays always travel through pinned staging memory).
  *   - "HOST" pointers are ordinary process memory, "DEVICE" pointers are HIP device
  *     memory of the GPU that is current when the call is made.
  *   - the caller owns the pool memory, block tables, Q/O tensors and workspaces; the
@@ -250,7 +264,6 @@ MUX_API size_t mux_prefill_workspace_bytes(const mux_pool_t *pool, int32_t n_seq
 MUX_API size_t mux_prefill_workspace_bound(const mux_pool_t *pool, int32_t max_total_q, int32_t max_ctx_len,
                                    int32_t n_q_heads, int32_t n_kv_heads);
 
-/* Human-readable name of a status code (static storage). */
 /* ---------------------------------------------------------------------------------
  * Batch scheduler (Section 3.3, Algorithm 3: adaptive batch scheduling).  Host code: it
  * owns the request queues and the block tables of the colocated models, takes blocks from
@@ -441,20 +454,7 @@ MUX_API double mux_estimate_tpt(int32_t n_models, const double *batch, const dou
 MUX_API int64_t mux_find_batch_size(double rate, int64_t max_batch, double p0, double p1, double d0, double d1,
                                     double gen_len, double other_prefill);
 
-/* ---------------------------------------------------------------------------------
- * Ceiling probes for reports (not part of the attention path): what the GPU at hand
- * sustains for a plain streaming read and for back-to-back matrix instructions.  Both only
- * enqueue on `stream`; the caller times them.
- * mux_probe_stream_read: `workgroups` x 4 waves read the whole 8 KiB chunks of `bytes`
- *   (>= 8192) of DEVICE memory at `buf` (16-byte aligned) once, 16 bytes per lane per load;
- *   `sink` = 4 bytes of DEVICE memory (never written in practice).
- * mux_probe_mfma: `workgroups` x 4 waves each issue iters x 16 (8 independent chains)
- *   v_mfma_f32_16x16x32_bf16; *flops (HOST, may be NULL) = floating-point operations of
- *   the launch; `sink` = 4 bytes of DEVICE memory.
- * ------------------------------------------------------------------------------- */
-MUX_API int mux_probe_stream_read(const void *buf, size_t bytes, void *sink, int32_t workgroups, void *stream);
-MUX_API int mux_probe_mfma(void *sink, int32_t workgroups, int32_t iters, double *flops, void *stream);
-
+/* Human-readable name of a status code (static storage). */
 MUX_API const char *mux_status_string(int status);
 
 #ifdef __cplusplus

@@ -29,6 +29,7 @@
 #include <map>
 #include <mutex>
 #include <type_traits>
+#include <utility>
 
 #include "mux_internal.h"
 
@@ -973,20 +974,25 @@ int env_int(const char *name, int fallback)
 }
 
 // Workgroups of `fn` the current GPU holds at once: compute units x the occupancy the runtime
-// reports for the kernel (asked once per kernel; MUX_DECODE_WG_PER_CU overrides it).  The
-// attention launch has exactly this many workgroups, so all of them start together and each
-// walks its own share of the work list.
+// reports for the kernel (asked once per (device, kernel); MUX_DECODE_WG_PER_CU overrides it).
+// The attention launch has exactly this many workgroups, so all of them start together and each
+// walks its own share of the work list.  The cache is the library's only process-wide state:
+// a read-mostly table of numbers that are properties of the hardware, guarded by a mutex.
 long long resident_workgroups(AttnKernel fn)
 {
     static std::mutex mu;
-    static std::map<AttnKernel, long long> known;
+    static std::map<std::pair<int, AttnKernel>, long long> known;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        dev = 0;
+    }
     std::lock_guard<std::mutex> lock(mu);
-    auto it = known.find(fn);
+    const auto key = std::make_pair(dev, fn);
+    auto it = known.find(key);
     if (it != known.end()) return it->second;
-    int dev = 0, cus = 0, per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        cus = 256;
+    int cus = 0, per_cu = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     static const int forced = env_int("MUX_DECODE_WG_PER_CU", 0);
     if (forced > 0)
         per_cu = forced;
@@ -996,7 +1002,7 @@ long long resident_workgroups(AttnKernel fn)
         per_cu = 2;
     (void)hipGetLastError();
     const long long n = static_cast<long long>(cus) * per_cu;
-    known[fn] = n;
+    known[key] = n;
     return n;
 }
 

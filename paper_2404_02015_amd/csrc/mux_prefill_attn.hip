@@ -29,8 +29,10 @@
 // front.  The accumulator is rescaled lazily: the reference maximum of a row only moves
 // when a score exceeds it by more than 2^kLazyBits, so most steps skip the rescale.
 //
-// Pools in fp32 or with a block size other than 16 take a slow generic path (each query row
-// handled like a decode step); see mux_launch_prefill_attn.
+// Blocks of 16 tokens have the block arithmetic folded at compile time; blocks of 8, 32, 64,
+// 128 or 256 tokens run the same kernel with it done at run time.  Pools in fp32 or with any
+// other block size take a slow generic path (each query row handled like a decode step); see
+// mux_launch_prefill_attn.
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
@@ -466,7 +468,7 @@ __global__ __launch_bounds__(kThreads, MUX_PREFILL_MIN_WGS) void prefill_attn_ke
 }
 
 template <int D, int HT, int CB, bool B16>
-void launch_mfma(PrefillArgs a, int max_q_len, hipStream_t st)
+hipError_t launch_mfma(PrefillArgs a, int max_q_len, hipStream_t st)
 {
     constexpr int QT = 16 * CB * (kWaves / HT);
     a.n_row_tiles = (max_q_len + QT - 1) / QT;
@@ -480,30 +482,28 @@ void launch_mfma(PrefillArgs a, int max_q_len, hipStream_t st)
     const long long bundles = (a.n_row_tiles + a.tile_bundle - 1) / a.tile_bundle;
     const long long grid = (units + 7) / 8 * 8 * bundles * a.tile_bundle;   // see the blockIdx mapping in the kernel
     constexpr int kLds = kBufs * 2 * kKT * D * 2 + kMaxCachedIds * 4;
+    // more than 64 KiB of LDS per workgroup has to be granted once per kernel (asked on first use; a
+    // refusal is reported by every launch)
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_attn_kernel<D, HT, CB, B16>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-    (void)attr;   // more than 64 KiB of LDS per workgroup has to be granted once per kernel
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL((prefill_attn_kernel<D, HT, CB, B16>), dim3(static_cast<unsigned>(grid)), dim3(kThreads), kLds, st, a);
+    return hipGetLastError();
 }
 
 template <int D, int CB, bool B16>
-void launch_by_heads2(int ht, const PrefillArgs &a, int max_q_len, hipStream_t st)
+hipError_t launch_by_heads2(int ht, const PrefillArgs &a, int max_q_len, hipStream_t st)
 {
-    if (ht == 4)
-        launch_mfma<D, 4, CB, B16>(a, max_q_len, st);
-    else if (ht == 2)
-        launch_mfma<D, 2, CB, B16>(a, max_q_len, st);
-    else
-        launch_mfma<D, 1, CB, B16>(a, max_q_len, st);
+    if (ht == 4) return launch_mfma<D, 4, CB, B16>(a, max_q_len, st);
+    if (ht == 2) return launch_mfma<D, 2, CB, B16>(a, max_q_len, st);
+    return launch_mfma<D, 1, CB, B16>(a, max_q_len, st);
 }
 
 template <int D, int CB>
-void launch_by_heads(int ht, const PrefillArgs &a, int max_q_len, hipStream_t st)
+hipError_t launch_by_heads(int ht, const PrefillArgs &a, int max_q_len, hipStream_t st)
 {
-    if (a.log2_block == 4)
-        launch_by_heads2<D, CB, true>(ht, a, max_q_len, st);
-    else
-        launch_by_heads2<D, CB, false>(ht, a, max_q_len, st);
+    if (a.log2_block == 4) return launch_by_heads2<D, CB, true>(ht, a, max_q_len, st);
+    return launch_by_heads2<D, CB, false>(ht, a, max_q_len, st);
 }
 
 }  // namespace
@@ -564,14 +564,16 @@ int mux_launch_prefill_attn(const mux_pool *pool, void *out, const void *q, cons
     const long long grid = ((max_q_len + rows_per_wg - 1) / rows_per_wg + 1) * (static_cast<long long>(n_seqs) * n_kv_heads * ((group + ht - 1) / ht) + 7);
     if (grid > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (pool->head_dim == 128) {
-        if (cb == 2) launch_by_heads<128, 2>(ht, a, max_q_len, st);
-        else launch_by_heads<128, 1>(ht, a, max_q_len, st);
-    } else if (pool->head_dim == 64) {
-        if (cb == 2) launch_by_heads<64, 2>(ht, a, max_q_len, st);
-        else launch_by_heads<64, 1>(ht, a, max_q_len, st);
-    } else {
+    hipError_t rc;
+    if (pool->head_dim == 128)
+        rc = cb == 2 ? launch_by_heads<128, 2>(ht, a, max_q_len, st) : launch_by_heads<128, 1>(ht, a, max_q_len, st);
+    else if (pool->head_dim == 64)
+        rc = cb == 2 ? launch_by_heads<64, 2>(ht, a, max_q_len, st) : launch_by_heads<64, 1>(ht, a, max_q_len, st);
+    else
         return MUX_ERR_UNSUPPORTED;
+    if (rc != hipSuccess) {
+        (void)hipGetLastError();
+        return MUX_ERR_HIP;
     }
-    return hipGetLastError() == hipSuccess ? MUX_OK : MUX_ERR_HIP;
+    return MUX_OK;
 }

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include "mux_internal.h"
+#include "mux_probes.h"
 
 namespace {
 

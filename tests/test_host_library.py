@@ -33,9 +33,17 @@ def host_pool(num_blocks, block_size=16, head_dim=128, dtype=mx.MUX_BF16, order=
 
 
 def test_every_declared_symbol_is_exported():
-    header = open(os.path.join(ROOT, "include", "mux.h")).read()
-    declared = re.findall(r"MUX_API\s+[\w\s\*]+?\b(mux_\w+)\s*\(", header)
-    assert len(declared) >= 13 and set(declared) == set(mx.EXPORTS)
+    import glob
+
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert [os.path.basename(h) for h in headers] == ["mux.h", "mux_probes.h"]
+    declared = []
+    for h in headers:
+        declared += re.findall(r"MUX_API\s+[\w\s\*]+?\b(mux_\w+)\s*\(", open(h).read())
+    assert len(declared) >= 13 and set(declared) == set(mx.EXPORTS) and len(declared) == len(set(declared))
+    # the measurement probes live in a header of their own: the product boundary is mux.h
+    product = re.findall(r"MUX_API\s+[\w\s\*]+?\b(mux_\w+)\s*\(", open(headers[0]).read())
+    assert not [n for n in product if n.startswith("mux_probe")]
     lib = mx.load()
     for name in declared:
         assert getattr(lib, name) is not None
