@@ -223,11 +223,21 @@ class PrefillModel:
                 self.events.append((e0, e1, st["flops"], st["kv_bytes"]))
 
 
-def build_workload(cfg_index: int, total_steps: int, device: str = "cuda"):
-    """Pool, decode models and (configuration 4) the prefill model of one configuration."""
+def build_workload(cfg_index: int, total_steps: int, device: str = "cuda", prefill_override=None, with_decode: bool = True):
+    """Pool, decode models and (configuration 4) the prefill model of one configuration.
+    prefill_override = (prompts, tokens per prompt, chunk) replaces the prefill model's prompts."""
     w = wl.config(cfg_index)
-    decode_jobs = [j for j in w.jobs if j.kind == "decode"]
+    if prefill_override is not None:
+        n, length, chunk = prefill_override
+        for j in w.jobs:
+            if j.kind == "prefill":
+                j.lens = np.full(n, length, dtype=np.int32)
+                j.chunk = chunk
+        w.num_blocks = max(w.num_blocks, int(w.demand_blocks() * 1.25) // 8192 * 8192 + 8192)
+    decode_jobs = [j for j in w.jobs if j.kind == "decode"] if with_decode else []
     prefill_jobs = [j for j in w.jobs if j.kind == "prefill"]
+    if not with_decode:
+        w.jobs = prefill_jobs
     growth = sum(j.n_seqs * j.shape.n_kv_heads * (total_steps // w.block_size + 2) for j in decode_jobs)
     block_bytes = 2 * w.block_size * w.head_dim * 2
     bank = None
@@ -488,6 +498,115 @@ def run_adbs(args) -> int:
     return 0
 
 
+def run_estimate(args) -> int:
+    """The throughput estimator (Section 3.3, Eq. 3; Appendix A.2) fed by latencies measured on this
+    GPU.  For the shapes of configuration 4 - a 13B-shaped LLM prefilling next to 7B- and
+    65B-GQA-shaped LLMs that decode - the attention path of ONE layer is timed at four batch
+    sizes per phase (prefill: prompts of 1 280 tokens, the mean of U[512, 2048]; decoding: contexts
+    U[256, 4096]) and fitted as lines in the batch size, t_p(b) = p0 + p1 b and t_d(b) = d0 + d1 b.
+    With a generation length of 338 tokens (the paper's ShareGPT mean) mux_find_batch_size then gives,
+    per decoding LLM, the batch that meets a request rate; the rates tried are fractions of the rate
+    the LLM can sustain at all, 1 / (d1 l_o) requests/s.  Beside each prediction: the measured
+    throughput at that batch size (its own t_d measured, not the fit)."""
+    dev, B, d = "cuda", 16, 128
+    gen_len = 338.0
+    rng = np.random.default_rng(4)
+
+    def make_pool(n_blocks):
+        kv = torch.empty(n_blocks * 2 * B * d * 2, dtype=torch.uint8, device=dev)
+        return kv, mx.mux_pool_create(kv, n_blocks, B, d, mx.MUX_BF16, wl.placement_order(rng, n_blocks))
+
+    def time_it(fn, reps=20):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    def decode_latency(shape, b):
+        lens = rng.integers(256, 4097, b).astype(np.int32)
+        nb = int(((lens + B - 1) // B).sum()) * shape.n_kv_heads + 64
+        kv, pool = make_pool(nb)
+        mb = int((lens.max() + B - 1) // B)
+        tables = torch.from_numpy(wl.build_tables(lambda m, k: mx.mux_alloc_blocks(pool, m, k), 0, lens, shape.n_kv_heads, B, mb)).to(dev)
+        q = torch.randn(b, shape.n_q_heads, d, device=dev).to(torch.bfloat16)
+        k = torch.randn(b, shape.n_kv_heads, d, device=dev).to(torch.bfloat16)
+        out = torch.empty_like(q)
+        lens_dev = torch.from_numpy(lens).to(dev)
+        ws = torch.empty(max(mx.mux_decode_step_workspace_bytes(pool, 1, b, shape.n_q_heads, shape.n_kv_heads, int(lens.max())), 16),
+                         dtype=torch.uint8, device=dev)
+        kv.zero_()      # values do not matter for the timing, but the pool must not hold NaN patterns
+        t = time_it(lambda: mx.mux_decode_step(pool, out[None], q[None], k[None], k[None], tables[None], lens_dev, int(lens.max()),
+                                               1.0 / math.sqrt(d), ws))
+        mx.mux_pool_destroy(pool)
+        return t
+
+    def prefill_latency(shape, b, plen=1280):
+        nb = b * (plen // B) * shape.n_kv_heads + 64
+        kv, pool = make_pool(nb)
+        lens = np.full(b, plen, np.int32)
+        tables = torch.from_numpy(wl.build_tables(lambda m, k: mx.mux_alloc_blocks(pool, m, k), 0, lens, shape.n_kv_heads, B, plen // B)).to(dev)
+        n = b * plen
+        q = torch.randn(n, shape.n_q_heads, d, device=dev).to(torch.bfloat16)
+        k = torch.randn(n, shape.n_kv_heads, d, device=dev).to(torch.bfloat16)
+        out = torch.empty_like(q)
+        seq = torch.arange(b, dtype=torch.int32, device=dev).repeat_interleave(plen).contiguous()
+        pos = torch.arange(plen, dtype=torch.int32, device=dev).repeat(b).contiguous()
+        cu = torch.arange(0, n + 1, plen, dtype=torch.int32, device=dev)
+        start = torch.zeros(b, dtype=torch.int32, device=dev)
+
+        def step():
+            mx.mux_kv_append(pool, k, k, seq, pos, tables)
+            mx.mux_prefill_attn(pool, out, q, cu, start, tables, plen, plen, 1.0 / math.sqrt(d), None)
+
+        t = time_it(step, reps=10)
+        mx.mux_pool_destroy(pool)
+        return t
+
+    def fit(bs, ts):
+        c1, c0 = np.polyfit(np.asarray(bs, float), np.asarray(ts, float), 1)
+        return max(float(c0), 0.0), max(float(c1), 0.0)
+
+    p_bs = [1, 2, 4, 8]
+    p_ts = [prefill_latency(wl.LLAMA_13B, b) for b in p_bs]
+    p0, p1 = fit(p_bs, p_ts)
+    other_prefill = p0 + p1 * 4          # the colocated prefilling LLM's batch of four prompts
+    report = {"prefill_13B": {"batch": p_bs, "seconds": p_ts, "fit": [p0, p1]}, "decoders": []}
+    d_bs = [16, 32, 64, 128]
+    for shape in (wl.LLAMA_7B, wl.GQA_65B):
+        d_ts = [decode_latency(shape, b) for b in d_bs]
+        d0, d1 = fit(d_bs, d_ts)
+        own_p = [prefill_latency(shape, b) for b in (1, 4)]
+        q1 = (own_p[1] - own_p[0]) / 3.0
+        q0 = max(own_p[0] - q1, 0.0)
+        ceiling = 1.0 / (d1 * gen_len) if d1 > 0 else float("inf")      # requests/s as b grows without bound
+        rows = []
+        for frac in (0.25, 0.5, 0.75, 0.9):
+            rate = frac * ceiling
+            b = int(mx.mux_find_batch_size(rate, 4096, q0, q1, d0, d1, gen_len, other_prefill))
+            row = {"rate_req_s": rate, "fraction_of_ceiling": frac, "batch_from_eq3": b}
+            if 0 < b <= 512:
+                td = decode_latency(shape, b)
+                tp = q0 + q1 * b
+                tput = b / (other_prefill + tp + td * gen_len)
+                row.update({"measured_t_d_s": td, "measured_req_s_at_that_batch": tput, "meets_rate": bool(tput >= 0.97 * rate)})
+            rows.append(row)
+        report["decoders"].append({"model": shape.name, "batch": d_bs, "seconds": d_ts, "fit": [d0, d1], "own_prefill_fit": [q0, q1],
+                                   "ceiling_req_s": ceiling, "rates": rows})
+    line = {"metric": "Eq. 3 estimator fed by measured attention latencies (one layer)", "value": report["decoders"][0]["ceiling_req_s"],
+            "unit": "requests/s", "n_gpus": 1, "higher_is_better": True, "dtype": "f32", "storage_dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "configuration 4's shapes: 13B-shaped prefill (prompts of 1 280 tokens) next to 7B- and 65B-GQA-shaped decoding "
+                                   "(contexts U[256, 4096]); generation length 338; latencies of the attention path of one layer"},
+            "estimate": report}
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -513,6 +632,12 @@ def main() -> int:
                     help="--adbs: models with all their layers (40 / 32 / 32) and a pool 32x as large: whole-model K/V traffic")
     ap.add_argument("--adbs-scale", type=int, default=1,
                     help="--adbs: multiply pool size, sequence slots, arrivals per pass and prefill token budget")
+    ap.add_argument("--prefill-prompts", type=int, default=0,
+                    help="--config 4 --only prefill: N prompts of --prefill-len tokens in chunks of --prefill-chunk instead of the configuration's 8")
+    ap.add_argument("--prefill-len", type=int, default=0)
+    ap.add_argument("--prefill-chunk", type=int, default=0)
+    ap.add_argument("--estimate", action="store_true",
+                    help="measure prefill / decode latencies against the batch size and feed the Eq. 3 estimator (prints its own JSON line)")
     ap.add_argument("--no-solo", action="store_true", help="skip the per-model solo passes after the timed loop")
     ap.add_argument("--models", type=int, default=0, help="run only the first N decode models of the configuration (0 = all)")
     ap.add_argument("--sustain-ms", type=float, default=150.0,
@@ -532,10 +657,18 @@ def main() -> int:
     mx.load()
     if args.adbs:
         return run_adbs(args)
+    if args.estimate:
+        return run_estimate(args)
     SOLO_STEPS = 20
     SUSTAIN_STEPS = 0 if args.sustain_ms <= 0 else {2: 400, 3: 300, 4: 150, 5: 15}.get(args.config, 100)
     total = args.steps + args.warmup + SOLO_STEPS + SUSTAIN_STEPS
-    w, pool, models, prefills = build_workload(args.config, total)
+    override = None
+    if args.prefill_prompts > 0:
+        if args.config != 4 or args.only != "prefill" or args.prefill_len <= 0:
+            print("bench.py: --prefill-prompts needs --config 4 --only prefill --prefill-len L", file=sys.stderr)
+            return 2
+        override = (args.prefill_prompts, args.prefill_len, args.prefill_chunk if args.prefill_chunk > 0 else args.prefill_len)
+    w, pool, models, prefills = build_workload(args.config, total, prefill_override=override, with_decode=args.only != "prefill")
     if args.models > 0:
         models = models[:args.models]
     step_models = [] if args.only == "prefill" else models
@@ -701,7 +834,8 @@ def main() -> int:
             "workload": "config %d: %s; block_size %d; %d head-blocks, seeded random placement; per step and model: "
                         "alloc -> table patch -> %s, one stream per model, decode kernels %s"
                         % (args.config, ", ".join(["%s x%d decoding seqs" % (m.shape.name, m.n) for m in models] +
-                                                  ["%s x%d prompts in chunks of %d" % (pm.shape.name, pm.job.n_seqs, pm.job.chunk)
+                                                  ["%s x%d prompts%s in chunks of %d" % (pm.shape.name, pm.job.n_seqs, " of %d tokens" % args.prefill_len
+                                                                                       if override else "", pm.job.chunk)
                                                    for pm in prefills]), w.block_size, pool.num_blocks,
                            "decode_step (fused append + attention)" if args.fused else "kv_append(1 token/seq) -> decode_attn",
                            "chained by events" if args.chain_decode else "unordered across streams"),
@@ -738,7 +872,7 @@ def main() -> int:
     result["kv_append"] = measure_append()
     if partition:
         result["config"]["cu_partition"] = partition
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and models:
         result["cpu_baseline"] = cpu_baseline(models, single_core=args.config <= 2)
     print(json.dumps(result))
     return 0
