@@ -237,7 +237,9 @@ __global__ __launch_bounds__(256) void decode_plan_kernel(const DecodeArgs a)
 // behind one waits for it.
 struct WorkCursor {
     int round;        // pieces this workgroup has taken so far
-    const int *rows;  // LDS: row of every rank, when the workgroup ranks the rows itself
+    // LDS, when the workgroup orders the work itself: the row of every rank (rank_rows), or the
+    // units as row | span << 16 with their number behind them (list_units)
+    const int *rows;
 };
 
 // Short launches (one span per row, at most kMaxRankedRows rows) skip the plan kernel: every
@@ -268,6 +270,44 @@ __device__ __forceinline__ void rank_rows(const DecodeArgs &a, int tid, int *sm_
     // the barrier at the top of take_work makes sm_row visible
 }
 
+// Launches of few rows whose contexts ARE cut into spans skip the plan kernel too: every workgroup
+// builds the same list as decode_plan_kernel in LDS - the full spans in row order, then every
+// row's last span by falling length - with one row per thread: a thread's place among the full
+// spans is the number of full spans of the rows before it, its place among the last spans the
+// number of rows whose last span is longer (or as long and earlier).  Everything is a pure
+// function of the context lengths, so all workgroups arrive at the same list.
+constexpr int kMaxInlineUnits = 1024;
+
+__device__ __forceinline__ void list_units(const DecodeArgs &a, int tid, int *sm_shape, int *sm_units)
+{
+    const int n_rows = a.n_seqs * a.n_layers;
+    const int span = a.span_blocks;
+    int full = 0, rem = 0;
+    if (tid < n_rows) {
+        int table_row, len;
+        resolve_row(a, tid, table_row, len);
+        const int blocks = (len + a.block_size - 1) / a.block_size;
+        full = blocks > 0 ? (blocks - 1) / span : 0;   // full spans before the last one
+        rem = blocks - full * span;                    // blocks in the last one
+        sm_shape[tid] = full << 16 | rem;
+    }
+    __syncthreads();
+    int before = 0, all_full = 0, rank = 0;
+    for (int j = 0; j < n_rows; ++j) {
+        const int shape = sm_shape[j];
+        const int f = shape >> 16, r = shape & 0xffff;
+        all_full += f;
+        before += j < tid ? f : 0;
+        rank += (r > rem || (r == rem && j < tid)) ? 1 : 0;
+    }
+    if (tid < n_rows) {
+        for (int p = 0; p < full; ++p) sm_units[before + p] = tid | p << 16;
+        sm_units[all_full + rank] = tid | full << 16;
+    }
+    if (tid == 0) sm_units[kMaxInlineUnits] = all_full + n_rows;
+    // the barrier at the top of take_work makes the list visible
+}
+
 __device__ __forceinline__ bool take_work(const DecodeArgs &a, int tid, WorkCursor &cur, bool first, int &row, int &split,
                                           int &kvh, int &pass)
 {
@@ -277,10 +317,15 @@ __device__ __forceinline__ bool take_work(const DecodeArgs &a, int tid, WorkCurs
     int w = k * G + ((k & 1) ? G - 1 - static_cast<int>(blockIdx.x) : static_cast<int>(blockIdx.x));
     cur.round = k + 1;
     const int per_unit = a.n_kv_heads * a.n_passes;
-    if (a.plan == nullptr) {
+    if (a.plan == nullptr && a.n_splits == 1) {
         if (w / per_unit >= a.n_seqs * a.n_layers) return false;
         row = __builtin_amdgcn_readfirstlane(cur.rows[w / per_unit]);
         split = 0;
+    } else if (a.plan == nullptr) {
+        if (w / per_unit >= __builtin_amdgcn_readfirstlane(cur.rows[kMaxInlineUnits])) return false;
+        const int u = __builtin_amdgcn_readfirstlane(cur.rows[w / per_unit]);
+        row = u & 0xffff;
+        split = u >> 16;
     } else {
         const int n_units = __builtin_amdgcn_readfirstlane(a.plan[1]);
         if (w / per_unit >= n_units) return false;
@@ -354,8 +399,11 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     const int c0 = (lane % LPR) * EPL;    // first head dimension of this lane
 
     int s, split, kvh, pass;   // s: row of q / out / the table
-    __shared__ int sm_rank_len[kMaxRankedRows], sm_rank_row[kMaxRankedRows];
-    rank_rows(a, tid, sm_rank_len, sm_rank_row);
+    __shared__ int sm_rank_len[kMaxRankedRows], sm_rank_row[kMaxInlineUnits + 1];
+    if (a.plan == nullptr && a.n_splits > 1)
+        list_units(a, tid, sm_rank_len, sm_rank_row);
+    else
+        rank_rows(a, tid, sm_rank_len, sm_rank_row);
     WorkCursor cursor{0, sm_rank_row};
     for (bool first = true; take_work(a, tid, cursor, first, s, split, kvh, pass); first = false) {
     // Block ids of this wave: block blk_lo + wave + kWaves * j sits in lane j.  The load does
@@ -734,8 +782,11 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
     const int g = lane >> 4, c = lane & 15;
 
     int s, split, kvh, pass;   // s: row of q / out / the table
-    __shared__ int sm_rank_len[kMaxRankedRows], sm_rank_row[kMaxRankedRows];
-    rank_rows(a, tid, sm_rank_len, sm_rank_row);
+    __shared__ int sm_rank_len[kMaxRankedRows], sm_rank_row[kMaxInlineUnits + 1];
+    if (a.plan == nullptr && a.n_splits > 1)
+        list_units(a, tid, sm_rank_len, sm_rank_row);
+    else
+        rank_rows(a, tid, sm_rank_len, sm_rank_row);
     WorkCursor cursor{0, sm_rank_row};
     for (bool first = true; take_work(a, tid, cursor, first, s, split, kvh, pass); first = false) {
     const int blk_lo = split * a.span_blocks;
@@ -1151,8 +1202,8 @@ int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, co
     const unsigned g = static_cast<unsigned>(std::min<long long>(most, resident_workgroups(fn)));
     a.grid_wgs = static_cast<int>(g);
     static const int force_plan_kernel = env_int("MUX_DECODE_PLAN_KERNEL", 0);
-    if (plan.n_splits == 1 && n_rows <= kMaxRankedRows && !force_plan_kernel) {
-        a.plan = nullptr;   // the workgroups rank the rows themselves (see rank_rows)
+    if (n_rows <= kMaxRankedRows && n_rows * plan.n_splits <= kMaxInlineUnits && !force_plan_kernel) {
+        a.plan = nullptr;   // the workgroups order the work themselves (see rank_rows and list_units)
     } else {
         hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(256), 0, st, a);
         if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
