@@ -457,7 +457,7 @@ def run_adbs(args) -> int:
             engine = eng.NativeEngine(pool, shapes, max_seqs, max_blocks, budget, None,
                                       shared_stream=args.adbs_driver == "runner-one-stream", layers=layers, **kw)
         use = np.zeros(len(shapes))
-        rid, t0, tok0 = 0, None, 0
+        rid, t0, tok0, host_s = 0, None, 0, 0.0
         for it in range(warm + iters):
             if it == warm:
                 torch.cuda.synchronize()
@@ -466,8 +466,10 @@ def run_adbs(args) -> int:
                 for _ in range(int(rng.poisson(per_iter[m]))):
                     engine.submit(m, rid, int(rng.integers(64, 385)) * length_scale[m], int(rng.integers(32, 129)) * length_scale[m])
                     rid += 1
+            h0 = time.perf_counter()
             engine.step()
             if it >= warm:
+                host_s += time.perf_counter() - h0
                 use += [mx.mux_pool_num_used(pool, m) for m in range(len(shapes))]
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
@@ -475,6 +477,7 @@ def run_adbs(args) -> int:
         out[mode] = {
             "tokens_per_s": (engine.tokens() - tok0) / dt,
             "ms_per_iteration": dt / iters * 1e3,
+            "host_ms_per_iteration": host_s / iters * 1e3,     # scheduler pass + enqueueing its jobs, without waiting for the GPU
             "block_usage_share": [round(float(x), 4) for x in use / max(use.sum(), 1)],
             "mean_blocks_in_use": float(use.sum() / iters),
             "kv_GBps_decode_reads": float(use.sum() / iters) * 2 * B * d * 2 / (dt / iters) / 1e9,

@@ -135,15 +135,41 @@ struct DecodeArgs {
     // units as (row, split) pairs, longest first
     int *plan;
     int grid_wgs;   // workgroups of the attention launch
+    // A fused step whose small integer arrays ride in the kernel arguments, so that no kernel has to
+    // run ahead of this one to put them into device memory (inl_rows == n_seqs > 0; ctx_lens is not
+    // read then).  inl holds, for the n_seqs rows of a layer: the context length; then the index
+    // of the row's entry or -1; then, per entry, inl_heads block ids: the block that the row's new
+    // token has just opened, for every kv head of every layer of the model (this launch's first
+    // layer starts at inl_head0).  The id of such a block is taken from here instead of the table
+    // (where head pass 0 stores it for the steps to come).
+    int inl_rows, inl_heads, inl_head0;
+    int inl[MUX_INLINE_STEP_INTS];
 };
+static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
+
+// The id of the block that column `col` of row s (kv head kvh) refers to, when the step's arrays
+// ride in the arguments and the row's new token has just opened that block; `id` otherwise.  Head
+// pass 0 leaves the id in the table.  L: the row's context length (0 for a row that is not part of
+// the step, or whose context was cut at the launch's bound: its new token lies beyond the cut).
+__device__ __forceinline__ int inline_block_id(const DecodeArgs &a, int s, int kvh, int pass, int L, int col, int id,
+                                               const int *table_row)
+{
+    if (L <= 0) return id;
+    const int e = a.inl[a.n_seqs + s % a.n_seqs];
+    if (e < 0 || col != (L - 1) / a.block_size) return id;
+    id = a.inl[2 * a.n_seqs + e * a.inl_heads + a.inl_head0 + (s / a.n_seqs) * a.n_kv_heads + kvh];
+    if (pass == 0) const_cast<int *>(table_row)[col] = id;
+    return id;
+}
 
 // Row r of q/out -> (block-table row, context length).  The length is cut at max_ctx_len (the
 // host's bound, which sized the launch); *cut, when asked for, tells whether that happened.
+template <bool INL>
 __device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &table_row, int &len, bool *cut = nullptr)
 {
     if (a.cu_q_lens == nullptr) {
         table_row = r;
-        len = a.ctx_lens[r % a.n_seqs];
+        len = INL ? a.inl[r % a.n_seqs] : a.ctx_lens[r % a.n_seqs];
     } else {
         int lo = 0, hi = a.n_table_seqs - 1;  // last sequence whose first row is <= r
         while (lo < hi) {
@@ -165,6 +191,7 @@ __device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &tab
 // and the attention kernel is launched with exactly as many workgroups as are resident at once,
 // each of which walks a fixed share of that list (see take_work).  No workgroup is ever started
 // for an empty span, and the longest units are never started last.
+template <bool INL>
 __global__ __launch_bounds__(256) void decode_plan_kernel(const DecodeArgs a)
 {
     __shared__ int sm_scan[256];
@@ -176,7 +203,7 @@ __global__ __launch_bounds__(256) void decode_plan_kernel(const DecodeArgs a)
     int2 *units = reinterpret_cast<int2 *>(a.plan + 4);
     auto shape_of = [&](int r, int &full, int &rem) {   // full spans before the last one, blocks in the last one
         int table_row, len;
-        resolve_row(a, r, table_row, len);
+        resolve_row<INL>(a, r, table_row, len);
         const int blocks = (len + B - 1) / B;
         full = blocks > 0 ? (blocks - 1) / span : 0;
         rem = blocks - full * span;
@@ -248,13 +275,14 @@ struct WorkCursor {
 // That costs a few hundred cycles per workgroup and saves a dependent kernel launch per call.
 constexpr int kMaxRankedRows = kThreads;
 
+template <bool INL>
 __device__ __forceinline__ void rank_rows(const DecodeArgs &a, int tid, int *sm_len, int *sm_row)
 {
     if (a.plan != nullptr) return;
     const int n_rows = a.n_seqs * a.n_layers;
     if (tid < n_rows) {
         int table_row, len;
-        resolve_row(a, tid, table_row, len);
+        resolve_row<INL>(a, tid, table_row, len);
         sm_len[tid] = len;
     }
     __syncthreads();
@@ -278,6 +306,7 @@ __device__ __forceinline__ void rank_rows(const DecodeArgs &a, int tid, int *sm_
 // function of the context lengths, so all workgroups arrive at the same list.
 constexpr int kMaxInlineUnits = 1024;
 
+template <bool INL>
 __device__ __forceinline__ void list_units(const DecodeArgs &a, int tid, int *sm_shape, int *sm_units)
 {
     const int n_rows = a.n_seqs * a.n_layers;
@@ -285,7 +314,7 @@ __device__ __forceinline__ void list_units(const DecodeArgs &a, int tid, int *sm
     int full = 0, rem = 0;
     if (tid < n_rows) {
         int table_row, len;
-        resolve_row(a, tid, table_row, len);
+        resolve_row<INL>(a, tid, table_row, len);
         const int blocks = (len + a.block_size - 1) / a.block_size;
         full = blocks > 0 ? (blocks - 1) / span : 0;   // full spans before the last one
         rem = blocks - full * span;                    // blocks in the last one
@@ -376,7 +405,7 @@ __device__ __forceinline__ void merge_waves_and_store(const DecodeArgs &a, const
 
 // BF16: storage type; D: head size; BS: tokens per block at compile time (0 = run time);
 // GT: query heads of one KV group handled together.
-template <bool BF16, int D, int BS, int GT>
+template <bool BF16, int D, int BS, int GT, bool INL>
 __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_kernel(const DecodeArgs a)
 {
     constexpr int EB = BF16 ? 2 : 4;
@@ -401,9 +430,9 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     int s, split, kvh, pass;   // s: row of q / out / the table
     __shared__ int sm_rank_len[kMaxRankedRows], sm_rank_row[kMaxInlineUnits + 1];
     if (a.plan == nullptr && a.n_splits > 1)
-        list_units(a, tid, sm_rank_len, sm_rank_row);
+        list_units<INL>(a, tid, sm_rank_len, sm_rank_row);
     else
-        rank_rows(a, tid, sm_rank_len, sm_rank_row);
+        rank_rows<INL>(a, tid, sm_rank_len, sm_rank_row);
     WorkCursor cursor{0, sm_rank_row};
     for (bool first = true; take_work(a, tid, cursor, first, s, split, kvh, pass); first = false) {
     // Block ids of this wave: block blk_lo + wave + kWaves * j sits in lane j.  The load does
@@ -412,7 +441,7 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     const int blk_lo = split * a.span_blocks;
     int table_row, L;
     bool cut;
-    resolve_row(a, s, table_row, L, &cut);
+    resolve_row<INL>(a, s, table_row, L, &cut);
     table_row = __builtin_amdgcn_readfirstlane(table_row);   // same for every lane: keep the block loop scalar
     L = __builtin_amdgcn_readfirstlane(L);
     // A fused step appends the row's new token at position L - 1.  A row whose context was cut at
@@ -423,7 +452,10 @@ __global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_ke
     int my_ids = 0;
     {
         const int col = blk_lo + wave + kWaves * lane;
-        if (col < a.max_blocks) my_ids = row[col];
+        if (col < a.max_blocks) {
+            my_ids = row[col];
+            if constexpr (INL) my_ids = inline_block_id(a, s, kvh, pass, cut ? 0 : L, col, my_ids, row);
+        }
     }
     const int n_blk_seq = (L + B - 1) / B;
     const int blk_hi = min(blk_lo + a.span_blocks, n_blk_seq);   // blk_lo < n_blk_seq unless the context is empty
@@ -763,7 +795,7 @@ __device__ __forceinline__ unsigned pack2_bf16(float x, float y)
     return static_cast<unsigned>(to_bf16_rne(x)) | (static_cast<unsigned>(to_bf16_rne(y)) << 16);
 }
 
-template <int D>
+template <int D, bool INL>
 __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_group_kernel(const DecodeArgs a)
 {
     constexpr int BS = 16, GT = 16;
@@ -784,15 +816,15 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
     int s, split, kvh, pass;   // s: row of q / out / the table
     __shared__ int sm_rank_len[kMaxRankedRows], sm_rank_row[kMaxInlineUnits + 1];
     if (a.plan == nullptr && a.n_splits > 1)
-        list_units(a, tid, sm_rank_len, sm_rank_row);
+        list_units<INL>(a, tid, sm_rank_len, sm_rank_row);
     else
-        rank_rows(a, tid, sm_rank_len, sm_rank_row);
+        rank_rows<INL>(a, tid, sm_rank_len, sm_rank_row);
     WorkCursor cursor{0, sm_rank_row};
     for (bool first = true; take_work(a, tid, cursor, first, s, split, kvh, pass); first = false) {
     const int blk_lo = split * a.span_blocks;
     int table_row, L;
     bool cut;
-    resolve_row(a, s, table_row, L, &cut);
+    resolve_row<INL>(a, s, table_row, L, &cut);
     table_row = __builtin_amdgcn_readfirstlane(table_row);   // same for every lane: keep the block loop scalar
     L = __builtin_amdgcn_readfirstlane(L);
     const bool appends = a.k_new != nullptr && __builtin_amdgcn_readfirstlane(static_cast<int>(cut)) == 0;   // a row cut at max_ctx_len appends nothing (see the vector kernel)
@@ -800,7 +832,10 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
     int my_ids = 0;
     {
         const int col = blk_lo + wave + kWaves * lane;
-        if (col < a.max_blocks) my_ids = row[col];
+        if (col < a.max_blocks) {
+            my_ids = row[col];
+            if constexpr (INL) my_ids = inline_block_id(a, s, kvh, pass, cut ? 0 : L, col, my_ids, row);
+        }
     }
     const int n_blk_seq = (L + BS - 1) / BS;
     const int blk_hi = min(blk_lo + a.span_blocks, n_blk_seq);
@@ -965,7 +1000,7 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
 }
 
 // Merge the spans of one (sequence, query head): thread c owns head dimension c.
-template <bool BF16, int D>
+template <bool BF16, int D, bool INL>
 __global__ __launch_bounds__(D) void decode_combine_kernel(const DecodeArgs a)
 {
     const int qrow = blockIdx.x;  // s * n_q_heads + head
@@ -973,7 +1008,7 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const DecodeArgs a)
     const int c = threadIdx.x;
     const int B = a.block_size;
     int table_row, L;
-    resolve_row(a, s, table_row, L);
+    resolve_row<INL>(a, s, table_row, L);
     const int n_blk_seq = (L + B - 1) / B;
     const int n_parts = min((n_blk_seq + a.span_blocks - 1) / a.span_blocks, a.n_splits);
     const float *ml = a.ws_ml + static_cast<long long>(qrow) * a.n_splits * 2;
@@ -991,25 +1026,49 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const DecodeArgs a)
 
 using AttnKernel = void (*)(DecodeArgs);
 
-template <bool BF16, int D, int BS>
+template <bool BF16, int D, int BS, bool INL>
 AttnKernel kernel_by_heads(int gt)
 {
     switch (gt) {
-        case 1: return decode_attn_kernel<BF16, D, BS, 1>;
-        case 2: return decode_attn_kernel<BF16, D, BS, 2>;
-        case 4: return decode_attn_kernel<BF16, D, BS, 4>;
-        default: return decode_attn_kernel<BF16, D, BS, 8>;
+        case 1: return decode_attn_kernel<BF16, D, BS, 1, INL>;
+        case 2: return decode_attn_kernel<BF16, D, BS, 2, INL>;
+        case 4: return decode_attn_kernel<BF16, D, BS, 4, INL>;
+        default: return decode_attn_kernel<BF16, D, BS, 8, INL>;
     }
 }
 
-template <bool BF16, int D>
+template <bool BF16, int D, bool INL>
 AttnKernel kernel_by_block(int block_size, int gt)
 {
     // the block sizes serving systems use get the unrolled, prefetching tile loop; the rest the run-time one
-    if (block_size == 16) return kernel_by_heads<BF16, D, 16>(gt);
-    if (BF16 && block_size == 32) return kernel_by_heads<BF16, D, 32>(gt);
-    if (BF16 && block_size == 64) return kernel_by_heads<BF16, D, 64>(gt);
-    return kernel_by_heads<BF16, D, 0>(gt);
+    if (block_size == 16) return kernel_by_heads<BF16, D, 16, INL>(gt);
+    if (BF16 && block_size == 32) return kernel_by_heads<BF16, D, 32, INL>(gt);
+    if (BF16 && block_size == 64) return kernel_by_heads<BF16, D, 64, INL>(gt);
+    return kernel_by_heads<BF16, D, 0, INL>(gt);
+}
+
+// The kernels of one launch: attention, and the work-list and merge kernels it may need.  INL: the
+// instantiations that take the step's context lengths and new block ids from the kernel
+// arguments (see DecodeArgs::inl).
+struct LaunchKernels {
+    AttnKernel attn = nullptr, plan = nullptr, combine = nullptr;
+};
+template <bool INL>
+LaunchKernels kernels_for(const mux_pool *pool, int gt)
+{
+    const bool bf16 = pool->dtype == MUX_BF16;
+    LaunchKernels k;
+    k.plan = decode_plan_kernel<INL>;
+    if (pool->head_dim == 128) {
+        k.combine = bf16 ? decode_combine_kernel<true, 128, INL> : decode_combine_kernel<false, 128, INL>;
+        k.attn = gt == 16 ? decode_attn_group_kernel<128, INL>
+                          : (bf16 ? kernel_by_block<true, 128, INL>(pool->block_size, gt) : kernel_by_block<false, 128, INL>(pool->block_size, gt));
+    } else if (pool->head_dim == 64) {
+        k.combine = bf16 ? decode_combine_kernel<true, 64, INL> : decode_combine_kernel<false, 64, INL>;
+        k.attn = gt == 16 ? decode_attn_group_kernel<64, INL>
+                          : (bf16 ? kernel_by_block<true, 64, INL>(pool->block_size, gt) : kernel_by_block<false, 64, INL>(pool->block_size, gt));
+    }
+    return k;
 }
 
 // The matrix-core kernel covers bf16 pools with 16-token blocks and groups of >= 4 query heads.
@@ -1146,9 +1205,19 @@ int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, co
                 const int32_t *ctx_lens, const int32_t *cu_q_lens, const int32_t *q_start, int32_t n_table_seqs,
                 int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len,
                 float scale, void *workspace, void *stream, int32_t n_layers = 1, const void *k_new = nullptr,
-                const void *v_new = nullptr)
+                const void *v_new = nullptr, const mux_inline_step *inl = nullptr)
 {
     DecodeArgs a{};
+    if (inl != nullptr) {
+        const long long ints = 2LL * inl->rows + static_cast<long long>(inl->n_entries) * inl->heads;
+        if (inl->rows != n_seqs || inl->rows <= 0 || inl->n_entries < 0 || ints > MUX_INLINE_STEP_INTS || k_new == nullptr ||
+            inl->head0 < 0 || inl->head0 + n_layers * n_kv_heads > inl->heads)
+            return MUX_ERR_INVALID;
+        a.inl_rows = inl->rows;
+        a.inl_heads = inl->heads;
+        a.inl_head0 = inl->head0;
+        std::copy(inl->v, inl->v + ints, a.inl);
+    }
     a.n_layers = n_layers;
     a.k_new = k_new;
     a.v_new = v_new;
@@ -1180,50 +1249,26 @@ int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, co
     }
     if (n_rows * plan.n_splits * n_kv_heads * plan.n_passes > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool bf16 = pool->dtype == MUX_BF16;
     const int gt = plan.heads_per_pass;
-    AttnKernel fn = nullptr;
-    if (gt == 16 && pool->head_dim == 128)
-        fn = decode_attn_group_kernel<128>;
-    else if (gt == 16 && pool->head_dim == 64)
-        fn = decode_attn_group_kernel<64>;
-    else if (bf16 && pool->head_dim == 128)
-        fn = kernel_by_block<true, 128>(pool->block_size, gt);
-    else if (bf16 && pool->head_dim == 64)
-        fn = kernel_by_block<true, 64>(pool->block_size, gt);
-    else if (!bf16 && pool->head_dim == 128)
-        fn = kernel_by_block<false, 128>(pool->block_size, gt);
-    else if (!bf16 && pool->head_dim == 64)
-        fn = kernel_by_block<false, 64>(pool->block_size, gt);
-    else
-        return MUX_ERR_UNSUPPORTED;
+    const LaunchKernels k = inl != nullptr ? kernels_for<true>(pool, gt) : kernels_for<false>(pool, gt);
+    if (k.attn == nullptr) return MUX_ERR_UNSUPPORTED;
     // as many workgroups as are resident at once (they walk the work list); never more than there is work
     const long long most = n_rows * plan.n_splits * n_kv_heads * plan.n_passes;
-    const unsigned g = static_cast<unsigned>(std::min<long long>(most, resident_workgroups(fn)));
+    const unsigned g = static_cast<unsigned>(std::min<long long>(most, resident_workgroups(k.attn)));
     a.grid_wgs = static_cast<int>(g);
     static const int force_plan_kernel = env_int("MUX_DECODE_PLAN_KERNEL", 0);
     if (n_rows <= kMaxRankedRows && n_rows * plan.n_splits <= kMaxInlineUnits && !force_plan_kernel) {
         a.plan = nullptr;   // the workgroups order the work themselves (see rank_rows and list_units)
     } else {
-        hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(k.plan, dim3(1), dim3(256), 0, st, a);
         if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
     }
-    hipLaunchKernelGGL(fn, dim3(g), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(k.attn, dim3(g), dim3(kThreads), 0, st, a);
     if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
     if (plan.n_splits > 1) {
         if (n_rows * n_q_heads > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
         const unsigned rows = static_cast<unsigned>(n_rows * n_q_heads);
-        if (pool->head_dim == 128) {
-            if (bf16)
-                hipLaunchKernelGGL((decode_combine_kernel<true, 128>), dim3(rows), dim3(128), 0, st, a);
-            else
-                hipLaunchKernelGGL((decode_combine_kernel<false, 128>), dim3(rows), dim3(128), 0, st, a);
-        } else {
-            if (bf16)
-                hipLaunchKernelGGL((decode_combine_kernel<true, 64>), dim3(rows), dim3(64), 0, st, a);
-            else
-                hipLaunchKernelGGL((decode_combine_kernel<false, 64>), dim3(rows), dim3(64), 0, st, a);
-        }
+        hipLaunchKernelGGL(k.combine, dim3(rows), dim3(static_cast<unsigned>(pool->head_dim)), 0, st, a);
         if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
     }
     return MUX_OK;
@@ -1257,8 +1302,8 @@ int mux_launch_prefill_rows_as_decode(const mux_pool *pool, void *out, const voi
 int mux_launch_decode_step(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q, const void *k_new,
                            const void *v_new, const int32_t *tables, const int32_t *ctx_lens, int32_t n_layers,
                            int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len,
-                           float scale, void *workspace, void *stream)
+                           float scale, void *workspace, void *stream, const mux_inline_step *inl)
 {
     return launch_rows(pool, plan, out, q, tables, ctx_lens, nullptr, nullptr, n_seqs, n_seqs, n_q_heads, n_kv_heads,
-                       max_blocks, max_ctx_len, scale, workspace, stream, n_layers, k_new, v_new);
+                       max_blocks, max_ctx_len, scale, workspace, stream, n_layers, k_new, v_new, inl);
 }

@@ -53,10 +53,23 @@ int mux_launch_decode_attn(const mux_pool *pool, const mux_decode_plan &plan, vo
                            int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len, float scale,
                            void *workspace, void *stream);
 
+// A decode step's small integer arrays handed over as kernel arguments instead of device memory
+// (the job runner's usual decode job): v = HOST [rows] context length per table row (0 = not in
+// this step), then [rows] index of the row's entry or -1, then per entry `heads` block ids - the
+// block the row's new token has just opened, for every kv head of every layer of the model.
+// head0: where the launch's first layer starts among them.  The attention kernel reads the
+// lengths and those ids from its arguments and stores the ids in the device table for later steps.
+// Precondition: no context length exceeds the launch's max_ctx_len.
+#define MUX_INLINE_STEP_INTS 960   // 3 840 bytes: with the other arguments under the 4 KiB argument limit
+struct mux_inline_step {
+    const int32_t *v;
+    int32_t rows, n_entries, heads, head0;
+};
+// ctx_lens may be null when inl is given (it is not read then).
 int mux_launch_decode_step(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q, const void *k_new,
                            const void *v_new, const int32_t *tables, const int32_t *ctx_lens, int32_t n_layers,
                            int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len,
-                           float scale, void *workspace, void *stream);
+                           float scale, void *workspace, void *stream, const mux_inline_step *inl = nullptr);
 
 int mux_launch_prefill_attn(const mux_pool *pool, void *out, const void *q, const int32_t *cu_q_lens,
                             const int32_t *q_start, const int32_t *tables, int32_t n_seqs, int32_t total_q,

@@ -44,31 +44,12 @@ __global__ void install_blocks_kernel(const int32_t *__restrict__ entries, const
     }
 }
 
-// The same for a decode job whose arrays are small enough to travel as kernel arguments (no
-// copy, no staging): context lengths of the job's rows, then entries, then ids.  One workgroup.
-constexpr int kInlineInts = 960;   // 3 840 bytes: with the other arguments under the 4 KiB argument limit
-struct InlineArrays {
-    int32_t v[kInlineInts];
-};
-__global__ void install_inline_kernel(InlineArrays a, int rows, int n_entries, int32_t *__restrict__ ctx_out,
-                                      int32_t *__restrict__ slot_tables, int heads, int hkv, int max_seqs, int max_blocks)
-{
-    for (int i = threadIdx.x; i < rows; i += blockDim.x) ctx_out[i] = a.v[i];
-    const int ids0 = rows + n_entries * kEntryInts;
-    for (int i = threadIdx.x; i < n_entries * heads; i += blockDim.x) {
-        const int e = i / heads, h = i - e * heads;
-        const int slot = a.v[rows + e * kEntryInts], col = a.v[rows + e * kEntryInts + 2];
-        slot_tables[table_cell(slot, h, hkv, max_seqs) * max_blocks + col] = a.v[ids0 + i];
-    }
-}
-
 struct ModelRun {
     int32_t hq = 0, hkv = 0;         // query and KV heads of ONE layer
     int32_t layers = 1, heads = 0;   // heads = layers * hkv = the scheduler's head count
     hipStream_t stream = nullptr;
     int32_t *tables = nullptr;       // DEVICE [layers][max_seqs][hkv][max_blocks], row = the scheduler's slot
     int32_t *job_tables = nullptr;   // DEVICE, same shape, row = position in the current prefill job
-    int32_t *ctx = nullptr;          // DEVICE [max_seqs]: context lengths of the current decode job, by slot
     void *decode_ws = nullptr, *prefill_ws = nullptr;
     size_t decode_ws_bytes = 0, prefill_ws_bytes = 0;
     int32_t *stage_dev = nullptr;    // DEVICE kRing areas
@@ -87,6 +68,11 @@ struct ModelRun {
         int64_t step = -1;               // scheduler iteration the job belongs to
         int32_t job = -1, kind = 0, n = 0, total = 0, longest = 0, rows = 0;
         const int32_t *seq = nullptr, *pos = nullptr, *cu = nullptr, *start = nullptr, *ctx = nullptr;   // DEVICE
+        // decode job whose arrays are small enough to travel as kernel arguments of the attention
+        // launch itself (no copy, no staging, no kernel ahead of it): see mux_inline_step
+        bool as_arguments = false;
+        int32_t n_entries = 0;
+        int32_t inl[MUX_INLINE_STEP_INTS];
     } prep;
 };
 
@@ -120,7 +106,6 @@ void release(mux_runner *r)
         (void)hipStreamSynchronize(m.stream);
         if (m.tables) (void)hipFree(m.tables);
         if (m.job_tables) (void)hipFree(m.job_tables);
-        if (m.ctx) (void)hipFree(m.ctx);
         if (m.decode_ws) (void)hipFree(m.decode_ws);
         if (m.prefill_ws) (void)hipFree(m.prefill_ws);
         if (m.stage_dev) (void)hipFree(m.stage_dev);
@@ -239,7 +224,6 @@ int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, 
         bool good = m.decode_ws_bytes != 0;
         good = good && ok(hipMalloc(&m.tables, table_bytes)) && ok(hipMalloc(&m.job_tables, table_bytes));
         good = good && ok(hipMemset(m.tables, 0, table_bytes)) && ok(hipMemset(m.job_tables, 0, table_bytes));
-        good = good && ok(hipMalloc(&m.ctx, static_cast<size_t>(max_seqs) * sizeof(int32_t)));
         good = good && ok(hipMalloc(&m.decode_ws, m.decode_ws_bytes));
         good = good && (m.prefill_ws_bytes == 0 || ok(hipMalloc(&m.prefill_ws, m.prefill_ws_bytes)));
         good = good && ok(hipMalloc(&m.stage_dev, kRing * r->area_ints * sizeof(int32_t)));
@@ -351,35 +335,47 @@ static int prepare_job(mux_runner_t *r, int32_t job, int32_t *model_out)
         if (m.layers > 1) rows = r->max_seqs;   // the layers of the device table are max_seqs rows apart
         const size_t need = static_cast<size_t>(rows) + static_cast<size_t>(n_entries) * (kEntryInts + heads);
         if (need > r->area_ints) return MUX_ERR_INVALID;
-        const bool as_arguments = !r->stage_always && need <= static_cast<size_t>(kInlineInts);
-        InlineArrays inl{};
-        int32_t *host = inl.v, *dev = nullptr;
-        int area = 0;
-        if (!as_arguments) {
+        const size_t need_inline = 2 * static_cast<size_t>(rows) + static_cast<size_t>(n_entries) * heads;
+        p.as_arguments = !r->stage_always && need_inline <= static_cast<size_t>(MUX_INLINE_STEP_INTS);
+        if (p.as_arguments) {
+            // context length per slot | index of the slot's entry or -1 | ids of the entries
+            int32_t *ctx = p.inl, *entry_of = ctx + rows, *ids = entry_of + rows;
+            std::fill(ctx, ctx + rows, 0);
+            std::fill(entry_of, entry_of + rows, -1);
+            int32_t e_at = 0;
+            for (int32_t i = 0; i < n; ++i) {
+                const int32_t slot = r->slots[i], len = r->lens[i];
+                ctx[slot] = len;
+                if (!(r->flags[i] & MUX_JOB_FLAG_TABLE)) continue;
+                const int32_t col = (len - 1) / B;   // the block the appended token opened
+                if (len <= 0 || col >= cols) return MUX_ERR_INVALID;
+                entry_of[slot] = e_at;
+                const int32_t *row = table + static_cast<size_t>(slot) * heads * cols;
+                for (int32_t h = 0; h < heads; ++h) ids[e_at * heads + h] = row[static_cast<size_t>(h) * cols + col];
+                ++e_at;
+            }
+            p.n_entries = n_entries;
+            p.ctx = nullptr;
+        } else {
+            int32_t *host = nullptr, *dev = nullptr;
+            int area = 0;
             rc = claim_area(m, r->area_ints, &host, &dev, &area);
             if (rc != MUX_OK) return rc;
-        }
-        int32_t *ctx = host, *entries = host + rows, *ids = entries + kEntryInts * n_entries;
-        std::fill(ctx, ctx + rows, 0);
-        int32_t e_at = 0;
-        for (int32_t i = 0; i < n; ++i) {
-            const int32_t slot = r->slots[i], len = r->lens[i];
-            ctx[slot] = len;
-            if (!(r->flags[i] & MUX_JOB_FLAG_TABLE)) continue;
-            const int32_t col = (len - 1) / B;   // the block the appended token opened
-            if (len <= 0 || col >= cols) return MUX_ERR_INVALID;
-            int32_t *e = entries + kEntryInts * e_at;
-            e[0] = slot, e[1] = -1, e[2] = col, e[3] = 1, e[4] = e_at * heads;
-            const int32_t *row = table + static_cast<size_t>(slot) * heads * cols;
-            for (int32_t h = 0; h < heads; ++h) ids[e_at * heads + h] = row[static_cast<size_t>(h) * cols + col];
-            ++e_at;
-        }
-        if (as_arguments) {
-            hipLaunchKernelGGL(install_inline_kernel, dim3(1), dim3(256), 0, m.stream, inl, rows, n_entries, m.ctx, m.tables, heads, m.hkv,
-                               r->max_seqs, cols);
-            if (!ok(hipGetLastError())) return MUX_ERR_HIP;
-            p.ctx = m.ctx;
-        } else {
+            int32_t *ctx = host, *entries = host + rows, *ids = entries + kEntryInts * n_entries;
+            std::fill(ctx, ctx + rows, 0);
+            int32_t e_at = 0;
+            for (int32_t i = 0; i < n; ++i) {
+                const int32_t slot = r->slots[i], len = r->lens[i];
+                ctx[slot] = len;
+                if (!(r->flags[i] & MUX_JOB_FLAG_TABLE)) continue;
+                const int32_t col = (len - 1) / B;   // the block the appended token opened
+                if (len <= 0 || col >= cols) return MUX_ERR_INVALID;
+                int32_t *e = entries + kEntryInts * e_at;
+                e[0] = slot, e[1] = -1, e[2] = col, e[3] = 1, e[4] = e_at * heads;
+                const int32_t *row = table + static_cast<size_t>(slot) * heads * cols;
+                for (int32_t h = 0; h < heads; ++h) ids[e_at * heads + h] = row[static_cast<size_t>(h) * cols + col];
+                ++e_at;
+            }
             rc = send_area(m, area, host, dev, need);
             if (rc != MUX_OK) return rc;
             rc = install(m, dev + rows, dev + rows + kEntryInts * n_entries, n_entries, false, r->max_seqs, cols);
@@ -421,8 +417,20 @@ static int run_layers(mux_runner_t *r, ModelRun &m, int32_t l0, int32_t l1, void
         return MUX_OK;
     }
     // one launch for the layers asked for (their tables follow one another)
-    return mux_decode_step(r->pool, out, q, k_new, v_new, m.tables + l0 * layer_cells, p.ctx, l1 - l0, p.rows, m.hq, m.hkv, cols, p.longest,
-                           scale, m.decode_ws, m.decode_ws_bytes, m.stream);
+    if (!p.as_arguments)
+        return mux_decode_step(r->pool, out, q, k_new, v_new, m.tables + l0 * layer_cells, p.ctx, l1 - l0, p.rows, m.hq, m.hkv, cols,
+                               p.longest, scale, m.decode_ws, m.decode_ws_bytes, m.stream);
+    // the same launch with the job's arrays in its arguments: the attention kernel installs the new ids itself
+    if (!out || !q || !k_new || !v_new || p.rows <= 0 || l1 <= l0) return MUX_ERR_INVALID;
+    if (((reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) |
+          reinterpret_cast<uintptr_t>(v_new)) & 15u) != 0)
+        return MUX_ERR_INVALID;
+    if (p.longest > static_cast<int64_t>(cols) * r->pool->block_size) return MUX_ERR_INVALID;
+    const mux_decode_plan plan = mux_plan_decode(r->pool, (l1 - l0) * p.rows, m.hq, m.hkv, std::max(p.longest, 1));
+    if (plan.workspace_bytes > m.decode_ws_bytes) return MUX_ERR_INVALID;
+    const mux_inline_step inl{p.inl, p.rows, p.n_entries, m.heads, l0 * m.hkv};
+    return mux_launch_decode_step(r->pool, plan, out, q, k_new, v_new, m.tables + l0 * layer_cells, nullptr, l1 - l0, p.rows, m.hq,
+                                  m.hkv, cols, p.longest, scale, m.decode_ws, m.stream, &inl);
 }
 
 int mux_runner_launch(mux_runner_t *r, int32_t job, void *out, const void *q, const void *k_new, const void *v_new, float scale)
