@@ -63,15 +63,25 @@ def oracle_job_outputs(op, os_, src, shapes, job, scale):
     return op.decode_attn(q, np.maximum(table[slots], 0), lens, hq, scale)
 
 
-@pytest.mark.parametrize("driver", ["python", "runner", "runner-one-stream", "runner-staged", "runner-layers"])
-@pytest.mark.parametrize("case", ["roomy", "tight-quota", "preempting"])
+CASES = [(c, d) for c in ("roomy", "tight-quota", "preempting")
+         for d in ("python", "runner", "runner-one-stream", "runner-staged", "runner-layers")]
+# hundreds of short requests at once: decode jobs of more than 256 rows (the work list then comes from
+# the plan kernel) whose arrays still fit the attention launch's arguments, and some that do not
+CASES += [("many-slots", "runner"), ("many-slots", "runner-layers")]
+
+
+@pytest.mark.parametrize("case,driver", CASES)
 def test_scheduler_drives_kernels_like_the_oracle(case, driver, monkeypatch):
     print("[case] adbs %s, driver %s" % (case, driver), flush=True)
     shapes = [wl.ModelShape("a", 8, 8, 128), wl.ModelShape("b", 16, 4, 128), wl.ModelShape("c", 4, 4, 128)]
     d, B = 128, 16
-    n_blocks = {"roomy": 4000, "tight-quota": 600, "preempting": 300}[case]
+    n_blocks = {"roomy": 4000, "tight-quota": 600, "preempting": 300, "many-slots": 9000}[case]
     max_seqs, max_blocks, budget = 6, 24, 256
-    rng = np.random.default_rng({"roomy": 1, "tight-quota": 2, "preempting": 3}[case])
+    many = case == "many-slots"
+    if many:
+        shapes = [wl.ModelShape("a", 4, 2, 128), wl.ModelShape("b", 8, 2, 128), wl.ModelShape("c", 2, 2, 128)]
+        max_seqs, max_blocks, budget = 300, 5, 2048
+    rng = np.random.default_rng({"roomy": 1, "tight-quota": 2, "preempting": 3, "many-slots": 4}[case])
     order = wl.placement_order(rng, n_blocks)
     kv = torch.empty(n_blocks * 2 * B * d * 2, dtype=torch.uint8, device="cuda")
     kv.view(torch.int16).fill_(0x7FC1)                      # NaN pattern: a read of a never-written slot shows
@@ -95,12 +105,12 @@ def test_scheduler_drives_kernels_like_the_oracle(case, driver, monkeypatch):
                                   layers=layers, **kw)
     os_ = orc.OracleScheduler(op, [s.n_kv_heads for s in shapes], max_seqs, max_blocks, budget, **kw)
     scale = H.default_scale(d)
-    rid, worst, kinds = 0, 0.0, set()
+    rid, worst, kinds, most_rows = 0, 0.0, set(), 0
     for it in range(400):
-        if it < 60:
-            for _ in range(int(rng.poisson(0.7))):
+        if it < (12 if many else 60):
+            for _ in range(int(rng.poisson(90 if many else 0.7))):
                 m = int(rng.integers(3))
-                plen, olen = int(rng.integers(1, 200)), int(rng.integers(1, 60))
+                plen, olen = (int(rng.integers(1, 24)), int(rng.integers(20, 50))) if many else (int(rng.integers(1, 200)), int(rng.integers(1, 60)))
                 engine.submit(m, rid, plen, olen)
                 assert os_.submit(m, rid, plen, olen) == 0
                 rid += 1
@@ -114,6 +124,8 @@ def test_scheduler_drives_kernels_like_the_oracle(case, driver, monkeypatch):
             kinds.add(job["kind"])
             if job["kind"] == mx.MUX_JOB_PREEMPT:
                 continue
+            if job["kind"] == mx.MUX_JOB_DECODE:
+                most_rows = max(most_rows, int(job["slots"].max()) + 1)
             want = oracle_job_outputs(op, os_, src, shapes, wj, scale)
             worst = max(worst, H.assert_close(out, want, "bf16", "%s job of model %d, iteration %d" % (
                 "prefill" if job["kind"] == mx.MUX_JOB_PREFILL else "decode", job["model"], it)))
@@ -139,6 +151,8 @@ def test_scheduler_drives_kernels_like_the_oracle(case, driver, monkeypatch):
     assert {mx.MUX_JOB_PREFILL, mx.MUX_JOB_DECODE} <= kinds
     if case == "preempting":
         assert mx.MUX_JOB_PREEMPT in kinds
+    if many:
+        assert most_rows > 256
     print("adbs %s: %d requests, %d iterations, max abs err %.2e" % (case, rid, engine.iterations, worst), flush=True)
 
 
