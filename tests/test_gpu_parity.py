@@ -173,6 +173,25 @@ def test_decode_few_long_rows_are_split_into_spans(n_q, n_kv):
     print("max abs err %.2e" % err)
 
 
+@pytest.mark.parametrize("n_rows,longest", [(230, 16000), (250, 21000)])
+@pytest.mark.parametrize("n_q,n_kv", [(2, 2), (8, 1)])
+def test_decode_one_long_row_among_hundreds_of_short_ones(n_q, n_kv, n_rows, longest):
+    """The span count follows the longest context, so one long row makes every row a split row.
+    230 rows x 4 spans = 920 units: the attention kernel lists them itself; 250 rows x 6 spans =
+    1 500 units: more than it holds, the plan kernel lists them.  Every other row has a short (or
+    empty) context and only a last span."""
+    _say("decode, %d rows, one of %d tokens, Hq=%d Hkv=%d" % (n_rows, longest, n_q, n_kv))
+    rng = np.random.default_rng(n_rows + n_q)
+    lens = rng.integers(0, 70, n_rows)
+    lens[n_rows // 3] = longest
+    lens[5] = 4097                                   # one more row with a full span and a one-token last span
+    ls, job, q, got, want = _decode_case("bf16", 128, 16, n_q, n_kv, [int(x) for x in lens], seed=90 + n_q)
+    spans = -(-longest // 4096)
+    assert (n_rows * spans <= 1024) == (n_rows == 230)
+    err = H.assert_close(got, want, "bf16")
+    print("max abs err %.2e" % err)
+
+
 def test_decode_rows_sum_to_one_on_gpu():
     """V == 1 everywhere => O == 1 (softmax weights sum to one), checked on the GPU path."""
     rng = np.random.Generator(np.random.PCG64(3))
