@@ -808,7 +808,7 @@ def main() -> int:
             achieved, avg_ms, per_launch = overlapped, float(np.mean(durs) * 1e3), float(np.mean(algo))
             basis = "timed region: mean start-to-end duration of a decode launch (launches of different models may overlap)"
         roofline = {
-            "kernel": "decode_attn_kernel (preceded by decode_plan_kernel, followed by decode_combine_kernel for split contexts), one launch per model per step",
+            "kernel": "decode_attn_kernel (alone for launches of whole rows; followed by decode_combine_kernel when contexts are split, preceded by decode_plan_kernel beyond 256 rows), one launch per model per step",
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "frac_basis": basis,
             "traffic": MEASURED_TRAFFIC_CFG2["bytes"] if args.config == 2 else None,
