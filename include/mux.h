@@ -199,7 +199,9 @@ MUX_API size_t mux_decode_workspace_bound(const mux_pool_t *pool, int32_t max_se
  * forbid hipMalloc.  Same arguments, same kernels and bit-identical results as
  * mux_decode_attn; the call's scratch lives in a fixed array of MUX_STATIC_SCRATCH_BYTES that
  * is part of the library's device image (every GPU the library runs on holds it until the
- * process ends).  The call allocates nothing and frees nothing, on the host side too.
+ * process ends).  The call allocates and frees no device memory and calls no allocating
+ * runtime routine; the only thing it may put on the host heap is one entry of a small table,
+ * the first time a GPU runs one of the kernels (how many of its workgroups the GPU holds at once).
  * A call whose mux_decode_workspace_bytes(...) exceeds MUX_STATIC_SCRATCH_BYTES is refused with
  * MUX_ERR_TOO_LARGE and launches nothing.  Every call on one GPU uses that GPU's one array:
  * two such calls must not overlap on a GPU (same stream, or ordered by events) - overlapping
