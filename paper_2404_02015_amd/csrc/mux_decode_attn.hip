@@ -135,23 +135,29 @@ struct DecodeArgs {
     // units as (row, split) pairs, longest first
     int *plan;
     int grid_wgs;   // workgroups of the attention launch
-    // A fused step whose small integer arrays ride in the kernel arguments, so that no kernel has to
-    // run ahead of this one to put them into device memory (inl_rows == n_seqs > 0; ctx_lens is not
-    // read then).  inl holds, for the n_seqs rows of a layer: the context length; then the index
-    // of the row's entry or -1; then, per entry, inl_heads block ids: the block that the row's new
-    // token has just opened, for every kv head of every layer of the model (this launch's first
-    // layer starts at inl_head0).  The id of such a block is taken from here instead of the table
-    // (where head pass 0 stores it for the steps to come).
-    int inl_rows, inl_heads, inl_head0;
+};
+
+// Arguments of a fused step whose small integer arrays ride in the kernel arguments, so that no
+// kernel has to run ahead of this one to put them into device memory (ctx_lens is not read
+// then).  inl holds, for the n_seqs rows of a layer: the context length; then the index of the
+// row's entry or -1; then, per entry, inl_heads block ids: the block that the row's new token
+// has just opened, for every kv head of every layer of the model (this launch's first layer
+// starts at inl_head0).  The id of such a block is taken from here instead of the table (where
+// head pass 0 stores it for the steps to come).  Only the INL instantiations of the kernels take
+// this (4 KiB of arguments cost ~2 us per launch, which the ordinary launches should not pay).
+struct DecodeArgsInl : DecodeArgs {
+    int inl_heads, inl_head0;
     int inl[MUX_INLINE_STEP_INTS];
 };
-static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
+static_assert(sizeof(DecodeArgsInl) <= 4096, "kernel arguments are limited to 4 KiB");
+template <bool INL>
+using Args = std::conditional_t<INL, DecodeArgsInl, DecodeArgs>;
 
 // The id of the block that column `col` of row s (kv head kvh) refers to, when the step's arrays
 // ride in the arguments and the row's new token has just opened that block; `id` otherwise.  Head
 // pass 0 leaves the id in the table.  L: the row's context length (0 for a row that is not part of
 // the step, or whose context was cut at the launch's bound: its new token lies beyond the cut).
-__device__ __forceinline__ int inline_block_id(const DecodeArgs &a, int s, int kvh, int pass, int L, int col, int id,
+__device__ __forceinline__ int inline_block_id(const DecodeArgsInl &a, int s, int kvh, int pass, int L, int col, int id,
                                                const int *table_row)
 {
     if (L <= 0) return id;
@@ -165,11 +171,14 @@ __device__ __forceinline__ int inline_block_id(const DecodeArgs &a, int s, int k
 // Row r of q/out -> (block-table row, context length).  The length is cut at max_ctx_len (the
 // host's bound, which sized the launch); *cut, when asked for, tells whether that happened.
 template <bool INL>
-__device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &table_row, int &len, bool *cut = nullptr)
+__device__ __forceinline__ void resolve_row(const Args<INL> &a, int r, int &table_row, int &len, bool *cut = nullptr)
 {
     if (a.cu_q_lens == nullptr) {
         table_row = r;
-        len = INL ? a.inl[r % a.n_seqs] : a.ctx_lens[r % a.n_seqs];
+        if constexpr (INL)
+            len = a.inl[r % a.n_seqs];
+        else
+            len = a.ctx_lens[r % a.n_seqs];
     } else {
         int lo = 0, hi = a.n_table_seqs - 1;  // last sequence whose first row is <= r
         while (lo < hi) {
@@ -192,7 +201,7 @@ __device__ __forceinline__ void resolve_row(const DecodeArgs &a, int r, int &tab
 // each of which walks a fixed share of that list (see take_work).  No workgroup is ever started
 // for an empty span, and the longest units are never started last.
 template <bool INL>
-__global__ __launch_bounds__(256) void decode_plan_kernel(const DecodeArgs a)
+__global__ __launch_bounds__(256) void decode_plan_kernel(const Args<INL> a)
 {
     __shared__ int sm_scan[256];
     __shared__ int sm_bin[kWaves * kMaxWaveBlocks + 1];   // by length of the last span, 0 .. span_blocks
@@ -276,7 +285,7 @@ struct WorkCursor {
 constexpr int kMaxRankedRows = kThreads;
 
 template <bool INL>
-__device__ __forceinline__ void rank_rows(const DecodeArgs &a, int tid, int *sm_len, int *sm_row)
+__device__ __forceinline__ void rank_rows(const Args<INL> &a, int tid, int *sm_len, int *sm_row)
 {
     if (a.plan != nullptr) return;
     const int n_rows = a.n_seqs * a.n_layers;
@@ -307,7 +316,7 @@ __device__ __forceinline__ void rank_rows(const DecodeArgs &a, int tid, int *sm_
 constexpr int kMaxInlineUnits = 1024;
 
 template <bool INL>
-__device__ __forceinline__ void list_units(const DecodeArgs &a, int tid, int *sm_shape, int *sm_units)
+__device__ __forceinline__ void list_units(const Args<INL> &a, int tid, int *sm_shape, int *sm_units)
 {
     const int n_rows = a.n_seqs * a.n_layers;
     const int span = a.span_blocks;
@@ -406,7 +415,7 @@ __device__ __forceinline__ void merge_waves_and_store(const DecodeArgs &a, const
 // BF16: storage type; D: head size; BS: tokens per block at compile time (0 = run time);
 // GT: query heads of one KV group handled together.
 template <bool BF16, int D, int BS, int GT, bool INL>
-__global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_kernel(const DecodeArgs a)
+__global__ __launch_bounds__(kThreads, MUX_DECODE_MIN_WAVES) void decode_attn_kernel(const Args<INL> a)
 {
     constexpr int EB = BF16 ? 2 : 4;
     constexpr int EPL = 16 / EB;          // elements per lane per load
@@ -796,7 +805,7 @@ __device__ __forceinline__ unsigned pack2_bf16(float x, float y)
 }
 
 template <int D, bool INL>
-__global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_group_kernel(const DecodeArgs a)
+__global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_group_kernel(const Args<INL> a)
 {
     constexpr int BS = 16, GT = 16;
     constexpr int KC = D / 32, NT = D / 16;
@@ -1001,7 +1010,7 @@ __global__ __launch_bounds__(kThreads, MUX_GROUP_MIN_WAVES) void decode_attn_gro
 
 // Merge the spans of one (sequence, query head): thread c owns head dimension c.
 template <bool BF16, int D, bool INL>
-__global__ __launch_bounds__(D) void decode_combine_kernel(const DecodeArgs a)
+__global__ __launch_bounds__(D) void decode_combine_kernel(const Args<INL> a)
 {
     const int qrow = blockIdx.x;  // s * n_q_heads + head
     const int s = qrow / a.n_q_heads;
@@ -1024,10 +1033,11 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const DecodeArgs a)
     store_out<BF16>(a.out, static_cast<long long>(qrow) * D + c, ll > 0.f ? o / ll : 0.f);
 }
 
-using AttnKernel = void (*)(DecodeArgs);
+template <bool INL>
+using AttnKernel = void (*)(Args<INL>);
 
 template <bool BF16, int D, int BS, bool INL>
-AttnKernel kernel_by_heads(int gt)
+AttnKernel<INL> kernel_by_heads(int gt)
 {
     switch (gt) {
         case 1: return decode_attn_kernel<BF16, D, BS, 1, INL>;
@@ -1038,7 +1048,7 @@ AttnKernel kernel_by_heads(int gt)
 }
 
 template <bool BF16, int D, bool INL>
-AttnKernel kernel_by_block(int block_size, int gt)
+AttnKernel<INL> kernel_by_block(int block_size, int gt)
 {
     // the block sizes serving systems use get the unrolled, prefetching tile loop; the rest the run-time one
     if (block_size == 16) return kernel_by_heads<BF16, D, 16, INL>(gt);
@@ -1049,15 +1059,16 @@ AttnKernel kernel_by_block(int block_size, int gt)
 
 // The kernels of one launch: attention, and the work-list and merge kernels it may need.  INL: the
 // instantiations that take the step's context lengths and new block ids from the kernel
-// arguments (see DecodeArgs::inl).
+// arguments (see DecodeArgsInl).
+template <bool INL>
 struct LaunchKernels {
-    AttnKernel attn = nullptr, plan = nullptr, combine = nullptr;
+    AttnKernel<INL> attn = nullptr, plan = nullptr, combine = nullptr;
 };
 template <bool INL>
-LaunchKernels kernels_for(const mux_pool *pool, int gt)
+LaunchKernels<INL> kernels_for(const mux_pool *pool, int gt)
 {
     const bool bf16 = pool->dtype == MUX_BF16;
-    LaunchKernels k;
+    LaunchKernels<INL> k;
     k.plan = decode_plan_kernel<INL>;
     if (pool->head_dim == 128) {
         k.combine = bf16 ? decode_combine_kernel<true, 128, INL> : decode_combine_kernel<false, 128, INL>;
@@ -1088,10 +1099,10 @@ int env_int(const char *name, int fallback)
 // The attention launch has exactly this many workgroups, so all of them start together and each
 // walks its own share of the work list.  The cache is the library's only process-wide state:
 // a read-mostly table of numbers that are properties of the hardware, guarded by a mutex.
-long long resident_workgroups(AttnKernel fn)
+long long resident_workgroups(const void *fn)
 {
     static std::mutex mu;
-    static std::map<std::pair<int, AttnKernel>, long long> known;
+    static std::map<std::pair<int, const void *>, long long> known;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) {
         (void)hipGetLastError();
@@ -1106,7 +1117,7 @@ long long resident_workgroups(AttnKernel fn)
     static const int forced = env_int("MUX_DECODE_WG_PER_CU", 0);
     if (forced > 0)
         per_cu = forced;
-    else if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fn), kThreads, 0) !=
+    else if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, 0) !=
                  hipSuccess ||
              per_cu <= 0)
         per_cu = 2;
@@ -1201,19 +1212,48 @@ size_t mux_decode_workspace_upper_bound(const mux_pool *pool, int32_t max_rows, 
 }
 
 namespace {
+// Work list (if the attention kernel cannot build it itself), attention, merge of the spans.
+template <bool INL>
+int launch_kernels(const mux_pool *pool, const mux_decode_plan &plan, Args<INL> &a, long long n_rows, int32_t n_q_heads,
+                   int32_t n_kv_heads, hipStream_t st)
+{
+    const int gt = plan.heads_per_pass;
+    const LaunchKernels<INL> k = kernels_for<INL>(pool, gt);
+    if (k.attn == nullptr) return MUX_ERR_UNSUPPORTED;
+    // as many workgroups as are resident at once (they walk the work list); never more than there is work
+    const long long most = n_rows * plan.n_splits * n_kv_heads * plan.n_passes;
+    const unsigned g = static_cast<unsigned>(std::min<long long>(most, resident_workgroups(reinterpret_cast<const void *>(k.attn))));
+    a.grid_wgs = static_cast<int>(g);
+    static const int force_plan_kernel = env_int("MUX_DECODE_PLAN_KERNEL", 0);
+    if (n_rows <= kMaxRankedRows && n_rows * plan.n_splits <= kMaxInlineUnits && !force_plan_kernel) {
+        a.plan = nullptr;   // the workgroups order the work themselves (see rank_rows and list_units)
+    } else {
+        hipLaunchKernelGGL(k.plan, dim3(1), dim3(256), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
+    }
+    hipLaunchKernelGGL(k.attn, dim3(g), dim3(kThreads), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
+    if (plan.n_splits > 1) {
+        if (n_rows * n_q_heads > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
+        const unsigned rows = static_cast<unsigned>(n_rows * n_q_heads);
+        hipLaunchKernelGGL(k.combine, dim3(rows), dim3(static_cast<unsigned>(pool->head_dim)), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
+    }
+    return MUX_OK;
+}
+
 int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, const void *q, const int32_t *tables,
                 const int32_t *ctx_lens, const int32_t *cu_q_lens, const int32_t *q_start, int32_t n_table_seqs,
                 int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_blocks, int32_t max_ctx_len,
                 float scale, void *workspace, void *stream, int32_t n_layers = 1, const void *k_new = nullptr,
                 const void *v_new = nullptr, const mux_inline_step *inl = nullptr)
 {
-    DecodeArgs a{};
+    DecodeArgsInl a{};   // the ordinary launches pass only its base part
     if (inl != nullptr) {
         const long long ints = 2LL * inl->rows + static_cast<long long>(inl->n_entries) * inl->heads;
         if (inl->rows != n_seqs || inl->rows <= 0 || inl->n_entries < 0 || ints > MUX_INLINE_STEP_INTS || k_new == nullptr ||
             inl->head0 < 0 || inl->head0 + n_layers * n_kv_heads > inl->heads)
             return MUX_ERR_INVALID;
-        a.inl_rows = inl->rows;
         a.inl_heads = inl->heads;
         a.inl_head0 = inl->head0;
         std::copy(inl->v, inl->v + ints, a.inl);
@@ -1249,29 +1289,8 @@ int launch_rows(const mux_pool *pool, const mux_decode_plan &plan, void *out, co
     }
     if (n_rows * plan.n_splits * n_kv_heads * plan.n_passes > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int gt = plan.heads_per_pass;
-    const LaunchKernels k = inl != nullptr ? kernels_for<true>(pool, gt) : kernels_for<false>(pool, gt);
-    if (k.attn == nullptr) return MUX_ERR_UNSUPPORTED;
-    // as many workgroups as are resident at once (they walk the work list); never more than there is work
-    const long long most = n_rows * plan.n_splits * n_kv_heads * plan.n_passes;
-    const unsigned g = static_cast<unsigned>(std::min<long long>(most, resident_workgroups(k.attn)));
-    a.grid_wgs = static_cast<int>(g);
-    static const int force_plan_kernel = env_int("MUX_DECODE_PLAN_KERNEL", 0);
-    if (n_rows <= kMaxRankedRows && n_rows * plan.n_splits <= kMaxInlineUnits && !force_plan_kernel) {
-        a.plan = nullptr;   // the workgroups order the work themselves (see rank_rows and list_units)
-    } else {
-        hipLaunchKernelGGL(k.plan, dim3(1), dim3(256), 0, st, a);
-        if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
-    }
-    hipLaunchKernelGGL(k.attn, dim3(g), dim3(kThreads), 0, st, a);
-    if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
-    if (plan.n_splits > 1) {
-        if (n_rows * n_q_heads > 0x7fffffffLL) return MUX_ERR_UNSUPPORTED;
-        const unsigned rows = static_cast<unsigned>(n_rows * n_q_heads);
-        hipLaunchKernelGGL(k.combine, dim3(rows), dim3(static_cast<unsigned>(pool->head_dim)), 0, st, a);
-        if (hipGetLastError() != hipSuccess) return MUX_ERR_HIP;
-    }
-    return MUX_OK;
+    if (inl != nullptr) return launch_kernels<true>(pool, plan, a, n_rows, n_q_heads, n_kv_heads, st);
+    return launch_kernels<false>(pool, plan, static_cast<DecodeArgs &>(a), n_rows, n_q_heads, n_kv_heads, st);
 }
 }  // namespace
 
