@@ -2,7 +2,7 @@
 // the GPU - the part of the paper's serving loop between "the scheduler picked a job" and "the
 // attention of that job ran over the unified KV cache" (Section 3.4).  For every job it stages
 // the job's small integer arrays - as kernel arguments when they fit (the usual decode job),
-// else in pinned memory sent with ONE host-to-device copy -, installs the block ids the
+// else in pinned memory that ONE kernel reads directly -, installs the block ids the
 // scheduler just handed out into the device copy of the model's table, and enqueues append +
 // attention on the model's stream.  Nothing here computes
 // attention: the kernels are those behind mux_kv_append, mux_prefill_attn and mux_decode_step.
@@ -28,19 +28,47 @@ __device__ __forceinline__ size_t table_cell(int row, int hh, int hkv, int max_s
     return (static_cast<size_t>(hh / hkv) * max_seqs + row) * hkv + hh % hkv;
 }
 
-// One workgroup per entry: the ids of one sequence, head-major [heads][n_cols], go to columns
-// col0 .. col0+n_cols-1 of its row in the model's table and, for a prefill, of the job's table.
-__global__ void install_blocks_kernel(const int32_t *__restrict__ entries, const int32_t *__restrict__ ids,
-                                      int32_t *__restrict__ slot_tables, int32_t *__restrict__ job_tables, int heads, int hkv,
-                                      int max_seqs, int max_blocks)
+// A job's arrays arrive in a pinned host area and this one kernel takes them from there (a
+// host-to-device copy, the event that says when the area is free again and a separate install
+// kernel cost ~75 us of runtime calls per job; a kernel launch costs ~8):
+//   - workgroups 0 .. n_entries-1 install one entry each: the ids of one sequence, head-major
+//     [heads][n_cols], go to columns col0 .. col0+n_cols-1 of its row in the model's table and,
+//     for a prefill, of the job's table (entries and ids are read from the host area: once each);
+//   - the other workgroups copy the area's first copy_ints ints - the arrays that the append and
+//     attention kernels read many times over - into the area's device twin;
+//   - the workgroup that finishes last writes the area's stamp into pinned host memory.  Every
+//     workgroup's reads of the host area have returned by then (their values were stored, or
+//     used as addresses, before its barrier), so the host may refill the area as soon as it
+//     sees the stamp: no event, no runtime call.
+__global__ __launch_bounds__(256) void stage_install_kernel(const int32_t *__restrict__ host_area, int32_t *__restrict__ dev_area,
+                                                            int copy_ints, int n_entries, int entries_at, int ids_at,
+                                                            int32_t *__restrict__ slot_tables, int32_t *__restrict__ job_tables,
+                                                            int heads, int hkv, int max_seqs, int max_blocks, int *arrivals,
+                                                            int32_t *stamp_host, int32_t stamp)
 {
-    const int32_t *e = entries + static_cast<size_t>(blockIdx.x) * kEntryInts;
-    const int slot = e[0], job_row = e[1], col0 = e[2], n_cols = e[3], at = e[4];
-    for (int i = threadIdx.x; i < heads * n_cols; i += blockDim.x) {
-        const int h = i / n_cols, j = i - h * n_cols;
-        const int32_t id = ids[at + i];
-        slot_tables[table_cell(slot, h, hkv, max_seqs) * max_blocks + col0 + j] = id;
-        if (job_row >= 0) job_tables[table_cell(job_row, h, hkv, max_seqs) * max_blocks + col0 + j] = id;
+    const int b = blockIdx.x;
+    if (b < n_entries) {
+        const int32_t *e = host_area + entries_at + static_cast<size_t>(b) * kEntryInts;
+        const int slot = e[0], job_row = e[1], col0 = e[2], n_cols = e[3], at = e[4];
+        const int32_t *ids = host_area + ids_at + at;
+        for (int i = threadIdx.x; i < heads * n_cols; i += blockDim.x) {
+            const int h = i / n_cols, j = i - h * n_cols;
+            const int32_t id = ids[i];
+            slot_tables[table_cell(slot, h, hkv, max_seqs) * max_blocks + col0 + j] = id;
+            if (job_row >= 0) job_tables[table_cell(job_row, h, hkv, max_seqs) * max_blocks + col0 + j] = id;
+        }
+    } else {
+        const int n_copy_wgs = static_cast<int>(gridDim.x) - n_entries;
+        for (int i = (b - n_entries) * 256 + threadIdx.x; i < copy_ints; i += n_copy_wgs * 256) dev_area[i] = host_area[i];
+    }
+    __shared__ int last;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        last = __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == static_cast<int>(gridDim.x) - 1;
+        if (last) {
+            __hip_atomic_store(arrivals, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // clean for the next job
+            __hip_atomic_store(stamp_host, stamp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
     }
 }
 
@@ -53,9 +81,11 @@ struct ModelRun {
     void *decode_ws = nullptr, *prefill_ws = nullptr;
     size_t decode_ws_bytes = 0, prefill_ws_bytes = 0;
     int32_t *stage_dev = nullptr;    // DEVICE kRing areas
-    int32_t *stage_host = nullptr;   // pinned HOST kRing areas
-    hipEvent_t copied[kRing] = {};   // the area's host-to-device copy has finished
-    bool in_flight[kRing] = {};
+    int32_t *stage_host = nullptr;   // pinned HOST kRing areas, then one stamp per area (16 ints apart)
+    int32_t *stage_host_dev = nullptr;   // the same memory as the GPU addresses it
+    int *arrivals = nullptr;         // DEVICE: workgroups of the staging kernel that are done (zero between jobs)
+    int32_t stamp_of[kRing] = {};    // what the staging kernel of the area's last job writes into its stamp; 0 = never used
+    int32_t next_stamp = 1;
     int next_area = 0;
     hipEvent_t done = nullptr;       // everything launched for this model so far
     // buffers registered with mux_runner_set_buffers: [0] prefill, [1] decode
@@ -110,8 +140,7 @@ void release(mux_runner *r)
         if (m.prefill_ws) (void)hipFree(m.prefill_ws);
         if (m.stage_dev) (void)hipFree(m.stage_dev);
         if (m.stage_host) (void)hipHostFree(m.stage_host);
-        for (hipEvent_t &e : m.copied)
-            if (e) (void)hipEventDestroy(e);
+        if (m.arrivals) (void)hipFree(m.arrivals);
         if (m.done) (void)hipEventDestroy(m.done);
     }
     delete r;
@@ -130,32 +159,53 @@ int order_after(mux_runner *r, ModelRun &m)
     return MUX_OK;
 }
 
-// Claims the model's next staging area; waits (rarely: kRing jobs later) for its last copy.
+constexpr int kStampStride = 16;   // ints between the stamps of two areas (a cache line of their own)
+
+int32_t *stamp_word(const ModelRun &m, size_t area_ints, int area)
+{
+    return m.stage_host + static_cast<size_t>(kRing) * area_ints + static_cast<size_t>(area) * kStampStride;
+}
+
+// Claims the model's next staging area; waits (rarely: kRing jobs later) until the staging kernel
+// of the area's last job has read it (that kernel's stamp in pinned memory says so).
 int claim_area(ModelRun &m, size_t area_ints, int32_t **host, int32_t **dev, int *area)
 {
     const int a = m.next_area;
     m.next_area = (a + 1) % kRing;
-    if (m.in_flight[a] && !ok(hipEventSynchronize(m.copied[a]))) return MUX_ERR_HIP;
-    m.in_flight[a] = false;
+    if (m.stamp_of[a] != 0) {
+        const int32_t *word = stamp_word(m, area_ints, a);
+        long spins = 0;
+        while (__atomic_load_n(word, __ATOMIC_ACQUIRE) != m.stamp_of[a]) {
+            // the kernel is at most kRing jobs behind: this wait ends as soon as the stream gets there; the
+            // runtime is asked now and then so that a failed stream ends the wait with an error
+            if (++spins % 4096 == 0 && hipStreamQuery(m.stream) != hipErrorNotReady) {
+                if (__atomic_load_n(word, __ATOMIC_ACQUIRE) == m.stamp_of[a]) break;
+                (void)hipGetLastError();
+                return MUX_ERR_HIP;
+            }
+        }
+    }
     *host = m.stage_host + static_cast<size_t>(a) * area_ints;
     *dev = m.stage_dev + static_cast<size_t>(a) * area_ints;
     *area = a;
     return MUX_OK;
 }
 
-int send_area(ModelRun &m, int area, const int32_t *host, int32_t *dev, size_t n_ints)
+// Hands the filled area to the GPU: its first copy_ints ints go to the device twin, its entries
+// (n_entries of them from entries_at, their ids from ids_at) into the tables.
+int stage_and_install(mux_runner *r, ModelRun &m, int area, const int32_t *host, int32_t *dev, size_t copy_ints, int n_entries,
+                      size_t entries_at, size_t ids_at, bool prefill)
 {
-    if (!ok(hipMemcpyAsync(dev, host, n_ints * sizeof(int32_t), hipMemcpyHostToDevice, m.stream))) return MUX_ERR_HIP;
-    if (!ok(hipEventRecord(m.copied[area], m.stream))) return MUX_ERR_HIP;
-    m.in_flight[area] = true;
-    return MUX_OK;
-}
-
-int install(ModelRun &m, const int32_t *entries_dev, const int32_t *ids_dev, int n_entries, bool prefill, int max_seqs, int max_blocks)
-{
-    if (n_entries == 0) return MUX_OK;
-    hipLaunchKernelGGL(install_blocks_kernel, dim3(static_cast<unsigned>(n_entries)), dim3(256), 0, m.stream, entries_dev, ids_dev,
-                       m.tables, prefill ? m.job_tables : nullptr, m.heads, m.hkv, max_seqs, max_blocks);
+    const int32_t stamp = m.next_stamp;
+    m.next_stamp = stamp == 0x7fffffff ? 1 : stamp + 1;
+    m.stamp_of[area] = stamp;
+    const unsigned copy_wgs = static_cast<unsigned>(std::min<size_t>((copy_ints + 1023) / 1024, 64));
+    const unsigned grid = static_cast<unsigned>(n_entries) + std::max(copy_wgs, n_entries == 0 ? 1u : 0u);
+    const int32_t *host_as_gpu = m.stage_host_dev + (host - m.stage_host);
+    int32_t *stamp_as_gpu = m.stage_host_dev + (stamp_word(m, r->area_ints, area) - m.stage_host);
+    hipLaunchKernelGGL(stage_install_kernel, dim3(grid), dim3(256), 0, m.stream, host_as_gpu, dev, static_cast<int>(copy_ints), n_entries,
+                       static_cast<int>(entries_at), static_cast<int>(ids_at), m.tables, prefill ? m.job_tables : nullptr, m.heads,
+                       m.hkv, r->max_seqs, r->max_blocks, m.arrivals, stamp_as_gpu, stamp);
     return ok(hipGetLastError()) ? MUX_OK : MUX_ERR_HIP;
 }
 
@@ -227,8 +277,12 @@ int mux_runner_create(mux_runner_t **out, mux_pool_t *pool, mux_sched_t *sched, 
         good = good && ok(hipMalloc(&m.decode_ws, m.decode_ws_bytes));
         good = good && (m.prefill_ws_bytes == 0 || ok(hipMalloc(&m.prefill_ws, m.prefill_ws_bytes)));
         good = good && ok(hipMalloc(&m.stage_dev, kRing * r->area_ints * sizeof(int32_t)));
-        good = good && ok(hipHostMalloc(&m.stage_host, kRing * r->area_ints * sizeof(int32_t), hipHostMallocDefault));
-        for (hipEvent_t &e : m.copied) good = good && ok(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        // pinned and mapped: the staging kernel reads the areas, and writes their stamps, in place
+        const size_t stage_ints = kRing * r->area_ints + static_cast<size_t>(kRing) * kStampStride;
+        good = good && ok(hipHostMalloc(&m.stage_host, stage_ints * sizeof(int32_t), hipHostMallocMapped | hipHostMallocPortable));
+        if (good) std::memset(m.stage_host, 0, stage_ints * sizeof(int32_t));
+        good = good && ok(hipHostGetDevicePointer(reinterpret_cast<void **>(&m.stage_host_dev), m.stage_host, 0));
+        good = good && ok(hipMalloc(&m.arrivals, sizeof(int))) && ok(hipMemset(m.arrivals, 0, sizeof(int)));
         good = good && ok(hipEventCreateWithFlags(&m.done, hipEventDisableTiming));
         if (!good) {
             release(r);
@@ -317,12 +371,12 @@ static int prepare_job(mux_runner_t *r, int32_t job, int32_t *model_out)
             for (int32_t h = 0; h < heads; ++h, at += nb) std::memcpy(ids + at, row + static_cast<size_t>(h) * cols, sizeof(int32_t) * nb);
         }
         cu[n] = t;
-        rc = send_area(m, area, host, dev, need);
+        // the per-token arrays and the chunk starts go to device memory, the entries and ids straight into the tables
+        const size_t entries_at = 2 * static_cast<size_t>(total) + 2 * static_cast<size_t>(n) + 1;
+        rc = stage_and_install(r, m, area, host, dev, entries_at, n, entries_at, entries_at + static_cast<size_t>(kEntryInts) * n, true);
         if (rc != MUX_OK) return rc;
         p.seq = dev, p.pos = dev + total, p.cu = dev + 2 * total, p.start = p.cu + n + 1;
         p.total = static_cast<int32_t>(total), p.longest = longest;
-        rc = install(m, p.start + n, p.start + n + kEntryInts * n, n, true, r->max_seqs, cols);
-        if (rc != MUX_OK) return rc;
     } else {
         // arrays: context length per slot (0 = not in this step), up to the highest slot | entries | ids
         int32_t rows = 0, longest = 0, n_entries = 0;
@@ -376,9 +430,8 @@ static int prepare_job(mux_runner_t *r, int32_t job, int32_t *model_out)
                 for (int32_t h = 0; h < heads; ++h) ids[e_at * heads + h] = row[static_cast<size_t>(h) * cols + col];
                 ++e_at;
             }
-            rc = send_area(m, area, host, dev, need);
-            if (rc != MUX_OK) return rc;
-            rc = install(m, dev + rows, dev + rows + kEntryInts * n_entries, n_entries, false, r->max_seqs, cols);
+            rc = stage_and_install(r, m, area, host, dev, rows, n_entries, rows, static_cast<size_t>(rows) + static_cast<size_t>(kEntryInts) * n_entries,
+                                   false);
             if (rc != MUX_OK) return rc;
             p.ctx = dev;
         }
