@@ -25,7 +25,7 @@
  *     contexts by the piece-count rule alone), MUX_PREFILL_BUNDLE=n (row tiles of one
  *     (sequence, head) dispatched back to back on one XCD), MUX_PREFILL_CB=1|2 (16-row
  *     column blocks per wave), MUX_RUNNER_STAGE_ALWAYS=1 (read by mux_runner_create: job
- *     arrays always travel through pinned staging memory).
+ *     arrays always travel through pinned staging memory, never as kernel arguments).
  *   - "HOST" pointers are ordinary process memory, "DEVICE" pointers are HIP device
  *     memory of the GPU that is current when the call is made.
  *   - the caller owns the pool memory, block tables, Q/O tensors and workspaces; the
@@ -345,10 +345,12 @@ MUX_API int mux_sched_counts(const mux_sched_t *sched, int32_t model, int64_t *c
 /* ---------------------------------------------------------------------------------
  * Job runner (Section 3.3, Algorithm 3 `execute`; Section 3.4: the engines fill K/V into the
  * blocks the manager assigned and run attention over them).  It launches the jobs of a
- * scheduler on the GPU: per job ONE host-to-device copy of the job's integer arrays (staged
- * in pinned memory the runner owns), a small kernel that installs the block ids the scheduler
- * just handed out into the runner's device copy of the model's table, then the append and the
- * attention on the model's stream.  Unlike the calls above the runner OWNS device memory
+ * scheduler on the GPU: a decode job's integer arrays (context lengths, new block ids) ride
+ * in the arguments of its one attention launch when they fit; any other job writes them into
+ * pinned memory the runner owns, from where ONE small kernel installs the block ids the
+ * scheduler just handed out into the runner's device copy of the model's table and copies the
+ * per-token arrays to device memory (no host-to-device copy call), then the append and the
+ * attention follow on the model's stream.  Unlike the calls above the runner OWNS device memory
  * (table copies, staging areas, kernel workspaces: allocated in mux_runner_create on the
  * current device, freed in mux_runner_destroy); launches allocate nothing.
  *
