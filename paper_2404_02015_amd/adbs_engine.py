@@ -6,7 +6,7 @@ the library.
 Engine       mirrors the scheduler's block tables to the device itself and calls mux_kv_append,
              mux_prefill_attn and mux_decode_attn for every job (a handful of small copies and
              launches per job from Python).
-NativeEngine hands every job to the library's runner (mux_runner_launch): one staged copy, the
+NativeEngine hands every job to the library's runner (mux_runner_launch): the job's arrays, the
              table update and the kernels are issued from C++.
 
 Used by the tests (with a seeded CPU source mirrored into the oracle) and by bench.py.
